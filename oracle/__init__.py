@@ -1,0 +1,162 @@
+"""ctypes front end of the CPU fp64 oracle (``normtest_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke()``
+and by the ``cpu_baseline`` leg of ``bench.py``.  The GPU library never touches
+it and the two share no code.
+
+Arrays are numpy: gradients as a 2-D array of shape (J, n), dtype float32, or
+uint16 holding bfloat16 bit patterns; the last axis must be contiguous, the
+row stride is free.  State vectors ``w, m, v`` are float32.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "normtest_oracle.c")
+_LIB = os.path.join(_HERE, "libnormtest_oracle.so")
+
+F32, BF16 = 0, 1
+
+NONFINITE = 1
+ZERO_GRAD_NORM = 2
+CLAMPED = 4
+T_SATURATED = 16
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, no fast-math: the compensated sums rely on IEEE order)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.run(
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fno-fast-math", "-ffp-contract=off",
+             "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"],
+            check=True,
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+class _Decision(ctypes.Structure):
+    _fields_ = [
+        ("gbar_sq", ctypes.c_double),
+        ("var_l1", ctypes.c_double),
+        ("T", ctypes.c_double),
+        ("next_b", ctypes.c_int64),
+        ("pass_", ctypes.c_int32),
+        ("status", ctypes.c_uint32),
+    ]
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        i64, dbl, vp = ctypes.c_int64, ctypes.c_double, ctypes.c_void_p
+        lib.nto_stats.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp]
+        lib.nto_stats.restype = ctypes.c_int
+        lib.nto_decide.argtypes = [dbl, dbl, dbl, i64, dbl, i64, i64, i64, ctypes.c_int32,
+                                   ctypes.POINTER(_Decision)]
+        lib.nto_decide.restype = ctypes.c_int
+        lib.nto_adamw.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, dbl, dbl, dbl, dbl, dbl,
+                                  i64, vp, vp, vp, vp]
+        lib.nto_adamw.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _grad_args(G: np.ndarray):
+    if G.ndim != 2:
+        raise ValueError("gradients must be a (J, n) array")
+    if G.dtype == np.float32:
+        dtype = F32
+    elif G.dtype == np.uint16:
+        dtype = BF16
+    else:
+        raise ValueError("gradients must be float32 or uint16 (bfloat16 bits), got %s" % G.dtype)
+    J, n = G.shape
+    isz = G.dtype.itemsize
+    if n > 0 and G.strides[1] != isz:
+        raise ValueError("last axis must be contiguous")
+    if J > 1 and n > 0:
+        if G.strides[0] % isz or G.strides[0] < n * isz:
+            raise ValueError("bad row stride")
+        ld = G.strides[0] // isz
+    else:
+        ld = max(n, 1)
+    return G.ctypes.data, dtype, J, ld, n
+
+
+class StatsAccumulator:
+    """Compensated running sums of A, B, C; feed coordinate ranges in any number of calls."""
+
+    def __init__(self):
+        self.acc = np.zeros(6, dtype=np.float64)
+
+    def add(self, G: np.ndarray) -> "StatsAccumulator":
+        ptr, dtype, J, ld, n = _grad_args(G)
+        if n:
+            rc = _load().nto_stats(ptr, dtype, J, ld, n, self.acc.ctypes.data)
+            if rc:
+                raise ValueError("nto_stats rejected its arguments")
+        return self
+
+    @property
+    def ABC(self):
+        a = self.acc
+        return float(a[0] + a[1]), float(a[2] + a[3]), float(a[4] + a[5])
+
+
+def stats(G: np.ndarray):
+    """(A, B, C) = (sum_j ||g_j||^2, ||sum_j g_j||^2, sum_j ||g_j - gbar||^2)."""
+    return StatsAccumulator().add(G).ABC
+
+
+def combine_chunks(parts):
+    """Exactly rounded sum of per-chunk (A, B, C) triples (used when chunks were evaluated separately)."""
+    return tuple(math.fsum(p[k] for p in parts) for k in range(3))
+
+
+@dataclass
+class Decision:
+    gbar_sq: float
+    var_l1: float
+    T: float
+    next_b: int
+    passed: bool
+    status: int
+
+
+def decide(A, B, C, J, eta, b_k, b_max=0, round_to=1, ddof=1) -> Decision:
+    out = _Decision()
+    rc = _load().nto_decide(A, B, C, J, eta, b_k, b_max, round_to, ddof, ctypes.byref(out))
+    if rc:
+        raise ValueError("nto_decide rejected its arguments")
+    return Decision(out.gbar_sq, out.var_l1, out.T, int(out.next_b), bool(out.pass_), int(out.status))
+
+
+def adamw(G, w, m, v, lr, beta1, beta2, eps, weight_decay, step, want_gbar=False):
+    """One AdamW step on the mean of the rows of G; returns fp64 (w', m', v'[, gbar])."""
+    ptr, dtype, J, ld, n = _grad_args(G)
+    for x in (w, m, v):
+        if x.dtype != np.float32 or x.ndim != 1 or x.shape[0] != n or not x.flags.c_contiguous:
+            raise ValueError("w, m, v must be contiguous float32 vectors of length n")
+    wo, mo, vo = (np.empty(n, dtype=np.float64) for _ in range(3))
+    go = np.empty(n, dtype=np.float64) if want_gbar else None
+    if n:
+        rc = _load().nto_adamw(ptr, dtype, J, ld, n, w.ctypes.data, m.ctypes.data, v.ctypes.data,
+                               lr, beta1, beta2, eps, weight_decay, step,
+                               wo.ctypes.data, mo.ctypes.data, vo.ctypes.data,
+                               go.ctypes.data if want_gbar else None)
+        if rc:
+            raise ValueError("nto_adamw rejected its arguments")
+    return (wo, mo, vo, go) if want_gbar else (wo, mo, vo)

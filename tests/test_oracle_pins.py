@@ -1,0 +1,387 @@
+"""Pins for the CPU oracle: everything here checks ``oracle/`` against facts that do not come from it
+(hand-worked examples, exact rational arithmetic, closed forms, numpy / torch library routines,
+invariants of Alg. 1).  No GPU, no HIP library."""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2412_21124_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "worked_examples.txt")
+
+
+# ---------------------------------------------------------------- helpers
+
+def bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Bit patterns of values that are exactly representable in bfloat16."""
+    u = np.asarray(x, dtype=np.float32).view(np.uint32)
+    assert np.all((u & 0xFFFF) == 0), "value not representable in bfloat16"
+    return (u >> 16).astype(np.uint16)
+
+
+def parse_golden(path):
+    cases, cur = [], None
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        key, *vals = line.split()
+        if key == "case":
+            cur = {"name": vals[0], "g": []}
+            cases.append(cur)
+        elif key == "g":
+            cur["g"].append([float(x) for x in vals])
+        else:
+            cur[key] = vals[0]
+    return cases
+
+
+GOLDEN_CASES = parse_golden(GOLDEN)
+
+
+def exact_stats(rows):
+    """A, B, C, in exact rational arithmetic, from the definitions."""
+    J, d = len(rows), len(rows[0])
+    R = [[Fraction(x) for x in r] for r in rows]
+    A = sum(x * x for r in R for x in r)
+    s = [sum(R[j][i] for j in range(J)) for i in range(d)]
+    B = sum(x * x for x in s)
+    gbar = [x / J for x in s]
+    C = sum((R[j][i] - gbar[i]) ** 2 for j in range(J) for i in range(d))
+    return A, B, C
+
+
+def alg1_rounding(T: Fraction, b_k: int, J: int, M: int) -> int:
+    """Alg. 1's If-branch, line by line, on integers."""
+    if T > b_k:
+        b = math.ceil(T)
+        micro = -(-b // (J * M))
+        minibatch = M * micro
+        return J * minibatch
+    return b_k
+
+
+# ---------------------------------------------------------------- hand-worked examples
+
+@pytest.mark.parametrize("case", [c for c in GOLDEN_CASES if "expect_A" in c], ids=lambda c: c["name"])
+@pytest.mark.parametrize("as_bf16", [False, True])
+def test_golden_statistic(case, as_bf16):
+    G = np.array(case["g"], dtype=np.float32)
+    Gin = bf16_bits(G) if as_bf16 else G
+    A, B, C = oracle.stats(Gin)
+    J = G.shape[0]
+    assert A == float(case["expect_A"])
+    assert B == float(case["expect_B"])
+    assert C == pytest.approx(float(case["expect_C"]), rel=1e-15)
+    dec = oracle.decide(A, B, C, J, float(case["eta"]), int(case["b_k"]), int(case["b_max"]),
+                        int(case["round_to"]), int(case["ddof"]))
+    assert dec.gbar_sq == pytest.approx(float(case["expect_gbar_sq"]), rel=1e-15)
+    assert dec.var_l1 == pytest.approx(float(case["expect_var_l1"]), rel=1e-15)
+    assert dec.T == pytest.approx(float(case["expect_T"]), rel=1e-14)
+    assert dec.passed == bool(int(case["expect_pass"]))
+    assert dec.next_b == int(case["expect_next_b"])
+
+
+@pytest.mark.parametrize("case", [c for c in GOLDEN_CASES if "expect_w" in c], ids=lambda c: c["name"])
+def test_golden_adamw(case):
+    G = np.array(case["g"], dtype=np.float32)
+    w, m, v = (np.array([float(case[k])], dtype=np.float32) for k in ("w", "m", "v"))
+    wo, mo, vo = oracle.adamw(G, w, m, v, float(case["lr"]), float(case["beta1"]), float(case["beta2"]),
+                              float(case["eps"]), float(case["weight_decay"]), int(case["step"]))
+    tol = float(case.get("tol", 1e-14))
+    assert wo[0] == pytest.approx(float(case["expect_w"]), rel=tol, abs=tol * 0.1)
+    assert mo[0] == pytest.approx(float(case["expect_m"]), rel=tol)
+    assert vo[0] == pytest.approx(float(case["expect_v"]), rel=tol)
+
+
+# ---------------------------------------------------------------- brute force, exact rationals
+
+@pytest.mark.parametrize("J", [2, 3, 4, 5, 8])
+@pytest.mark.parametrize("d", [1, 3, 16])
+@pytest.mark.parametrize("as_bf16", [False, True])
+def test_brute_force_exact_rational(J, d, as_bf16):
+    rng = np.random.default_rng(1000 * J + 10 * d + as_bf16)
+    for trial in range(8):
+        # multiples of 1/16 with at most 8 significant bits: exact in bfloat16, fp32 and fp64
+        G = rng.integers(-40, 41, size=(J, d)).astype(np.float32) / 16.0
+        if trial == 0:
+            G[:] = G[0]  # identical rows
+        Gin = bf16_bits(G) if as_bf16 else G
+        Ae, Be, Ce = exact_stats(G.tolist())
+        A, B, C = oracle.stats(Gin)
+        assert A == float(Ae) and B == float(Be)           # sums of dyadic rationals: exact
+        assert C == pytest.approx(float(Ce), rel=1e-14, abs=1e-300)
+        if J & (J - 1) == 0:
+            assert C == float(Ce)                           # s/J is exact when J is a power of two
+        assert Ce == Ae - Be / J                            # the identity, exactly
+        for ddof in (0, 1):
+            for eta, M, b_k in ((Fraction(1, 2), 1, 1), (Fraction(1, 4), 2, 7), (Fraction(1, 8), 16, 300)):
+                dec = oracle.decide(A, B, C, J, float(eta), b_k, 0, J * M, ddof)
+                if Be == 0:
+                    assert dec.status & oracle.ZERO_GRAD_NORM
+                    continue
+                Te = (Ce / (J - ddof)) / (eta * eta * Be / (J * J))
+                assert dec.T == pytest.approx(float(Te), rel=1e-14, abs=1e-300)
+                # an exact T on (or within rounding of) an integer or b_k is decided by the last bit of the
+                # fp64 quotient: only asserted when every step is exact (J and J - ddof powers of two)
+                near = min(abs(Te - b_k), abs(Te - round(Te))) < Fraction(1, 10**9) * max(Te, 1)
+                exact_steps = J & (J - 1) == 0 and (J - ddof) & (J - ddof - 1) == 0
+                if near and not exact_steps:
+                    continue
+                assert dec.passed == (not Te > b_k)
+                assert dec.next_b == alg1_rounding(Te, b_k, J, M)
+
+
+# ---------------------------------------------------------------- identity, zero variance, ddof
+
+@pytest.mark.parametrize("J", [2, 3, 4, 7, 8, 16])
+@pytest.mark.parametrize("gdtype", [torch.float32, torch.bfloat16])
+def test_identity_C_equals_A_minus_B_over_J(J, gdtype):
+    wl = synth.make("t", J, 5003, gdtype=gdtype, sigma=1e-2, seed=J, with_state=False)
+    A, B, C = oracle.stats(synth.grads_as_numpy(wl.grads))
+    assert C == pytest.approx(A - B / J, rel=1e-12 * A / C)
+    assert 0 < C < A
+
+
+@pytest.mark.parametrize("J", [2, 3, 4, 8])
+def test_zero_variance_when_rows_identical(J):
+    wl = synth.make("t", J, 4099, gdtype=torch.bfloat16, sigma=1e-2, seed=3, with_state=False)
+    wl.grads[:] = wl.grads[0].clone()
+    G = synth.grads_as_numpy(wl.grads)
+    A, B, C = oracle.stats(G)
+    g0 = wl.grads[0].double().numpy()
+    n2 = math.fsum((g0 * g0).tolist())
+    if J & (J - 1) == 0:
+        assert C == 0.0
+    else:
+        assert C <= 1e-30 * A
+    dec = oracle.decide(A, B, 0.0, J, 0.1, 32, 8192, 4, 1)
+    assert dec.gbar_sq == pytest.approx(n2, rel=1e-14)
+    assert A == pytest.approx(J * n2, rel=1e-14)
+    assert dec.T == 0.0 and dec.passed and dec.next_b == 32 and dec.status == 0
+
+
+def test_ddof_relation():
+    wl = synth.make("t", 5, 3001, sigma=3e-2, seed=5, with_state=False)
+    A, B, C = oracle.stats(synth.grads_as_numpy(wl.grads))
+    d0 = oracle.decide(A, B, C, 5, 0.1, 32, 0, 1, 0)
+    d1 = oracle.decide(A, B, C, 5, 0.1, 32, 0, 1, 1)
+    assert d0.var_l1 * 5 == pytest.approx(C, rel=1e-15)
+    assert d1.var_l1 * 4 == pytest.approx(C, rel=1e-15)
+    assert d0.T == pytest.approx(d1.T * 4 / 5, rel=1e-14)
+
+
+# ---------------------------------------------------------------- Gaussian closed forms
+
+@pytest.mark.parametrize("sigma,expect_pass", [(1e-3, True), (1e-2, False)])
+def test_gaussian_closed_form_tiny(sigma, expect_pass):
+    wl = synth.tiny(sigma)
+    J, d, mu2 = wl.J, wl.d, 1e-4
+    A, B, C = oracle.stats(synth.grads_as_numpy(wl.grads))
+    # C ~ sigma^2 chi^2 with (J-1) d degrees of freedom
+    assert C == pytest.approx((J - 1) * sigma**2 * d, rel=5 * math.sqrt(2 / ((J - 1) * d)))
+    # gbar_i ~ N(0, mu2 + sigma^2/J) i.i.d.
+    tau2 = mu2 + sigma**2 / J
+    assert B / J**2 == pytest.approx(tau2 * d, rel=5 * math.sqrt(2 / d))
+    # E A = J d (mu2 + sigma^2); its spread is dominated by the shared mu
+    assert A == pytest.approx(J * d * (mu2 + sigma**2), rel=8 * math.sqrt(2 / d))
+    h = wl.hyper
+    dec = oracle.decide(A, B, C, J, h.eta, h.b_k, h.b_max, h.round_to, h.ddof)
+    r2 = sigma**2 / mu2
+    T_formula = r2 / (h.eta**2 * (1 + r2 / J))
+    assert dec.T == pytest.approx(T_formula, rel=2e-2)
+    assert dec.passed == expect_pass
+    if not expect_pass:
+        assert dec.next_b == h.round_to * math.ceil(math.ceil(dec.T) / h.round_to)
+
+
+@pytest.mark.parametrize("ratio", [0.3, 1.0, 3.0, 10.0])
+def test_block_scales_cancel_in_T(ratio):
+    """g = s_l (mu + sigma eps) with |mu| fixed: T depends on sigma/|mu| only, T -> J/eta^2 for large ratios."""
+    sizes = synth.scaled_blocks(synth.gpt2_small_blocks(), 1 << 20)
+    wl = synth.gpt2_small(ratio, block_sizes=sizes, seed=1)
+    J = wl.J
+    Gt = wl.grads.float()
+    A, B, C = oracle.stats(synth.grads_as_numpy(wl.grads))
+    h = wl.hyper
+    dec = oracle.decide(A, B, C, J, h.eta, h.b_k, h.b_max, h.round_to, h.ddof)
+    r2 = ratio**2
+    T_formula = r2 / (h.eta**2 * (1 + r2 / J))
+    # the two largest blocks carry the sums, so the effective sample is smaller than d; bf16 rounding adds ~2^-9 noise
+    assert dec.T == pytest.approx(T_formula, rel=3e-2)
+    assert dec.T < J / h.eta**2
+    assert dec.passed == (T_formula <= h.b_k)
+    assert Gt.abs().max() < 1.0
+
+
+# ---------------------------------------------------------------- library cross-checks
+
+@pytest.mark.parametrize("J,ddof", [(4, 0), (4, 1), (7, 1), (16, 0)])
+def test_matches_numpy_column_variance(J, ddof):
+    wl = synth.make("t", J, 2053, gdtype=torch.bfloat16, sigma=2e-2, seed=11, with_state=False)
+    G = synth.grads_as_numpy(wl.grads)
+    G64 = wl.grads.double().numpy()
+    A, B, C = oracle.stats(G)
+    dec = oracle.decide(A, B, C, J, 0.1, 32, 0, 1, ddof)
+    assert dec.var_l1 == pytest.approx(np.var(G64, axis=0, ddof=ddof).sum(), rel=1e-12)
+    assert dec.gbar_sq == pytest.approx(float(np.linalg.norm(G64.mean(axis=0)) ** 2), rel=1e-12)
+    assert A == pytest.approx(float(np.linalg.norm(G64) ** 2), rel=1e-12)
+
+
+def test_matches_library_adamw_over_steps():
+    """Five consecutive steps against torch.optim.AdamW in fp64, starting from m = v = 0 (Alg. 1 Require line)."""
+    d, J = 257, 4
+    hp = dict(lr=4e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    rng = np.random.default_rng(7)
+    w = (0.02 * rng.standard_normal(d)).astype(np.float32)
+    m = np.zeros(d, np.float32)
+    v = np.zeros(d, np.float32)
+    for step in range(1, 6):
+        G = (1e-2 * rng.standard_normal((J, d))).astype(np.float32)
+        wo, mo, vo = oracle.adamw(G, w, m, v, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"],
+                                  hp["weight_decay"], step)
+        p = torch.nn.Parameter(torch.from_numpy(w).double())
+        opt = torch.optim.AdamW([p], lr=hp["lr"], betas=(hp["beta1"], hp["beta2"]), eps=hp["eps"],
+                                weight_decay=hp["weight_decay"], amsgrad=False)
+        opt.state[p] = {"step": torch.tensor(float(step - 1)),
+                        "exp_avg": torch.from_numpy(m).double(),
+                        "exp_avg_sq": torch.from_numpy(v).double()}
+        p.grad = torch.from_numpy(G.astype(np.float64).mean(axis=0))
+        opt.step()
+        np.testing.assert_allclose(wo, p.detach().numpy(), rtol=1e-12, atol=1e-18)
+        np.testing.assert_allclose(mo, opt.state[p]["exp_avg"].numpy(), rtol=1e-12, atol=1e-300)
+        np.testing.assert_allclose(vo, opt.state[p]["exp_avg_sq"].numpy(), rtol=1e-12, atol=1e-300)
+        w, m, v = wo.astype(np.float32), mo.astype(np.float32), vo.astype(np.float32)
+
+
+def test_adamw_first_step_is_a_sign_step():
+    """m = v = 0, k = 1: mhat = gbar, vhat = gbar^2, so w' = (1 - lr wd) w - lr gbar / (|gbar| + eps)."""
+    d, J = 1031, 8
+    wl = synth.make("t", J, d, gdtype=torch.bfloat16, sigma=1e-2, seed=2)
+    G = synth.grads_as_numpy(wl.grads)
+    w = wl.w.numpy()
+    z = np.zeros(d, np.float32)
+    lr, b1, b2, eps, wd = 1e-3, 0.9, 0.95, 1e-8, 0.1
+    wo, mo, vo, gbar = oracle.adamw(G, w, z, z, lr, b1, b2, eps, wd, 1, want_gbar=True)
+    gb = wl.grads.double().numpy().mean(axis=0)
+    np.testing.assert_allclose(gbar, gb, rtol=1e-14)
+    np.testing.assert_allclose(mo, (1 - b1) * gb, rtol=1e-13)
+    np.testing.assert_allclose(vo, (1 - b2) * gb * gb, rtol=1e-13)
+    np.testing.assert_allclose(wo, (1 - lr * wd) * w.astype(np.float64) - lr * gb / (np.abs(gb) + eps),
+                               rtol=1e-11, atol=1e-16)
+
+
+# ---------------------------------------------------------------- invariants of the statistic
+
+def test_scale_row_permutation_and_shard_additivity():
+    J, d = 6, 4001
+    wl = synth.make("t", J, d, sigma=2e-2, seed=9, with_state=False)
+    G = synth.grads_as_numpy(wl.grads)
+    A, B, C = oracle.stats(G)
+    T = oracle.decide(A, B, C, J, 0.1, 1, 0, 1, 1).T
+    # power-of-two scaling is exact, so T is bit-identical; any other positive scale moves it by rounding only
+    A2, B2, C2 = oracle.stats(G * np.float32(4.0))
+    assert (A2, B2, C2) == (16 * A, 16 * B, 16 * C)
+    assert oracle.decide(A2, B2, C2, J, 0.1, 1, 0, 1, 1).T == T
+    G64 = G.astype(np.float64) * 3.0
+    A3 = float((G64 * G64).sum())
+    assert A3 == pytest.approx(9 * A, rel=1e-12)
+    # permuting the workers
+    perm = np.random.default_rng(0).permutation(J)
+    Ap, Bp, Cp = oracle.stats(np.ascontiguousarray(G[perm]))
+    assert (Ap, Bp, Cp) == pytest.approx((A, B, C), rel=1e-13)
+    # shards: contiguous coordinate ranges add up, through the running accumulator and through separate sums
+    cuts = [0, 17, 1000, 1001, 3000, d]
+    acc = oracle.StatsAccumulator()
+    parts = []
+    for lo, hi in zip(cuts[:-1], cuts[1:]):
+        acc.add(G[:, lo:hi])
+        parts.append(oracle.stats(G[:, lo:hi]))
+    assert acc.ABC == pytest.approx((A, B, C), rel=1e-14)
+    assert oracle.combine_chunks(parts) == pytest.approx((A, B, C), rel=1e-14)
+
+
+def test_row_stride_is_honoured():
+    wl = synth.make("t", 3, 100, sigma=1e-2, seed=4, with_state=False, ld=128)
+    wl.grads[:, 100:] = 7.0  # padding must never be read
+    G = synth.grads_as_numpy(wl.grads)[:, :100]
+    assert G.strides[0] == 128 * 4
+    assert oracle.stats(G) == oracle.stats(np.ascontiguousarray(G))
+
+
+# ---------------------------------------------------------------- decision rules
+
+def _abc_for_T(T, J=4, eta=0.5, ddof=0):
+    """(A, B, C) with ||gbar||^2 = 1 whose statistic is T (exact when T*eta^2*(J-ddof) is representable)."""
+    B = float(J * J)
+    C = T * eta * eta * (J - ddof)
+    return B / J + C, B, C
+
+
+def test_equality_passes_and_strict_excess_grows():
+    b_k = 48
+    A, B, C = _abc_for_T(float(b_k))
+    dec = oracle.decide(A, B, C, 4, 0.5, b_k, 0, 1, 0)
+    assert dec.T == b_k and dec.passed and dec.next_b == b_k
+    Cup = math.nextafter(C, math.inf)
+    dec = oracle.decide(A, B, Cup, 4, 0.5, b_k, 0, 1, 0)
+    assert dec.T > b_k and not dec.passed and dec.next_b == b_k + 1
+
+
+@pytest.mark.parametrize("J,M", [(4, 16), (8, 16), (4, 1), (3, 5), (1, 1)])
+def test_rounding_chain_against_alg1_lines(J, M):
+    rng = np.random.default_rng(J * 100 + M)
+    b_k = 256
+    for T in list(rng.uniform(1, 20000, size=200)) + [256.0, 257.0, 256.000001, 8191.5, 8192.0, 8193.0]:
+        Jd = max(J, 2)
+        A, B, C = _abc_for_T(T, J=Jd, eta=0.5, ddof=0)
+        dec = oracle.decide(A, B, C, Jd, 0.5, b_k, 0, J * M, 0)
+        expect = alg1_rounding(Fraction(dec.T), b_k, J, M)
+        assert dec.next_b == expect
+        assert dec.next_b >= b_k                       # Alg. 1 never shrinks the batch
+        if not dec.passed:
+            assert dec.next_b % (J * M) == 0 and dec.next_b >= math.ceil(dec.T)
+        capped = oracle.decide(A, B, C, Jd, 0.5, b_k, 8192, J * M, 0)
+        assert capped.next_b == max(b_k, min(expect, 8192))
+        assert bool(capped.status & oracle.CLAMPED) == (expect > 8192)
+
+
+def test_degenerate_inputs():
+    # zero gradient norm with spread: cannot pass, jump to the cap
+    dec = oracle.decide(2.0, 0.0, 2.0, 2, 0.1, 32, 8192, 4, 1)
+    assert not dec.passed and dec.next_b == 8192 and dec.status & oracle.ZERO_GRAD_NORM and math.isinf(dec.T)
+    dec = oracle.decide(2.0, 0.0, 2.0, 2, 0.1, 32, 0, 4, 1)
+    assert not dec.passed and dec.next_b == 32
+    # all-zero gradients: nothing to test
+    dec = oracle.decide(0.0, 0.0, 0.0, 2, 0.1, 32, 8192, 4, 1)
+    assert dec.passed and dec.next_b == 32 and dec.status & oracle.ZERO_GRAD_NORM
+    # NaN / Inf anywhere: do not grow
+    for bad in (math.nan, math.inf):
+        dec = oracle.decide(bad, 1.0, 1.0, 2, 0.1, 32, 8192, 4, 1)
+        assert dec.passed and dec.next_b == 32 and dec.status & oracle.NONFINITE
+    # a statistic too large for an integer batch size
+    dec = oracle.decide(1e300, 1e-300, 1e300, 2, 0.1, 32, 8192, 4, 1)
+    assert not dec.passed and dec.next_b == 8192 and dec.status & oracle.T_SATURATED
+    # NaN gradients reach the sums
+    G = np.array([[1.0, np.nan], [2.0, 3.0]], dtype=np.float32)
+    A, B, C = oracle.stats(G)
+    assert math.isnan(A) and math.isnan(B) and math.isnan(C)
+    # the cap never pulls the batch size below the current one
+    A, B, C = _abc_for_T(5000.0)
+    dec = oracle.decide(A, B, C, 4, 0.5, 4096, 2048, 1, 0)
+    assert dec.next_b == 4096
+
+
+def test_argument_checks():
+    with pytest.raises(ValueError):
+        oracle.decide(1, 1, 1, 1, 0.1, 32, 0, 1, 1)      # J - ddof = 0
+    with pytest.raises(ValueError):
+        oracle.decide(1, 1, 1, 2, 0.0, 32, 0, 1, 1)      # eta must be positive
+    with pytest.raises(ValueError):
+        oracle.stats(np.zeros((2, 3), dtype=np.float64))
+    assert oracle.stats(np.zeros((2, 0), dtype=np.float32)) == (0.0, 0.0, 0.0)
