@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused norm-test + AdamW step on one MI355X.
+
+A "step" is one pass of the whole hot path (statistics, decision, fused AdamW: `normtest_step`) over
+the headline workload: J=8 bfloat16 gradient rows of a flat d=1.5e9 vector with fp32 w, m, v, all
+resident in HBM before the timed region.  Prints one JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload flat_1p5b|gpt2_small|fsdp_shard|per_sample|tiny]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+# HBM bytes per step from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/), scaled by the
+# copy-kernel calibration; None until measured for that workload.
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/k_step_flat_1p5b.md: FETCH_SIZE x 2.0000 + WRITE_SIZE x 1.0000 per k_step launch
+    "flat_1p5b": 6.0016e10,
+}
+
+
+def make_workload(name: str, device: str, scale: float):
+    from paper_2412_21124_amd import synth
+    if name == "flat_1p5b":
+        return synth.flat_1p5b(d=int(1_500_000_000 * scale), device=device)
+    if name == "gpt2_small":
+        sizes = synth.gpt2_small_blocks()
+        if scale != 1.0:
+            sizes = synth.scaled_blocks(sizes, int(sum(sizes) * scale), 8)
+        return synth.gpt2_small(1.0, block_sizes=sizes, device=device)
+    if name == "fsdp_shard":
+        return synth.fsdp_shard(3, d_shard=int(875_000_000 * scale), device=device)
+    if name == "per_sample":
+        return synth.per_sample(d=max(64, int((1 << 24) * scale) // 64 * 64), device=device)
+    if name == "tiny":
+        return synth.tiny(1e-2, device=device)
+    raise SystemExit("unknown workload %r" % name)
+
+
+def cpu_baseline(wl, sample_coords: int):
+    """The oracle, as it stands, on the host cores over the first `sample_coords` coordinates."""
+    import numpy as np
+    import oracle
+    from concurrent.futures import ThreadPoolExecutor
+    from paper_2412_21124_amd import synth
+
+    n = min(wl.d, sample_coords)
+    threads = max(1, min(16, os.cpu_count() or 1))
+    chunk = 1 << 22
+    h = wl.hyper
+    G = synth.grads_as_numpy(wl.grads, 0, n)
+    w, m, v = (t[:n].cpu().numpy() for t in (wl.w, wl.m, wl.v))
+    ranges = [(lo, min(n, lo + chunk)) for lo in range(0, n, chunk)]
+
+    def work(r):
+        lo, hi = r
+        part = oracle.stats(G[:, lo:hi])
+        oracle.adamw(G[:, lo:hi], w[lo:hi], m[lo:hi], v[lo:hi], h.lr, h.beta1, h.beta2, h.eps,
+                     h.weight_decay, h.step)
+        return part
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(threads) as ex:
+        parts = list(ex.map(work, ranges))
+    A, Bv, C = oracle.combine_chunks(parts)
+    oracle.decide(A, Bv, C, wl.J, h.eta, h.b_k, h.b_max, h.round_to, h.ddof)
+    dt = time.perf_counter() - t0
+    bytes_per_param = wl.J * wl.grad_bytes + 24
+    return {
+        "value": n * bytes_per_param / dt / 1e9,
+        "unit": "GB/s",
+        "params_per_s": n / dt,
+        "cores": min(threads, len(ranges)),
+        "kind": "oracle",
+        "seconds": dt,
+        "sample": "first %d coordinates of the same workload (J=%d), statistics + decision + AdamW in fp64" % (n, wl.J),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="flat_1p5b")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink d (debugging only; the result is then not the headline)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 28)
+    ap.add_argument("--calib-copy-gib", type=int, default=0,
+                    help="also run the library's plain copy kernel once on this many GiB (known traffic for scaling byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import torch
+    from paper_2412_21124_amd import binding as B
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU: the library has no CPU path")
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wl = make_workload(args.workload, dev, args.scale)
+    h = wl.hyper
+    flags = B.NT_DO_STATS | B.NT_DO_ADAMW | (B.NT_PARTIAL if args.workload == "fsdp_shard" else 0)
+    hy = B.make_hyper(lr=h.lr, beta1=h.beta1, beta2=h.beta2, eps=h.eps, weight_decay=h.weight_decay, eta=h.eta,
+                      step=h.step, b_k=h.b_k, b_max=h.b_max, round_to=h.round_to, ddof=h.ddof, flags=flags)
+    workspace = torch.empty(B.normtest_workspace_bytes(wl.J, wl.d), dtype=torch.uint8, device=dev)
+    result = torch.empty(B.RESULT_BYTES, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hy, workspace=workspace, result=result, stream=stream)
+
+    if args.calib_copy_gib > 0:
+        src = torch.zeros(args.calib_copy_gib << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        B.normtest_calib_copy(dst, src, stream=stream)
+        torch.cuda.synchronize()
+        del src, dst
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        starts[i].record(stream)
+        step()
+        stops[i].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev_ms = [s.elapsed_time(e) for s, e in zip(starts, stops)]
+    res = B.read_result(result).as_dict()
+
+    alg_bytes = wl.algorithmic_bytes()
+    ms_per_step = wall * 1e3 / args.steps
+    ev_avg = sum(ev_ms) / len(ev_ms)
+    value = alg_bytes / (wall / args.steps) / 1e9
+    achieved = alg_bytes / (ev_avg * 1e-3) / 1e9
+    out = {
+        "metric": "norm-test+AdamW step: achieved HBM GB/s (% of peak), params/s at d=1.5B J=8",
+        "value": value,
+        "unit": "GB/s",
+        "pct_of_peak": 100.0 * value / HBM_PEAK_GBS,
+        "params_per_s": wl.d / (wall / args.steps),
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": "%s: J=%d %s gradient rows, d=%d, fp32 w/m/v, stats+decision+fused AdamW in one pass" % (
+                wl.name, wl.J, "bf16" if wl.grad_bytes == 2 else "fp32", wl.d),
+            "J": wl.J, "d": wl.d, "grad_dtype": "bf16" if wl.grad_bytes == 2 else "f32",
+            "bytes_per_param": wl.J * wl.grad_bytes + 24, "flags": flags,
+        },
+        "result": {k: res[k] for k in ("T", "pass", "next_b", "status")},
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "k_step (the fused streaming kernel; the HIP events bracket the whole step, i.e. also the two reduction kernels, about 15 us)",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "launch_ms_avg": ev_avg,
+            "launch_ms_min": min(ev_ms),
+            "algorithmic_bytes": alg_bytes,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if args.scale == 1.0 else None,
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

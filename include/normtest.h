@@ -1,0 +1,145 @@
+/*
+ * normtest.h -- C ABI of libnormtest.so: the per-step statistics pass of the norm-test adaptive
+ * batch-size schedules (DDP-Norm / FSDP-Norm) fused with the AdamW update, for one MI355X (gfx950).
+ *
+ * Given J gradient vectors g_1..g_J of length d (the workers' minibatch gradients of Sec. 3.2, the
+ * micro-batch gradients of a parameter shard of Sec. 3.3, or per-sample gradients of Sec. 3.1), one
+ * streaming pass over HBM computes
+ *
+ *     gbar = (1/J) sum_j g_j                                   (Sec. 3.2; Alg. 1 "batch gradient")
+ *     A = sum_j ||g_j||^2,  B = ||sum_j g_j||^2,  C = sum_j ||g_j - gbar||^2
+ *     ||gbar||^2 = B/J^2,   ||Var||_1 = C/(J - ddof)           (variance estimator of Sec. 3.2 / Alg. 1)
+ *     T = ||Var||_1 / (eta^2 ||gbar||^2)                       (Alg. 1, test statistic)
+ *     pass = !(T > b_k), next_b by Alg. 1's rounding chain     (Alg. 1, If-branch)
+ *     AdamW on gbar, in place on w, m, v                       (Alg. 1, last five update lines)
+ *
+ * All pointers named "device" must be dereferenceable by the GPU (device memory; result may also be
+ * pinned host memory).  The library allocates nothing, keeps no state between calls, never
+ * synchronises the device and never touches host copies of the data: it validates, enqueues kernels
+ * on the caller's stream and returns.  No C++ types or exceptions cross this boundary.
+ */
+#ifndef NORMTEST_H
+#define NORMTEST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* element type of the gradient rows */
+typedef enum { NT_F32 = 0, NT_BF16 = 1 } nt_dtype;
+
+/* nt_hyper.flags */
+enum {
+  NT_DO_STATS = 1u,   /* compute A, B, C (and, unless NT_PARTIAL, the test)                      */
+  NT_DO_ADAMW = 2u,   /* update w, m, v in place with AdamW on gbar                              */
+  NT_PARTIAL = 4u,    /* FSDP shard: stop at the additive sums A, B, C; decide in normtest_combine */
+  NT_WRITE_GBAR = 8u  /* also store gbar (fp32[d]) to gbar_out                                   */
+};
+
+/* nt_result.status bits */
+enum {
+  NT_STATUS_NONFINITE = 1u,      /* a sum is NaN/Inf (NaN/Inf gradient, or |g| beyond ~1.8e19): batch size kept  */
+  NT_STATUS_ZERO_GRAD_NORM = 2u, /* ||gbar||^2 == 0: T is NaN (C == 0, passes) or +inf (fails, goes to the cap)  */
+  NT_STATUS_CLAMPED = 4u,        /* the rounded batch size exceeded b_max and was cut to it                      */
+  NT_STATUS_PARTIAL_ONLY = 8u,   /* NT_PARTIAL: only A, B, C (and their low parts) are meaningful                */
+  NT_STATUS_T_SATURATED = 16u,   /* T >= 2^62: treated as infinite                                               */
+  NT_STATUS_NO_STATS = 32u       /* NT_DO_STATS was clear: sums are NaN, pass = 1, next_b = b_k                  */
+};
+
+/* return codes; values <= NT_ERR_HIP_BASE carry a HIP error: code = NT_ERR_HIP_BASE - hipError_t */
+enum {
+  NT_OK = 0,
+  NT_ERR_BAD_ARG = -1,
+  NT_ERR_UNSUPPORTED = -2,
+  NT_ERR_WORKSPACE_TOO_SMALL = -3,
+  NT_ERR_HIP_BASE = -1000
+};
+
+/*
+ * Scalars of one step.  AdamW symbols as in Alg. 1's Require line; eta, b_k and the rounding as in
+ * Alg. 1's test; b_max as in Sec. 5 ("maximum global batch size").
+ */
+typedef struct {
+  double lr, beta1, beta2, eps, weight_decay; /* alpha >= 0, 0 <= beta < 1, epsilon >= 0, lambda >= 0          */
+  double eta;                                 /* eta > 0                                                       */
+  int64_t step;                               /* k >= 1, used for the bias corrections 1 - beta^k              */
+  int64_t b_k;                                /* current global batch size, >= 1                               */
+  int64_t b_max;                              /* cap on next_b, 0 = none; never pulls next_b below b_k         */
+  int64_t round_to;                           /* J*M (workers x accumulation steps): next_b is a multiple;     */
+                                              /* 1 = the plain ceiling rule of Sec. 3.1                        */
+  int32_t ddof;                               /* 0: variance / J (Alg. 1);  1: / (J-1) (sample variance)       */
+  uint32_t flags;                             /* NT_DO_* | NT_PARTIAL | NT_WRITE_GBAR                          */
+} nt_hyper;
+
+/* Where this call's coordinates sit in the full parameter vector (Sec. 3.3).  Informational: the sums
+ * are additive over coordinates, so a shard needs nothing from the others. */
+typedef struct {
+  int32_t shard_id, num_shards;
+  int64_t shard_offset, d_global;
+} nt_shard_info;
+
+typedef struct {
+  double A, B, C;          /* sum_j||g_j||^2, ||sum_j g_j||^2, sum_j||g_j - gbar||^2 over this call's coordinates  */
+  double A_lo, B_lo, C_lo; /* low-order parts: each sum is X + X_lo to ~1e-30 relative, so shards add up exactly   */
+  double gbar_sq;          /* ||gbar||^2 = B/J^2                         (NaN if NT_PARTIAL or no stats)           */
+  double var_l1;           /* C/(J - ddof)                                                                        */
+  double T;                /* var_l1 / (eta^2 gbar_sq)                                                            */
+  int64_t next_b;          /* b_{k+1}                                                                             */
+  int32_t pass;            /* 1 iff not (T > b_k)                                                                 */
+  uint32_t status;         /* NT_STATUS_* bits                                                                    */
+} nt_result;
+
+/* Number of coordinates per partial-sum tile for J rows.  Results are bit-identical for any split of
+ * a vector into calls whose boundaries are multiples of this (same J, dtype and alignment class). */
+int64_t normtest_tile_coords(int64_t J);
+
+/* Bytes of device workspace normtest_step needs for J rows of d coordinates (0 if J or d is invalid). */
+size_t normtest_workspace_bytes(int64_t J, int64_t d);
+
+/*
+ * One step.  Row j of the gradients starts at element j*ld of `grads` (device; ld >= d; elements of
+ * type gdtype).  w, m, v: device fp32[d], updated in place when NT_DO_ADAMW (may be NULL otherwise).
+ * gbar_out: device fp32[d], written when NT_WRITE_GBAR, else ignored.  hyper, shard: host pointers,
+ * read before returning (shard may be NULL).  workspace: device scratch of at least
+ * normtest_workspace_bytes(J, d) bytes, 8-byte aligned, contents irrelevant before and after.
+ * result_dev: device or pinned-host nt_result, 8-byte aligned, written by the last kernel.
+ * hip_stream: a hipStream_t (NULL = the default stream).
+ *
+ * Everything is enqueued on the stream; the result and the updated state are valid once the caller
+ * has synchronised it.  Any pointer alignment is accepted: rows, w, m, v (and gbar_out) that are not
+ * all 16-byte aligned take a slower path with bit-identical results.  d == 0 succeeds (sums are 0).
+ * AdamW is fused into the same pass: it has been applied even if status reports NONFINITE.
+ * Returns NT_OK or a negative code; on any error nothing was enqueued and no buffer was touched,
+ * except that a failing launch (HIP code returned) may follow launches that already succeeded.
+ */
+int normtest_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld,
+                  float* w, float* m, float* v, float* gbar_out,
+                  const nt_hyper* hyper, const nt_shard_info* shard,
+                  void* workspace, size_t workspace_bytes,
+                  nt_result* result_dev, void* hip_stream);
+
+/*
+ * Host-side combination of n per-shard partial results (all host memory), Sec. 3.3 / Appendix A:
+ * gradients of the shards are concatenated, so A, B, C add.  Sums (with their low parts) are added in
+ * shard order in double-double arithmetic, then the same decision as in normtest_step is taken in
+ * fp64 with `hyper` (eta, b_k, b_max, round_to, ddof; flags ignored).  Status bits of the parts are
+ * OR-ed (minus PARTIAL_ONLY).  Returns NT_OK or NT_ERR_BAD_ARG.
+ */
+int normtest_combine(const nt_result* partials, int32_t n, int64_t J, const nt_hyper* hyper,
+                     nt_result* out);
+
+/* Plain streaming copy of `bytes` bytes (device to device, 16-byte aligned, bytes % 16 == 0) with the
+ * same load/store instructions as the step kernel: a yardstick for achievable HBM bandwidth and for
+ * scaling hardware byte counters.  Enqueued on the stream. */
+int normtest_calib_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
+
+/* Static, human-readable text for a return code. */
+const char* normtest_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NORMTEST_H */

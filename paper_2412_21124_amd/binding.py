@@ -1,0 +1,191 @@
+"""ctypes binding of ``libnormtest.so`` (``include/normtest.h``): argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels.  torch supplies device memory and the
+current stream, nothing else.  There is no CPU fallback: if the library cannot be loaded or a call
+fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+from . import build as _build
+
+NT_F32, NT_BF16 = 0, 1
+NT_DO_STATS, NT_DO_ADAMW, NT_PARTIAL, NT_WRITE_GBAR = 1, 2, 4, 8
+NT_STATUS_NONFINITE = 1
+NT_STATUS_ZERO_GRAD_NORM = 2
+NT_STATUS_CLAMPED = 4
+NT_STATUS_PARTIAL_ONLY = 8
+NT_STATUS_T_SATURATED = 16
+NT_STATUS_NO_STATS = 32
+NT_OK, NT_ERR_BAD_ARG, NT_ERR_UNSUPPORTED, NT_ERR_WORKSPACE_TOO_SMALL, NT_ERR_HIP_BASE = 0, -1, -2, -3, -1000
+
+
+class nt_hyper(ctypes.Structure):
+    _fields_ = [
+        ("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
+        ("eps", ctypes.c_double), ("weight_decay", ctypes.c_double), ("eta", ctypes.c_double),
+        ("step", ctypes.c_int64), ("b_k", ctypes.c_int64), ("b_max", ctypes.c_int64),
+        ("round_to", ctypes.c_int64), ("ddof", ctypes.c_int32), ("flags", ctypes.c_uint32),
+    ]
+
+
+class nt_shard_info(ctypes.Structure):
+    _fields_ = [
+        ("shard_id", ctypes.c_int32), ("num_shards", ctypes.c_int32),
+        ("shard_offset", ctypes.c_int64), ("d_global", ctypes.c_int64),
+    ]
+
+
+class nt_result(ctypes.Structure):
+    _fields_ = [
+        ("A", ctypes.c_double), ("B", ctypes.c_double), ("C", ctypes.c_double),
+        ("A_lo", ctypes.c_double), ("B_lo", ctypes.c_double), ("C_lo", ctypes.c_double),
+        ("gbar_sq", ctypes.c_double), ("var_l1", ctypes.c_double), ("T", ctypes.c_double),
+        ("next_b", ctypes.c_int64), ("pass_", ctypes.c_int32), ("status", ctypes.c_uint32),
+    ]
+
+    def as_dict(self) -> dict:
+        d = {k: getattr(self, k) for k, _ in self._fields_}
+        d["pass"] = d.pop("pass_")
+        return d
+
+
+RESULT_BYTES = ctypes.sizeof(nt_result)
+
+
+class NormtestError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__("%s failed with code %d: %s" % (where, code, normtest_strerror(code)))
+
+
+_lib = None
+
+
+def lib(path: Optional[str] = None):
+    """The loaded C-ABI library (built on first use if missing).  `path` loads another build of it."""
+    global _lib
+    if _lib is None or path is not None:
+        L = ctypes.CDLL(path if path is not None else _build.ensure_built())
+        vp, i64 = ctypes.c_void_p, ctypes.c_int64
+        L.normtest_tile_coords.argtypes = [i64]
+        L.normtest_tile_coords.restype = i64
+        L.normtest_workspace_bytes.argtypes = [i64, i64]
+        L.normtest_workspace_bytes.restype = ctypes.c_size_t
+        L.normtest_step.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp,
+                                    ctypes.POINTER(nt_hyper), ctypes.POINTER(nt_shard_info),
+                                    vp, ctypes.c_size_t, vp, vp]
+        L.normtest_step.restype = ctypes.c_int
+        L.normtest_combine.argtypes = [ctypes.POINTER(nt_result), ctypes.c_int32, i64,
+                                       ctypes.POINTER(nt_hyper), ctypes.POINTER(nt_result)]
+        L.normtest_combine.restype = ctypes.c_int
+        L.normtest_calib_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.normtest_calib_copy.restype = ctypes.c_int
+        L.normtest_strerror.argtypes = [ctypes.c_int]
+        L.normtest_strerror.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def normtest_strerror(code: int) -> str:
+    return lib().normtest_strerror(code).decode()
+
+
+def normtest_tile_coords(J: int) -> int:
+    return int(lib().normtest_tile_coords(J))
+
+
+def normtest_workspace_bytes(J: int, d: int) -> int:
+    return int(lib().normtest_workspace_bytes(J, d))
+
+
+def make_hyper(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, eta=0.1, step=1, b_k=1,
+               b_max=0, round_to=1, ddof=1, flags=NT_DO_STATS | NT_DO_ADAMW) -> nt_hyper:
+    return nt_hyper(lr, beta1, beta2, eps, weight_decay, eta, step, b_k, b_max, round_to, ddof, flags)
+
+
+def _gdtype(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return NT_F32
+    if t.dtype == torch.bfloat16:
+        return NT_BF16
+    raise TypeError("gradients must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def normtest_step(grads: torch.Tensor, w: Optional[torch.Tensor], m: Optional[torch.Tensor],
+                  v: Optional[torch.Tensor], hyper: nt_hyper, *, d: Optional[int] = None,
+                  shard: Optional[nt_shard_info] = None, gbar_out: Optional[torch.Tensor] = None,
+                  workspace: Optional[torch.Tensor] = None, result: Optional[torch.Tensor] = None,
+                  stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Enqueue one step on `stream` (default: torch's current stream) and return the device tensor
+    (uint8[sizeof(nt_result)]) that will hold the nt_result; read it with `read_result` after a sync.
+
+    grads: (J, ld) device tensor whose rows are the gradient vectors (last axis contiguous); the first
+    d columns are used (default: all).  w, m, v: float32 device vectors of length >= d, updated in place.
+    """
+    if grads.dim() != 2 or (grads.shape[1] > 1 and grads.stride(1) != 1):
+        raise ValueError("grads must be (J, ld) with a contiguous last axis")
+    J = grads.shape[0]
+    ld = grads.stride(0) if J > 1 else grads.shape[1]
+    d = grads.shape[1] if d is None else d
+    dev = grads.device
+    if dev.type != "cuda":
+        raise ValueError("normtest_step needs device tensors; there is no CPU path")
+    for name, t in (("w", w), ("m", m), ("v", v), ("gbar_out", gbar_out)):
+        if t is not None:
+            if t.dtype != torch.float32 or t.device != dev or not t.is_contiguous() or t.numel() < d:
+                raise ValueError("%s must be a contiguous float32 tensor of >= d elements on %s" % (name, dev))
+    need = normtest_workspace_bytes(J, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=dev)
+    if result is None:
+        result = torch.empty(RESULT_BYTES, dtype=torch.uint8, device=dev)
+    if stream is None:
+        stream = torch.cuda.current_stream(dev)
+    with torch.cuda.device(dev):
+        rc = lib().normtest_step(_ptr(grads), _gdtype(grads), J, d, ld, _ptr(w), _ptr(m), _ptr(v),
+                                 _ptr(gbar_out), ctypes.byref(hyper),
+                                 ctypes.byref(shard) if shard is not None else None,
+                                 _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                 _ptr(result), ctypes.c_void_p(stream.cuda_stream))
+    if rc != NT_OK:
+        raise NormtestError(rc, "normtest_step")
+    # keep the scratch alive until the stream has consumed it
+    workspace.record_stream(stream)
+    return result
+
+
+def read_result(result: torch.Tensor) -> nt_result:
+    """Synchronising read of the device nt_result."""
+    host = result.cpu().numpy().tobytes()
+    return nt_result.from_buffer_copy(host)
+
+
+def normtest_combine(partials, J: int, hyper: nt_hyper) -> nt_result:
+    arr = (nt_result * len(partials))(*partials)
+    out = nt_result()
+    rc = lib().normtest_combine(arr, len(partials), J, ctypes.byref(hyper), ctypes.byref(out))
+    if rc != NT_OK:
+        raise NormtestError(rc, "normtest_combine")
+    return out
+
+
+def normtest_calib_copy(dst: torch.Tensor, src: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() < nbytes:
+        raise ValueError("dst smaller than src")
+    if stream is None:
+        stream = torch.cuda.current_stream(src.device)
+    with torch.cuda.device(src.device):
+        rc = lib().normtest_calib_copy(_ptr(dst), _ptr(src), nbytes, ctypes.c_void_p(stream.cuda_stream))
+    if rc != NT_OK:
+        raise NormtestError(rc, "normtest_calib_copy")

@@ -1,0 +1,972 @@
+// libnormtest: norm-test statistics pass fused with AdamW, hand-written for gfx950 (MI355X).
+//
+// One streaming kernel reads the J gradient rows and w, m, v once, writes w, m, v once and leaves
+// three fp64 partial sums per fixed-size tile of coordinates; a one-block kernel then adds the tile
+// partials in double-double arithmetic and takes Alg. 1's decision.  The path is bound by HBM
+// bandwidth (about one flop per byte), so there is no MFMA here: the work is 128-bit coalesced
+// loads, fp32 per-coordinate arithmetic, fp64 accumulation and wave64 shuffle reductions.
+//
+// Numerics.  The centred sum C = sum_j (g_j - gbar)^2 is formed directly from the J values of a
+// coordinate held in registers, never as A - B/J (which cancels badly when the workers agree).  A
+// rounding error e in gbar only adds J e^2 to a coordinate's centred sum because the cross term
+// sums to zero.  For more than 16 rows the rows are taken 16 at a time and the chunks' means and
+// centred sums are merged with the pairwise update  M2 += M2_b + delta^2 n_a n_b / (n_a + n_b).
+// Per-lane sums leave fp32 after one group of 4 or 8 coordinates; everything above is fp64 in a
+// fixed order, so results do not depend on the grid size and are reproducible bit for bit.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+
+#include "normtest.h"
+
+#ifndef NT_BLOCK
+#define NT_BLOCK 1024         // threads per block of the streaming kernel
+#endif
+#ifndef NT_ITERS_SMALL
+#define NT_ITERS_SMALL 1      // block sweeps per partial-sum tile, J <= 16
+#endif
+#ifndef NT_ITERS_LARGE
+#define NT_ITERS_LARGE 1      // block sweeps per tile, J > 16 (rows are walked inside each sweep)
+#endif
+#ifndef NT_BLOCKS_PER_CU
+#define NT_BLOCKS_PER_CU 4096 // grid = min(tiles, CUs * this); blocks stride over tiles beyond that
+#endif
+#ifndef NT_NT_GRAD
+#define NT_NT_GRAD 1          // nontemporal hint on gradient loads
+#endif
+#ifndef NT_NT_STATE
+#define NT_NT_STATE 1         // nontemporal hint on w, m, v loads
+#endif
+#ifndef NT_NT_STORE
+#define NT_NT_STORE 1         // nontemporal hint on stores
+#endif
+#ifndef NT_NT_COPY
+#define NT_NT_COPY 1          // nontemporal hint in the calibration copy kernel
+#endif
+#ifndef NT_REUNPACK
+#define NT_REUNPACK 0         // 1: make the compiler widen the packed rows again in the second pass
+#endif
+#ifndef NT_UNROLL
+#define NT_UNROLL 1           // unroll factor of the per-tile sweep loop
+#endif
+#ifndef NT_WAVES_PER_EU
+#define NT_WAVES_PER_EU 1     // occupancy the register allocator must leave room for (waves per SIMD)
+#endif
+
+#define NT_VEC 4              // coordinates per lane and sweep: 16-byte fp32 accesses, 8-byte bf16 row loads
+#define NT_TILE_SMALL (NT_BLOCK * NT_VEC * NT_ITERS_SMALL)
+#define NT_TILE_LARGE (NT_BLOCK * NT_VEC * NT_ITERS_LARGE)
+
+#define NT_PRAGMA_(x) _Pragma(#x)
+#define NT_PRAGMA_UNROLL(n) NT_PRAGMA_(unroll n)
+
+#define NT_JCHUNK 16          // rows held in registers at once
+#define NT_FIN_THREADS 1024
+#define NT_GROUP_THREADS 256   // first-stage reduction: threads per block
+#define NT_GROUP_TILES 2048    // ... and tile partials per block
+#define NT_DIRECT_TILES 4096   // up to this many tiles the finalize kernel reads the tile partials itself
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+enum { MODE_FULL = 0, MODE_STATS = 1, MODE_ADAMW = 2 };
+
+template <bool NT, class T>
+__device__ inline T ld_vec(const void* p) {
+  if constexpr (NT)
+    return __builtin_nontemporal_load((const T*)p);
+  else
+    return *(const T*)p;
+}
+
+struct F32 {
+  static constexpr int VEC = 4;
+  static constexpr int ESIZE = 4;
+  typedef u32x4 raw_t;
+  __device__ static inline raw_t ldraw(const void* p) { return ld_vec<NT_NT_GRAD, raw_t>(p); }
+  __device__ static inline float val(const raw_t& r, int e) { return __builtin_bit_cast(float, (uint32_t)r[e]); }
+  __device__ static inline float ld(const void* base, int64_t i) { return ((const float*)base)[i]; }
+};
+
+struct BF16 {
+  static constexpr int VEC = 4;
+  static constexpr int ESIZE = 2;
+  typedef u32x2 raw_t;
+  __device__ static inline raw_t ldraw(const void* p) { return ld_vec<NT_NT_GRAD, raw_t>(p); }
+  // bfloat16 is the high half of a binary32: widening is a shift or a mask
+  __device__ static inline float val(const raw_t& r, int e) {
+    uint32_t u = r[e >> 1];
+    return __builtin_bit_cast(float, (e & 1) ? (u & 0xffff0000u) : (u << 16));
+  }
+  __device__ static inline float ld(const void* base, int64_t i) {
+    return __builtin_bit_cast(float, (uint32_t)((const uint16_t*)base)[i] << 16);
+  }
+};
+
+// opaque to the optimiser: the packed words may have "changed", so values widened from them before
+// this point cannot be kept alive across it
+template <class R>
+__device__ inline void forget(R& r) {
+#if NT_REUNPACK
+  if constexpr (sizeof(R) == 16) {
+    uint32_t a = r[0], b = r[1], c = r[2], d = r[3];
+    asm volatile("" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+    r[0] = a; r[1] = b; r[2] = c; r[3] = d;
+  } else {
+    uint32_t a = r[0], b = r[1];
+    asm volatile("" : "+v"(a), "+v"(b));
+    r[0] = a; r[1] = b;
+  }
+#else
+  (void)r;
+#endif
+}
+
+struct StepParams {
+  const void* grads;
+  int64_t ld;       // row stride in elements
+  int64_t d;
+  int J;
+  float* w;
+  float* m;
+  float* v;
+  float* gbar;      // nullptr unless requested
+  double* partials; // 3 doubles per tile
+  double inv_J;
+  float beta1, omb1, beta2, omb2; // omb = 1 - beta
+  float decay;                    // 1 - lr * weight_decay
+  float step_size;                // lr / (1 - beta1^k)
+  float inv_sqrt_bc2;             // 1 / sqrt(1 - beta2^k)
+  float eps;
+};
+
+__device__ inline u32x4 ld16(const void* p) { return ld_vec<NT_NT_STATE, u32x4>(p); }
+__device__ inline void st16(void* p, f32x4 x) {
+#if NT_NT_STORE
+  __builtin_nontemporal_store(x, (f32x4*)p);
+#else
+  *(f32x4*)p = x;
+#endif
+}
+
+// AdamW on one coordinate (Alg. 1): moments, bias corrections folded into step_size and
+// inv_sqrt_bc2, decoupled decay.  sqrt and reciprocal are the 1-ulp hardware forms: the term they
+// feed is scaled by lr before it meets w.
+__device__ inline void adamw_coord(const StepParams& p, float g, float& w, float& m, float& v) {
+  m = __builtin_fmaf(p.beta1, m, p.omb1 * g);
+  v = __builtin_fmaf(p.beta2, v, (p.omb2 * g) * g);
+  float denom = __builtin_fmaf(__builtin_amdgcn_sqrtf(v), p.inv_sqrt_bc2, p.eps);
+  float upd = (p.step_size * m) * __builtin_amdgcn_rcpf(denom);
+  w = __builtin_fmaf(p.decay, w, -upd);
+}
+
+template <int VEC>
+__device__ inline float lane_tree(const float* x) {
+  if constexpr (VEC == 8)
+    return ((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7]));
+  else
+    return (x[0] + x[1]) + (x[2] + x[3]);
+}
+
+__device__ inline double wave_sum(double x) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
+  return x;
+}
+
+// Block partial of one tile -> partials[3*tile ..].  `buf` alternates between tiles so that one
+// barrier per tile is enough.
+__device__ inline void tile_reduce(double a, double b, double c, double (*red)[NT_BLOCK / 64][3], int buf,
+                                   double* partials, int64_t tile) {
+  a = wave_sum(a);
+  b = wave_sum(b);
+  c = wave_sum(c);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) {
+    red[buf][wave][0] = a;
+    red[buf][wave][1] = b;
+    red[buf][wave][2] = c;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double sa = red[buf][0][0], sb = red[buf][0][1], sc = red[buf][0][2];
+#pragma unroll
+    for (int wv = 1; wv < NT_BLOCK / 64; ++wv) {
+      sa += red[buf][wv][0];
+      sb += red[buf][wv][1];
+      sc += red[buf][wv][2];
+    }
+    partials[3 * tile + 0] = sa;
+    partials[3 * tile + 1] = sb;
+    partials[3 * tile + 2] = sc;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Guarded tile: any J, any alignment, ragged end.  Same lane-to-coordinate map and the same
+// sequence of floating-point operations per coordinate as the fast tiles below (rows are re-read
+// instead of held in registers), so a tile's partial sums and outputs have the same bits on either
+// path.  Coordinates at or beyond d contribute exact zeros.
+// ---------------------------------------------------------------------------------------------
+template <class GT>
+__device__ inline void coord_stats_generic(const StepParams& p, int64_t i, double& S, float& M2, float& a) {
+  const void* grads = p.grads;
+  const int64_t ld = p.ld;
+  const int J = p.J;
+  a = 0.f;
+  int na = 0;
+  for (int j0 = 0; j0 < J; j0 += NT_JCHUNK) {
+    const int nb = (J - j0 < NT_JCHUNK) ? (J - j0) : NT_JCHUNK;
+    double sb = (double)GT::ld(grads, (int64_t)j0 * ld + i);
+    for (int j = 1; j < nb; ++j) sb += (double)GT::ld(grads, (int64_t)(j0 + j) * ld + i);
+    // a single chunk is centred on the overall mean, exactly as in the fast tile
+    const float mb = (J <= NT_JCHUNK) ? (float)(sb * p.inv_J) : (float)(sb * (1.0 / (double)nb));
+    float cb = 0.f;
+    for (int j = 0; j < nb; ++j) {
+      const float x = GT::ld(grads, (int64_t)(j0 + j) * ld + i);
+      const float r = x - mb;
+      cb = __builtin_fmaf(r, r, cb);
+      a = __builtin_fmaf(x, x, a);
+    }
+    if (na == 0) {
+      S = sb;
+      M2 = cb;
+    } else {
+      const float coef = ((float)na * (float)nb) / (float)(na + nb);
+      const float delta = mb - (float)(S * (1.0 / (double)na));
+      M2 = M2 + __builtin_fmaf(delta * delta, coef, cb);
+      S = S + sb;
+    }
+    na += nb;
+  }
+}
+
+template <class GT, int MODE>
+__device__ inline void guarded_tile(const StepParams& p, int64_t tile, int tile_coords, double (*red)[NT_BLOCK / 64][3],
+                                    int buf) {
+  constexpr int VEC = GT::VEC;
+  const int iters = tile_coords / (NT_BLOCK * VEC);
+  double accA = 0.0, accB = 0.0, accC = 0.0;
+  for (int it = 0; it < iters; ++it) {
+    const int64_t i0 = tile * (int64_t)tile_coords + ((int64_t)it * NT_BLOCK + threadIdx.x) * VEC;
+    float a[VEC], b[VEC], c[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const int64_t i = i0 + e;
+      a[e] = b[e] = c[e] = 0.f;
+      if (i < p.d) {
+        double S;
+        float M2, aa;
+        coord_stats_generic<GT>(p, i, S, M2, aa);
+        const float gb = (float)(S * p.inv_J);
+        const float sf = (float)S;
+        a[e] = aa;
+        b[e] = sf * sf;
+        c[e] = M2;
+        if constexpr (MODE != MODE_STATS) {
+          float w = p.w[i], m = p.m[i], v = p.v[i];
+          adamw_coord(p, gb, w, m, v);
+          p.w[i] = w;
+          p.m[i] = m;
+          p.v[i] = v;
+        }
+        if (p.gbar) p.gbar[i] = gb;
+      }
+    }
+    if constexpr (MODE != MODE_ADAMW) {
+      accA += (double)lane_tree<VEC>(a);
+      accB += (double)lane_tree<VEC>(b);
+      accC += (double)lane_tree<VEC>(c);
+    }
+  }
+  if constexpr (MODE != MODE_ADAMW) tile_reduce(accA, accB, accC, red, buf, p.partials, tile);
+}
+
+// AdamW on VEC coordinates whose state was loaded as 16-byte vectors, then the 16-byte stores.
+template <int VEC>
+__device__ inline void adamw_store(const StepParams& p, int64_t i0, const float* gb, const u32x4* sw, const u32x4* sm,
+                                   const u32x4* sv) {
+#pragma unroll
+  for (int q = 0; q < VEC / 4; ++q) {
+    f32x4 ow, om, ov;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float w = __builtin_bit_cast(float, (uint32_t)sw[q][e]);
+      float m = __builtin_bit_cast(float, (uint32_t)sm[q][e]);
+      float v = __builtin_bit_cast(float, (uint32_t)sv[q][e]);
+      adamw_coord(p, gb[4 * q + e], w, m, v);
+      ow[e] = w;
+      om[e] = m;
+      ov[e] = v;
+    }
+    st16(p.w + i0 + 4 * q, ow);
+    st16(p.m + i0 + 4 * q, om);
+    st16(p.v + i0 + 4 * q, ov);
+  }
+}
+
+template <int VEC>
+__device__ inline void gbar_store(const StepParams& p, int64_t i0, const float* gb) {
+#pragma unroll
+  for (int q = 0; q < VEC / 4; ++q) {
+    f32x4 og = {gb[4 * q], gb[4 * q + 1], gb[4 * q + 2], gb[4 * q + 3]};
+    st16(p.gbar + i0 + 4 * q, og);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Fast tile, J <= 16 known at compile time: all J rows of a group of VEC coordinates sit in
+// registers; needs 16-byte aligned rows and state and a tile that lies wholly below d.
+// The row sum is carried in fp64 so that the mean is correctly rounded even when the rows cancel.
+// ---------------------------------------------------------------------------------------------
+template <class GT, int J, int MODE, int TILE>
+__device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red)[NT_BLOCK / 64][3], int buf) {
+  constexpr int VEC = GT::VEC;
+  constexpr int ITERS = TILE / (NT_BLOCK * VEC);
+  static_assert(TILE % (NT_BLOCK * VEC) == 0, "tile must be a whole number of block sweeps");
+  const char* gbase = (const char*)p.grads;
+  const int64_t row_bytes = p.ld * GT::ESIZE;
+  double accA = 0.0, accB = 0.0, accC = 0.0;
+  NT_PRAGMA_UNROLL(NT_UNROLL)
+  for (int it = 0; it < ITERS; ++it) {
+    const int64_t i0 = tile * TILE + ((int64_t)it * NT_BLOCK + threadIdx.x) * VEC;
+    typename GT::raw_t raw[J];
+#pragma unroll
+    for (int j = 0; j < J; ++j) raw[j] = GT::ldraw(gbase + j * row_bytes + i0 * GT::ESIZE);
+    u32x4 sw[VEC / 4], sm[VEC / 4], sv[VEC / 4];
+    if constexpr (MODE != MODE_STATS) {
+#pragma unroll
+      for (int q = 0; q < VEC / 4; ++q) {
+        sw[q] = ld16(p.w + i0 + 4 * q);
+        sm[q] = ld16(p.m + i0 + 4 * q);
+        sv[q] = ld16(p.v + i0 + 4 * q);
+      }
+    }
+    double s[VEC];
+    float gb[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) s[e] = (double)GT::val(raw[0], e);
+#pragma unroll
+    for (int j = 1; j < J; ++j)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) s[e] += (double)GT::val(raw[j], e);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) gb[e] = (float)(s[e] * p.inv_J);
+
+    if constexpr (MODE != MODE_ADAMW) {
+      float a[VEC], c[VEC], b[VEC];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) a[e] = c[e] = 0.f;
+#pragma unroll
+      for (int j = 0; j < J; ++j) forget(raw[j]);
+#pragma unroll
+      for (int j = 0; j < J; ++j)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          const float x = GT::val(raw[j], e);
+          const float r = x - gb[e];
+          c[e] = __builtin_fmaf(r, r, c[e]);
+          a[e] = __builtin_fmaf(x, x, a[e]);
+        }
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        const float sf = (float)s[e];
+        b[e] = sf * sf;
+      }
+      accA += (double)lane_tree<VEC>(a);
+      accB += (double)lane_tree<VEC>(b);
+      accC += (double)lane_tree<VEC>(c);
+    }
+    if constexpr (MODE != MODE_STATS) adamw_store<VEC>(p, i0, gb, sw, sm, sv);
+    if (p.gbar) gbar_store<VEC>(p, i0, gb);
+  }
+  if constexpr (MODE != MODE_ADAMW) tile_reduce(accA, accB, accC, red, buf, p.partials, tile);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Fast tile, J > 16: rows are walked NT_JCHUNK at a time; per coordinate the running sum S (fp64),
+// the running centred sum M2 and the sum of squares a are carried and chunks are merged pairwise.
+// nb is the number of rows in this chunk (compile-time NB when RT is false), na the rows before it.
+// ---------------------------------------------------------------------------------------------
+template <class GT, bool FIRST, bool RT>
+__device__ inline void chunk_update(typename GT::raw_t* raw, int nb, int na, double* S, float* M2, float* a) {
+  constexpr int VEC = GT::VEC;
+  double sb[VEC];
+  float mb[VEC], cb[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) sb[e] = (double)GT::val(raw[0], e);
+#pragma unroll
+  for (int j = 1; j < NT_JCHUNK; ++j)
+    if (!RT || j < nb) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) sb[e] += (double)GT::val(raw[j], e);
+    }
+  const double inv_nb = 1.0 / (double)nb;
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) {
+    mb[e] = (float)(sb[e] * inv_nb);
+    cb[e] = 0.f;
+  }
+#pragma unroll
+  for (int j = 0; j < NT_JCHUNK; ++j)
+    if (!RT || j < nb) forget(raw[j]);
+#pragma unroll
+  for (int j = 0; j < NT_JCHUNK; ++j)
+    if (!RT || j < nb) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        const float x = GT::val(raw[j], e);
+        const float r = x - mb[e];
+        cb[e] = __builtin_fmaf(r, r, cb[e]);
+        a[e] = __builtin_fmaf(x, x, a[e]);
+      }
+    }
+  if constexpr (FIRST) {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      S[e] = sb[e];
+      M2[e] = cb[e];
+    }
+  } else {
+    const float coef = ((float)na * (float)nb) / (float)(na + nb);
+    const double inv_na = 1.0 / (double)na;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const float delta = mb[e] - (float)(S[e] * inv_na);
+      M2[e] = M2[e] + __builtin_fmaf(delta * delta, coef, cb[e]);
+      S[e] = S[e] + sb[e];
+    }
+  }
+}
+
+template <class GT, int MODE, int TILE>
+__device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double (*red)[NT_BLOCK / 64][3], int buf) {
+  constexpr int VEC = GT::VEC;
+  constexpr int ITERS = TILE / (NT_BLOCK * VEC);
+  static_assert(TILE % (NT_BLOCK * VEC) == 0, "tile must be a whole number of block sweeps");
+  const char* gbase = (const char*)p.grads;
+  const int64_t row_bytes = p.ld * GT::ESIZE;
+  const int J = p.J;
+  double accA = 0.0, accB = 0.0, accC = 0.0;
+#pragma unroll 1
+  for (int it = 0; it < ITERS; ++it) {
+    const int64_t i0 = tile * TILE + ((int64_t)it * NT_BLOCK + threadIdx.x) * VEC;
+    const char* gp = gbase + i0 * GT::ESIZE;
+    double S[VEC];
+    float M2[VEC], a[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) a[e] = 0.f;
+    typename GT::raw_t raw[NT_JCHUNK];
+    // first chunk (J > NT_JCHUNK here, so it is full)
+#pragma unroll
+    for (int j = 0; j < NT_JCHUNK; ++j) raw[j] = GT::ldraw(gp + j * row_bytes);
+    chunk_update<GT, true, false>(raw, NT_JCHUNK, 0, S, M2, a);
+    int j0 = NT_JCHUNK;
+#pragma unroll 1
+    for (; j0 + NT_JCHUNK <= J; j0 += NT_JCHUNK) {
+      const char* cp = gp + (int64_t)j0 * row_bytes;
+#pragma unroll
+      for (int j = 0; j < NT_JCHUNK; ++j) raw[j] = GT::ldraw(cp + j * row_bytes);
+      chunk_update<GT, false, false>(raw, NT_JCHUNK, j0, S, M2, a);
+    }
+    if (j0 < J) {
+      const int nb = J - j0;
+      const char* cp = gp + (int64_t)j0 * row_bytes;
+#pragma unroll
+      for (int j = 0; j < NT_JCHUNK; ++j)
+        if (j < nb) raw[j] = GT::ldraw(cp + j * row_bytes);
+      chunk_update<GT, false, true>(raw, nb, j0, S, M2, a);
+    }
+    float gb[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) gb[e] = (float)(S[e] * p.inv_J);
+
+    if constexpr (MODE != MODE_ADAMW) {
+      float b[VEC];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        const float sf = (float)S[e];
+        b[e] = sf * sf;
+      }
+      accA += (double)lane_tree<VEC>(a);
+      accB += (double)lane_tree<VEC>(b);
+      accC += (double)lane_tree<VEC>(M2);
+    }
+    if constexpr (MODE != MODE_STATS) {
+      u32x4 sw[VEC / 4], sm[VEC / 4], sv[VEC / 4];
+#pragma unroll
+      for (int q = 0; q < VEC / 4; ++q) {
+        sw[q] = ld16(p.w + i0 + 4 * q);
+        sm[q] = ld16(p.m + i0 + 4 * q);
+        sv[q] = ld16(p.v + i0 + 4 * q);
+      }
+      adamw_store<VEC>(p, i0, gb, sw, sm, sv);
+    }
+    if (p.gbar) gbar_store<VEC>(p, i0, gb);
+  }
+  if constexpr (MODE != MODE_ADAMW) tile_reduce(accA, accB, accC, red, buf, p.partials, tile);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Kernels.  Block b takes tiles b, b + gridDim.x, ...; tiles below nfull are whole and aligned (fast
+// path), the others go through the guarded path.  When the vector ends in a ragged tile, block 0
+// takes it first so that the slow tile overlaps with everything else.
+// J_T = 0 selects the J > 16 row-walking variant.
+// ---------------------------------------------------------------------------------------------
+template <class GT, int J_T, int MODE, int TILE>
+__global__ __launch_bounds__(NT_BLOCK, NT_WAVES_PER_EU) void k_step(StepParams p, int64_t nfull, int64_t ntiles) {
+  __shared__ double red[2][NT_BLOCK / 64][3];
+  int buf = 0;
+  const int64_t nrest = ntiles - nfull;  // guarded tiles (0 or 1 on the aligned path)
+  for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    // rotate: the first nrest slots are the guarded tiles nfull.., then the fast tiles 0..nfull-1
+    const int64_t tile = (t < nrest) ? nfull + t : t - nrest;
+    if (tile < nfull) {
+      if constexpr (J_T > 0)
+        fast_tile<GT, J_T, MODE, TILE>(p, tile, red, buf);
+      else
+        fast_tile_multi<GT, MODE, TILE>(p, tile, red, buf);
+    } else {
+      guarded_tile<GT, MODE>(p, tile, TILE, red, buf);
+    }
+    buf ^= 1;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Double-double helpers (error-free transformations; the file is compiled with contraction off).
+// ---------------------------------------------------------------------------------------------
+struct dd {
+  double hi, lo;
+};
+__host__ __device__ inline dd dd_add(dd x, dd y) {
+  double s = x.hi + y.hi;
+  double bb = s - x.hi;
+  double e = (x.hi - (s - bb)) + (y.hi - bb);
+  e += x.lo + y.lo;
+  dd r;
+  r.hi = s + e;
+  r.lo = e - (r.hi - s);
+  return r;
+}
+
+struct DecideParams {
+  int64_t J;
+  double eta;
+  int64_t b_k, b_max, round_to;
+  int32_t ddof;
+  uint32_t flags;
+};
+
+// From the sums in r->A, r->B, r->C to ||gbar||^2, ||Var||_1, T, pass and next_b (Alg. 1: test
+// statistic, strict comparison with b_k, ceiling, rounding through micro-batch, minibatch and
+// global batch, which composes to the next multiple of J*M; Sec. 5: cap at the maximum batch size).
+__host__ __device__ inline void decide(const DecideParams& q, nt_result* r) {
+  const double Jd = (double)q.J;
+  const int64_t cap = (q.b_max > q.b_k) ? q.b_max : q.b_k;
+  r->pass = 1;
+  r->next_b = q.b_k;
+  r->gbar_sq = r->B / (Jd * Jd);
+  r->var_l1 = r->C / (double)(q.J - q.ddof);
+  if (!(__builtin_isfinite(r->A) && __builtin_isfinite(r->B) && __builtin_isfinite(r->C))) {
+    r->status |= NT_STATUS_NONFINITE;
+    r->T = __builtin_nan("");
+    return;
+  }
+  if (r->gbar_sq == 0.0) {
+    r->status |= NT_STATUS_ZERO_GRAD_NORM;
+    if (r->C == 0.0) {
+      r->T = __builtin_nan("");
+    } else {
+      r->T = __builtin_inf();
+      r->pass = 0;
+      r->next_b = cap;
+    }
+    return;
+  }
+  const double T = r->var_l1 / (q.eta * q.eta * r->gbar_sq);
+  r->T = T;
+  if (T > (double)q.b_k) {
+    r->pass = 0;
+    if (!(T < 4611686018427387904.0)) {
+      r->status |= NT_STATUS_T_SATURATED;
+      r->next_b = cap;
+      return;
+    }
+    const int64_t t = (int64_t)ceil(T);
+    int64_t nb = ((t + q.round_to - 1) / q.round_to) * q.round_to;
+    if (q.b_max > 0 && nb > q.b_max) {
+      nb = q.b_max;
+      r->status |= NT_STATUS_CLAMPED;
+    }
+    r->next_b = nb < q.b_k ? q.b_k : nb;
+  }
+}
+
+__device__ inline dd dd_wave_sum(dd x) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    dd y;
+    y.hi = __shfl_xor(x.hi, off, 64);
+    y.lo = __shfl_xor(x.lo, off, 64);
+    // both partners must form the same sum: order the operands by lane
+    const bool low = (threadIdx.x & off) == 0;
+    x = low ? dd_add(x, y) : dd_add(y, x);
+  }
+  return x;
+}
+
+// Sum of n entries of 3 sums each, read with `stride` doubles per entry: stride 3 = plain tile
+// partials {A, B, C}, stride 6 = double-double group partials {A, A_lo, B, B_lo, C, C_lo}.
+// All threads of the block take part; thread 0 returns the totals in tot[3].
+template <int THREADS>
+__device__ inline void block_dd_sum(const double* in, int64_t n, int stride, double (*sh)[6], dd* tot) {
+  dd acc[3] = {{0.0, 0.0}, {0.0, 0.0}, {0.0, 0.0}};
+  for (int64_t t = threadIdx.x; t < n; t += THREADS) {
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      dd x;
+      if (stride == 3) {
+        x.hi = in[3 * t + k];
+        x.lo = 0.0;
+      } else {
+        x.hi = in[6 * t + 2 * k];
+        x.lo = in[6 * t + 2 * k + 1];
+      }
+      acc[k] = dd_add(acc[k], x);
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < 3; ++k) acc[k] = dd_wave_sum(acc[k]);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) {
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      sh[wave][2 * k] = acc[k].hi;
+      sh[wave][2 * k + 1] = acc[k].lo;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      tot[k].hi = sh[0][2 * k];
+      tot[k].lo = sh[0][2 * k + 1];
+      for (int wv = 1; wv < THREADS / 64; ++wv) {
+        dd x = {sh[wv][2 * k], sh[wv][2 * k + 1]};
+        tot[k] = dd_add(tot[k], x);
+      }
+    }
+  }
+}
+
+// First stage for long vectors: block g adds tile partials [g*NT_GROUP_TILES, ...) into one
+// double-double group partial.
+__global__ __launch_bounds__(NT_GROUP_THREADS) void k_reduce_groups(const double* partials, int64_t ntiles,
+                                                                    double* groups) {
+  __shared__ double sh[NT_GROUP_THREADS / 64][6];
+  const int64_t t0 = (int64_t)blockIdx.x * NT_GROUP_TILES;
+  const int64_t n = (ntiles - t0 < NT_GROUP_TILES) ? (ntiles - t0) : NT_GROUP_TILES;
+  dd tot[3];
+  block_dd_sum<NT_GROUP_THREADS>(partials + 3 * t0, n, 3, sh, tot);
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      groups[6 * (int64_t)blockIdx.x + 2 * k] = tot[k].hi;
+      groups[6 * (int64_t)blockIdx.x + 2 * k + 1] = tot[k].lo;
+    }
+  }
+}
+
+// One block: partials (tile or group) -> A, B, C in double-double, then the decision.
+__global__ __launch_bounds__(NT_FIN_THREADS) void k_finalize(const double* in, int64_t n, int stride, DecideParams q,
+                                                             nt_result* out) {
+  __shared__ double sh[NT_FIN_THREADS / 64][6];
+  const bool stats = (q.flags & NT_DO_STATS) != 0;
+  dd tot[3] = {{0.0, 0.0}, {0.0, 0.0}, {0.0, 0.0}};
+  if (stats) block_dd_sum<NT_FIN_THREADS>(in, n, stride, sh, tot);
+  if (threadIdx.x != 0) return;
+  nt_result r;
+  r.status = 0;
+  const double nan = __builtin_nan("");
+  if (!stats) {
+    r.A = r.B = r.C = r.A_lo = r.B_lo = r.C_lo = nan;
+    r.gbar_sq = r.var_l1 = r.T = nan;
+    r.pass = 1;
+    r.next_b = q.b_k;
+    r.status = NT_STATUS_NO_STATS;
+  } else {
+    r.A = tot[0].hi; r.A_lo = tot[0].lo;
+    r.B = tot[1].hi; r.B_lo = tot[1].lo;
+    r.C = tot[2].hi; r.C_lo = tot[2].lo;
+    if (q.flags & NT_PARTIAL) {
+      r.gbar_sq = r.var_l1 = r.T = nan;
+      r.pass = 1;
+      r.next_b = q.b_k;
+      r.status = NT_STATUS_PARTIAL_ONLY;
+      if (!(__builtin_isfinite(r.A) && __builtin_isfinite(r.B) && __builtin_isfinite(r.C)))
+        r.status |= NT_STATUS_NONFINITE;
+    } else {
+      decide(q, &r);
+    }
+  }
+  *out = r;
+}
+
+__global__ __launch_bounds__(NT_BLOCK) void k_copy16(f32x4* dst, const u32x4* src, int64_t n16) {
+  for (int64_t i = (int64_t)blockIdx.x * NT_BLOCK + threadIdx.x; i < n16; i += (int64_t)gridDim.x * NT_BLOCK) {
+    u32x4 x = ld_vec<NT_NT_COPY, u32x4>(src + i);
+    f32x4 y = __builtin_bit_cast(f32x4, x);
+#if NT_NT_COPY
+    __builtin_nontemporal_store(y, dst + i);
+#else
+    dst[i] = y;
+#endif
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------------------------
+inline int hip_code(hipError_t e) { return e == hipSuccess ? NT_OK : NT_ERR_HIP_BASE - (int)e; }
+
+int cu_count() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  int n = __atomic_load_n(&cached[dev], __ATOMIC_RELAXED);
+  if (n <= 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    __atomic_store_n(&cached[dev], n, __ATOMIC_RELAXED);
+  }
+  return n;
+}
+
+inline int64_t tile_coords(int64_t J) { return J <= NT_JCHUNK ? NT_TILE_SMALL : NT_TILE_LARGE; }
+
+bool hyper_ok(const nt_hyper* h, int64_t J) {
+  if (!h) return false;
+  const uint32_t known = NT_DO_STATS | NT_DO_ADAMW | NT_PARTIAL | NT_WRITE_GBAR;
+  if (h->flags & ~known) return false;
+  if (!(h->flags & (NT_DO_STATS | NT_DO_ADAMW))) return false;
+  if ((h->flags & NT_PARTIAL) && !(h->flags & NT_DO_STATS)) return false;
+  if (!(h->eta > 0.0) || !std::isfinite(h->eta)) return false;
+  if (h->b_k < 1 || h->b_max < 0 || h->round_to < 1) return false;
+  if (h->ddof != 0 && h->ddof != 1) return false;
+  if (J - h->ddof < 1) return false;
+  if (h->flags & NT_DO_ADAMW) {
+    if (h->step < 1) return false;
+    if (!(h->lr >= 0.0) || !std::isfinite(h->lr)) return false;
+    if (!(h->beta1 >= 0.0 && h->beta1 < 1.0) || !(h->beta2 >= 0.0 && h->beta2 < 1.0)) return false;
+    if (!(h->eps >= 0.0) || !std::isfinite(h->eps)) return false;
+    if (!(h->weight_decay >= 0.0) || !std::isfinite(h->weight_decay)) return false;
+  }
+  return true;
+}
+
+template <class GT, int MODE>
+hipError_t launch_step(const StepParams& p, int64_t nfull, int64_t ntiles, int grid, hipStream_t st) {
+  constexpr int TS = NT_TILE_SMALL, TL = NT_TILE_LARGE;
+#define NT_CASE(JJ)                                                                                        \
+  case JJ:                                                                                                 \
+    hipLaunchKernelGGL((k_step<GT, JJ, MODE, TS>), dim3(grid), dim3(NT_BLOCK), 0, st, p, nfull, ntiles); \
+    break;
+  switch (p.J) {
+    NT_CASE(2) NT_CASE(3) NT_CASE(4) NT_CASE(5) NT_CASE(6) NT_CASE(7) NT_CASE(8) NT_CASE(9)
+    NT_CASE(10) NT_CASE(11) NT_CASE(12) NT_CASE(13) NT_CASE(14) NT_CASE(15) NT_CASE(16)
+    default:
+      hipLaunchKernelGGL((k_step<GT, 0, MODE, TL>), dim3(grid), dim3(NT_BLOCK), 0, st, p, nfull, ntiles);
+  }
+#undef NT_CASE
+  return hipGetLastError();
+}
+
+template <class GT>
+hipError_t launch_step_mode(int mode, const StepParams& p, int64_t nfull, int64_t ntiles, int grid, hipStream_t st) {
+  switch (mode) {
+    case MODE_FULL: return launch_step<GT, MODE_FULL>(p, nfull, ntiles, grid, st);
+    case MODE_STATS: return launch_step<GT, MODE_STATS>(p, nfull, ntiles, grid, st);
+    default: return launch_step<GT, MODE_ADAMW>(p, nfull, ntiles, grid, st);
+  }
+}
+
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+int64_t normtest_tile_coords(int64_t J) { return J >= 2 ? tile_coords(J) : 0; }
+
+size_t normtest_workspace_bytes(int64_t J, int64_t d) {
+  if (J < 2 || d < 0) return 0;
+  const int64_t tc = tile_coords(J);
+  const int64_t ntiles = (d + tc - 1) / tc;
+  const int64_t n = ntiles > 0 ? ntiles : 1;
+  const int64_t ngroups = ntiles > NT_DIRECT_TILES ? (ntiles + NT_GROUP_TILES - 1) / NT_GROUP_TILES : 0;
+  return (size_t)(n * 3 + ngroups * 6) * sizeof(double);
+}
+
+int normtest_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld, float* w, float* m,
+                  float* v, float* gbar_out, const nt_hyper* hyper, const nt_shard_info* shard, void* workspace,
+                  size_t workspace_bytes, nt_result* result_dev, void* hip_stream) {
+  if (gdtype != NT_F32 && gdtype != NT_BF16) return NT_ERR_UNSUPPORTED;
+  if (J < 2 || J > (1 << 20) || d < 0 || ld < d) return NT_ERR_BAD_ARG;
+  if (!hyper_ok(hyper, J) || !result_dev || !workspace) return NT_ERR_BAD_ARG;
+  if (((uintptr_t)result_dev & 7u) || ((uintptr_t)workspace & 7u)) return NT_ERR_BAD_ARG;
+  const uint32_t flags = hyper->flags;
+  if (d > 0 && !grads) return NT_ERR_BAD_ARG;
+  if (d > 0 && (flags & NT_DO_ADAMW) && (!w || !m || !v)) return NT_ERR_BAD_ARG;
+  if (d > 0 && (flags & NT_WRITE_GBAR) && !gbar_out) return NT_ERR_BAD_ARG;
+  const int esize = gdtype == NT_F32 ? 4 : 2;
+  if (((uintptr_t)grads & (uintptr_t)(esize - 1)) || ((uintptr_t)w & 3u) || ((uintptr_t)m & 3u) ||
+      ((uintptr_t)v & 3u) || ((flags & NT_WRITE_GBAR) && ((uintptr_t)gbar_out & 3u)))
+    return NT_ERR_BAD_ARG;
+  if (shard) {
+    if (shard->num_shards < 1 || shard->shard_id < 0 || shard->shard_id >= shard->num_shards ||
+        shard->shard_offset < 0 || shard->d_global < 0 || shard->shard_offset + d > shard->d_global)
+      return NT_ERR_BAD_ARG;
+  }
+  if (workspace_bytes < normtest_workspace_bytes(J, d)) return NT_ERR_WORKSPACE_TOO_SMALL;
+
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int64_t tc = tile_coords(J);
+  const int64_t ntiles = (d + tc - 1) / tc;
+  const int mode = (flags & NT_DO_STATS) ? ((flags & NT_DO_ADAMW) ? MODE_FULL : MODE_STATS) : MODE_ADAMW;
+
+  StepParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.grads = grads;
+  p.ld = ld;
+  p.d = d;
+  p.J = (int)J;
+  p.w = w;
+  p.m = m;
+  p.v = v;
+  p.gbar = (flags & NT_WRITE_GBAR) ? gbar_out : nullptr;
+  p.partials = (double*)workspace;
+  p.inv_J = 1.0 / (double)J;
+  if (flags & NT_DO_ADAMW) {
+    // scalar constants in fp64 on the host, rounded once to fp32
+    const double bc1 = 1.0 - std::pow(hyper->beta1, (double)hyper->step);
+    const double bc2 = 1.0 - std::pow(hyper->beta2, (double)hyper->step);
+    p.beta1 = (float)hyper->beta1;
+    p.omb1 = (float)(1.0 - hyper->beta1);
+    p.beta2 = (float)hyper->beta2;
+    p.omb2 = (float)(1.0 - hyper->beta2);
+    p.decay = (float)(1.0 - hyper->lr * hyper->weight_decay);
+    p.step_size = (float)(hyper->lr / bc1);
+    p.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(bc2));
+    p.eps = (float)hyper->eps;
+  }
+
+  if (ntiles > 0) {
+    bool al = aligned16(grads) && ((ld * esize) % 16 == 0);
+    if (mode != MODE_STATS) al = al && aligned16(w) && aligned16(m) && aligned16(v);
+    if (p.gbar) al = al && aligned16(p.gbar);
+    const int64_t nfull = al ? d / tc : 0;
+    const int64_t max_grid = (int64_t)cu_count() * NT_BLOCKS_PER_CU;
+    const int grid = (int)(ntiles < max_grid ? ntiles : max_grid);
+    const hipError_t e = (gdtype == NT_F32) ? launch_step_mode<F32>(mode, p, nfull, ntiles, grid, st)
+                                            : launch_step_mode<BF16>(mode, p, nfull, ntiles, grid, st);
+    if (e != hipSuccess) return hip_code(e);
+  }
+
+  DecideParams q;
+  q.J = J;
+  q.eta = hyper->eta;
+  q.b_k = hyper->b_k;
+  q.b_max = hyper->b_max;
+  q.round_to = hyper->round_to;
+  q.ddof = hyper->ddof;
+  q.flags = flags;
+  const double* partials = (const double*)workspace;
+  if ((flags & NT_DO_STATS) && ntiles > NT_DIRECT_TILES) {
+    const int64_t ngroups = (ntiles + NT_GROUP_TILES - 1) / NT_GROUP_TILES;
+    double* groups = (double*)workspace + 3 * ntiles;
+    hipLaunchKernelGGL(k_reduce_groups, dim3((unsigned)ngroups), dim3(NT_GROUP_THREADS), 0, st, partials, ntiles, groups);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_code(e);
+    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(NT_FIN_THREADS), 0, st, (const double*)groups, ngroups, 6, q, result_dev);
+  } else {
+    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(NT_FIN_THREADS), 0, st, partials, ntiles, 3, q, result_dev);
+  }
+  return hip_code(hipGetLastError());
+}
+
+int normtest_combine(const nt_result* partials, int32_t n, int64_t J, const nt_hyper* hyper, nt_result* out) {
+  if (!partials || !out || n < 1 || J < 2 || !hyper) return NT_ERR_BAD_ARG;
+  if (!(hyper->eta > 0.0) || !std::isfinite(hyper->eta) || hyper->b_k < 1 || hyper->b_max < 0 ||
+      hyper->round_to < 1 || (hyper->ddof != 0 && hyper->ddof != 1) || J - hyper->ddof < 1)
+    return NT_ERR_BAD_ARG;
+  dd tot[3] = {{0.0, 0.0}, {0.0, 0.0}, {0.0, 0.0}};
+  uint32_t status = 0;
+  for (int32_t s = 0; s < n; ++s) {
+    if (partials[s].status & NT_STATUS_NO_STATS) return NT_ERR_BAD_ARG;
+    const dd a = {partials[s].A, partials[s].A_lo}, b = {partials[s].B, partials[s].B_lo},
+             c = {partials[s].C, partials[s].C_lo};
+    tot[0] = dd_add(tot[0], a);
+    tot[1] = dd_add(tot[1], b);
+    tot[2] = dd_add(tot[2], c);
+    status |= partials[s].status & NT_STATUS_NONFINITE;
+  }
+  nt_result r;
+  std::memset(&r, 0, sizeof(r));
+  r.A = tot[0].hi; r.A_lo = tot[0].lo;
+  r.B = tot[1].hi; r.B_lo = tot[1].lo;
+  r.C = tot[2].hi; r.C_lo = tot[2].lo;
+  if (status & NT_STATUS_NONFINITE) {
+    // a non-finite low part would otherwise poison finite high parts; report the plain sums
+    r.A = r.B = r.C = 0.0;
+    for (int32_t s = 0; s < n; ++s) {
+      r.A += partials[s].A;
+      r.B += partials[s].B;
+      r.C += partials[s].C;
+    }
+    r.A_lo = r.B_lo = r.C_lo = 0.0;
+  }
+  r.status = 0;
+  DecideParams q;
+  q.J = J;
+  q.eta = hyper->eta;
+  q.b_k = hyper->b_k;
+  q.b_max = hyper->b_max;
+  q.round_to = hyper->round_to;
+  q.ddof = hyper->ddof;
+  q.flags = NT_DO_STATS;
+  decide(q, &r);
+  *out = r;
+  return NT_OK;
+}
+
+int normtest_calib_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
+  if (!dst || !src || !aligned16(dst) || !aligned16(src) || (bytes & 15u)) return NT_ERR_BAD_ARG;
+  if (bytes == 0) return NT_OK;
+  const int64_t n16 = (int64_t)(bytes / 16);
+  const int64_t want = (n16 + NT_BLOCK - 1) / NT_BLOCK;
+  const int64_t max_grid = (int64_t)cu_count() * NT_BLOCKS_PER_CU;
+  const int grid = (int)(want < max_grid ? want : max_grid);
+  hipLaunchKernelGGL(k_copy16, dim3(grid), dim3(NT_BLOCK), 0, (hipStream_t)hip_stream, (f32x4*)dst,
+                     (const u32x4*)src, n16);
+  return hip_code(hipGetLastError());
+}
+
+const char* normtest_strerror(int code) {
+  switch (code) {
+    case NT_OK: return "success";
+    case NT_ERR_BAD_ARG: return "bad argument (null or misaligned pointer, J < 2, d < 0, ld < d, or invalid hyper-parameters)";
+    case NT_ERR_UNSUPPORTED: return "unsupported gradient dtype";
+    case NT_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than normtest_workspace_bytes(J, d)";
+    default: break;
+  }
+  if (code <= NT_ERR_HIP_BASE) return hipGetErrorString((hipError_t)(NT_ERR_HIP_BASE - code));
+  return "unknown error code";
+}
+
+}  // extern "C"

@@ -1,0 +1,290 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same seeded
+inputs, element by element; plus bit-exactness properties (determinism, path and shard invariance)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2412_21124_amd import binding as B
+from paper_2412_21124_amd import synth
+
+import helpers as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+FULL = B.NT_DO_STATS | B.NT_DO_ADAMW
+
+
+def hyper_of(h: synth.Hyper, flags=FULL) -> B.nt_hyper:
+    return B.make_hyper(lr=h.lr, beta1=h.beta1, beta2=h.beta2, eps=h.eps, weight_decay=h.weight_decay,
+                        eta=h.eta, step=h.step, b_k=h.b_k, b_max=h.b_max, round_to=h.round_to,
+                        ddof=h.ddof, flags=flags)
+
+
+def gpu_step(grads, w, m, v, h: synth.Hyper, d=None, flags=FULL, **kw) -> dict:
+    res = B.normtest_step(grads, w, m, v, hyper_of(h, flags), d=d, **kw)
+    torch.cuda.synchronize()
+    return B.read_result(res).as_dict()
+
+
+def full_parity(wl: synth.Workload, d=None, flags=FULL, check_gbar=False):
+    """One full step on the GPU, everything compared with the oracle."""
+    d = wl.d if d is None else d
+    w0, m0, v0 = wl.w.clone(), wl.m.clone(), wl.v.clone()
+    gbar = torch.full((max(d, 1),), 7.0, dtype=torch.float32, device=wl.grads.device) if check_gbar else None
+    fl = flags | (B.NT_WRITE_GBAR if check_gbar else 0)
+    res = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper, d=d, flags=fl, gbar_out=gbar)
+    ref = H.oracle_full(wl.grads, d, wl.J, wl.hyper)
+    H.assert_stats_close(res, ref)
+    H.assert_decision_matches(res, ref, wl.hyper)
+    H.oracle_adamw_check(wl.grads, d, w0, m0, v0, wl.w, wl.m, wl.v, wl.hyper, gbar=gbar)
+    # coordinates past d are never written
+    for a, b in ((wl.w, w0), (wl.m, m0), (wl.v, v0)):
+        assert torch.equal(a[d:], b[d:])
+    return res, ref
+
+
+# ------------------------------------------------------------------ the paper-shaped workloads, small
+
+@pytest.mark.parametrize("sigma,expect_pass", [(1e-3, True), (1e-2, False)])
+def test_tiny_config(sigma, expect_pass):
+    wl = synth.tiny(sigma, device=DEV)
+    res, ref = full_parity(wl, check_gbar=True)
+    assert bool(res["pass"]) == expect_pass == ref.dec.passed
+    assert res["next_b"] == ref.dec.next_b
+
+
+@pytest.mark.parametrize("ratio", [0.1, 0.3, 1.0, 1.9, 2.0, 3.0, 10.0])
+def test_gpt2_small_scaled_ratio_sweep(ratio):
+    sizes = synth.scaled_blocks(synth.gpt2_small_blocks(), 1 << 21, multiple=8)
+    wl = synth.gpt2_small(ratio, block_sizes=sizes, seed=2, device=DEV)
+    res, ref = full_parity(wl)
+    assert res["C"] < res["A"]
+
+
+def test_per_sample_scaled():
+    wl = synth.per_sample(b=512, d=1 << 16, n_blocks=64, seed=3, device=DEV)
+    full_parity(wl)
+
+
+def test_fsdp_shard_scaled_and_combine():
+    """Eight shards with fresh seeds, each a PARTIAL call; the host combine equals the oracle on the concatenation."""
+    d_shard, J = 100_003, 16
+    parts, accs = [], []
+    hyper = None
+    for sid in range(8):
+        wl = synth.fsdp_shard(sid, d_shard=d_shard, J=J, seed=5, device=DEV)
+        hyper = wl.hyper
+        w0, m0, v0 = wl.w.clone(), wl.m.clone(), wl.v.clone()
+        shard = B.nt_shard_info(sid, 8, sid * d_shard, 8 * d_shard)
+        res = B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hyper_of(hyper, FULL | B.NT_PARTIAL), shard=shard)
+        torch.cuda.synchronize()
+        r = B.read_result(res)
+        assert r.status == B.NT_STATUS_PARTIAL_ONLY and math.isnan(r.T) and r.next_b == hyper.b_k
+        ref = H.oracle_full(wl.grads, d_shard, J, hyper)
+        H.assert_stats_close(r.as_dict(), ref, partial=True)
+        H.oracle_adamw_check(wl.grads, d_shard, w0, m0, v0, wl.w, wl.m, wl.v, hyper)
+        parts.append(r)
+        accs.append((ref.A, ref.B, ref.C))
+    comb = B.normtest_combine(parts, J, hyper_of(hyper)).as_dict()
+    A, Bs, C = oracle.combine_chunks(accs)
+    ref = H.OracleOut(A, Bs, C, H.oracle_decide(A, Bs, C, J, hyper))
+    H.assert_stats_close(comb, ref)
+    H.assert_decision_matches(comb, ref, hyper)
+
+
+# ------------------------------------------------------------------ shapes: every J path, ragged tails
+
+@pytest.mark.parametrize("J", [2, 3, 4, 5, 6, 7, 8, 9, 11, 13, 15, 16])
+@pytest.mark.parametrize("gdtype", [torch.float32, torch.bfloat16])
+def test_small_J_ragged(J, gdtype):
+    d = 3 * 16384 + 4321          # three full tiles, a ragged tile whose end is not a multiple of the vector width
+    wl = synth.make("t", J, d, gdtype=gdtype, sigma=2e-2, seed=J, device=DEV,
+                    hyper=synth.Hyper(b_k=16, round_to=J, step=3))
+    full_parity(wl, check_gbar=(J % 4 == 0))
+
+
+@pytest.mark.parametrize("J", [17, 31, 32, 48, 100])
+@pytest.mark.parametrize("gdtype", [torch.float32, torch.bfloat16])
+def test_large_J_ragged(J, gdtype):
+    d = 5 * 4096 + 777
+    wl = synth.make("t", J, d, gdtype=gdtype, sigma=1e-2, seed=J, device=DEV,
+                    hyper=synth.Hyper(b_k=64, round_to=1, step=7))
+    full_parity(wl, check_gbar=True)
+
+
+@pytest.mark.parametrize("d", [0, 1, 7, 8, 2047, 2048, 16383, 16384, 16385])
+def test_small_d(d):
+    wl = synth.make("t", 8, max(d, 1), gdtype=torch.bfloat16, sigma=1e-2, seed=d, device=DEV)
+    full_parity(wl, d=d)
+
+
+def test_d_zero_result():
+    wl = synth.make("t", 4, 8, device=DEV)
+    res = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper, d=0)
+    assert (res["A"], res["B"], res["C"]) == (0.0, 0.0, 0.0)
+    assert res["pass"] == 1 and res["next_b"] == wl.hyper.b_k and res["status"] == B.NT_STATUS_ZERO_GRAD_NORM
+
+
+# ------------------------------------------------------------------ bit-exactness properties
+
+def test_two_runs_bit_identical():
+    wl = synth.gpt2_small(1.0, block_sizes=synth.scaled_blocks(synth.gpt2_small_blocks(), 1 << 20, 8), device=DEV)
+    w0, m0, v0 = wl.w.clone(), wl.m.clone(), wl.v.clone()
+    r1 = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper)
+    out1 = (wl.w.clone(), wl.m.clone(), wl.v.clone())
+    wl.w.copy_(w0), wl.m.copy_(m0), wl.v.copy_(v0)
+    r2 = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper)
+    assert r1 == r2
+    for a, b in zip(out1, (wl.w, wl.m, wl.v)):
+        assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("J,gdtype", [(8, torch.bfloat16), (4, torch.float32), (40, torch.bfloat16)])
+def test_misaligned_and_padded_rows_same_bits(J, gdtype):
+    """Rows that start 1 element off a 16-byte boundary, or with a padded stride, take the guarded
+    kernel; the sums and the updated state must have the same bits as on the aligned fast path."""
+    d = 2 * B.normtest_tile_coords(J) + 1000
+    wl = synth.make("t", J, d, gdtype=gdtype, sigma=1e-2, seed=1, device=DEV)
+    state0 = (wl.w.clone(), wl.m.clone(), wl.v.clone())
+    ref = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper)
+    ref_state = (wl.w.clone(), wl.m.clone(), wl.v.clone())
+    for pad, off in ((3, 1), (8, 0), (0, 1)):
+        big = torch.zeros((J, d + pad + off), dtype=gdtype, device=DEV)
+        big[:] = 9.0                                 # poison the padding
+        view = big[:, off:off + d]
+        view.copy_(wl.grads)
+        st = [torch.full((d + 1,), 5.0, device=DEV)[off:off + d] for _ in range(3)]
+        for t, s in zip(st, state0):
+            t.copy_(s)
+        res = gpu_step(view, st[0], st[1], st[2], wl.hyper, d=d)
+        assert res == ref
+        for a, b in zip(st, ref_state):
+            assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("J,gdtype", [(8, torch.bfloat16), (16, torch.bfloat16), (4, torch.float32), (64, torch.bfloat16)])
+def test_tile_aligned_shards_add_up_bit_exactly(J, gdtype):
+    tc = B.normtest_tile_coords(J)
+    d = 11 * tc + 517
+    wl = synth.make("t", J, d, gdtype=gdtype, sigma=1e-2, seed=4, device=DEV)
+    state0 = (wl.w.clone(), wl.m.clone(), wl.v.clone())
+    whole = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper)
+    whole_state = (wl.w.clone(), wl.m.clone(), wl.v.clone())
+    for t, s in zip((wl.w, wl.m, wl.v), state0):
+        t.copy_(s)
+    cuts = [0, 2 * tc, 3 * tc, 8 * tc, d]
+    parts = []
+    for sid, (lo, hi) in enumerate(zip(cuts[:-1], cuts[1:])):
+        res = B.normtest_step(wl.grads[:, lo:hi], wl.w[lo:hi], wl.m[lo:hi], wl.v[lo:hi],
+                              hyper_of(wl.hyper, FULL | B.NT_PARTIAL),
+                              shard=B.nt_shard_info(sid, len(cuts) - 1, lo, d))
+        torch.cuda.synchronize()
+        parts.append(B.read_result(res))
+    comb = B.normtest_combine(parts, J, hyper_of(wl.hyper)).as_dict()
+    for k in ("A", "B", "C", "gbar_sq", "var_l1", "T", "next_b", "pass", "status"):
+        assert comb[k] == whole[k], k
+    for a, b in zip((wl.w, wl.m, wl.v), whole_state):
+        assert torch.equal(a, b)
+
+
+# ------------------------------------------------------------------ flags
+
+def test_stats_only_leaves_state_untouched():
+    wl = synth.tiny(1e-2, d=50_000, device=DEV)
+    w0, m0, v0 = wl.w.clone(), wl.m.clone(), wl.v.clone()
+    res = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper, flags=B.NT_DO_STATS)
+    ref = H.oracle_full(wl.grads, wl.d, wl.J, wl.hyper)
+    H.assert_stats_close(res, ref)
+    H.assert_decision_matches(res, ref, wl.hyper)
+    assert torch.equal(wl.w, w0) and torch.equal(wl.m, m0) and torch.equal(wl.v, v0)
+    # state pointers may be absent altogether
+    res2 = gpu_step(wl.grads, None, None, None, wl.hyper, flags=B.NT_DO_STATS)
+    assert res2 == res
+    # and the sums are the same bits as in the fused step
+    res3 = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper, flags=FULL)
+    assert (res3["A"], res3["B"], res3["C"]) == (res["A"], res["B"], res["C"])
+
+
+def test_adamw_only_reports_no_stats():
+    wl = synth.make("t", 8, 70_001, gdtype=torch.bfloat16, seed=8, device=DEV)
+    w0, m0, v0 = wl.w.clone(), wl.m.clone(), wl.v.clone()
+    res = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper, flags=B.NT_DO_ADAMW)
+    assert res["status"] == B.NT_STATUS_NO_STATS and res["pass"] == 1 and res["next_b"] == wl.hyper.b_k
+    assert math.isnan(res["A"]) and math.isnan(res["T"])
+    H.oracle_adamw_check(wl.grads, wl.d, w0, m0, v0, wl.w, wl.m, wl.v, wl.hyper)
+
+
+def test_first_step_from_zero_moments():
+    """k = 1 with m = v = 0 (Alg. 1's initial state): the update is a sign step of size lr."""
+    wl = synth.make("t", 8, 40_000, gdtype=torch.bfloat16, seed=9, device=DEV,
+                    hyper=synth.Hyper(step=1, lr=4e-4, b_k=256, round_to=128))
+    wl.m.zero_(), wl.v.zero_()
+    w0 = wl.w.clone()
+    full_parity(wl)
+    moved = (wl.w - (1 - 4e-4 * 0.1) * w0).abs()
+    assert float(moved.max()) <= 4e-4 * (1 + 1e-5)
+
+
+def test_ddof_zero_is_alg1_estimator():
+    wl = synth.tiny(1e-2, d=100_000, device=DEV)
+    wl.hyper.ddof = 0
+    res, ref = full_parity(wl)
+    assert res["var_l1"] == pytest.approx(res["C"] / wl.J, rel=1e-15)
+
+
+# ------------------------------------------------------------------ degenerate inputs
+
+@pytest.mark.parametrize("J", [4, 8, 32])
+def test_identical_rows_have_exactly_zero_variance(J):
+    wl = synth.make("t", J, 40_000, gdtype=torch.bfloat16, seed=10, device=DEV)
+    wl.grads[:] = wl.grads[0].clone()
+    res = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper)
+    assert res["C"] == 0.0 and res["T"] == 0.0 and res["pass"] == 1 and res["next_b"] == wl.hyper.b_k
+    n2 = float((wl.grads[0].double() ** 2).sum())
+    assert res["gbar_sq"] == pytest.approx(n2, rel=1e-6)
+
+
+def test_zero_gradients_and_zero_mean():
+    wl = synth.make("t", 4, 20_000, seed=11, device=DEV)
+    wl.grads.zero_()
+    res = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper)
+    assert res["status"] == B.NT_STATUS_ZERO_GRAD_NORM and res["pass"] == 1 and res["next_b"] == wl.hyper.b_k
+    # rows that cancel exactly: zero mean, positive spread -> cannot pass, go to the cap
+    wl.grads[0] = 1.0
+    wl.grads[1] = -1.0
+    res = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper)
+    assert res["status"] == B.NT_STATUS_ZERO_GRAD_NORM and res["pass"] == 0 and res["next_b"] == wl.hyper.b_max
+    assert math.isinf(res["T"]) and res["C"] == 2.0 * 20_000
+
+
+@pytest.mark.parametrize("bad", [float("nan"), float("inf")])
+def test_nonfinite_gradient_is_flagged_and_batch_kept(bad):
+    wl = synth.make("t", 8, 50_000, gdtype=torch.bfloat16, seed=12, device=DEV)
+    wl.grads[3, 31_337] = bad
+    res = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper)
+    assert res["status"] & B.NT_STATUS_NONFINITE and res["pass"] == 1 and res["next_b"] == wl.hyper.b_k
+    ref = H.oracle_full(wl.grads, wl.d, wl.J, wl.hyper)
+    assert ref.dec.status & oracle.NONFINITE and ref.dec.next_b == res["next_b"]
+
+
+def test_threshold_and_cap():
+    """A statistic far above b_max is cut to it; b_k above the statistic passes."""
+    wl = synth.tiny(1e-2, d=100_000, device=DEV)
+    wl.hyper.b_max = 64
+    res, ref = full_parity(wl)
+    assert res["next_b"] == 64 and res["status"] == B.NT_STATUS_CLAMPED == ref.dec.status
+    wl2 = synth.tiny(1e-2, d=100_000, device=DEV)
+    wl2.hyper.b_k = 4096
+    res, ref = full_parity(wl2)
+    assert res["pass"] == 1 and res["next_b"] == 4096
+
+
+def test_calib_copy():
+    src = torch.randn(1 << 20, device=DEV)
+    dst = torch.zeros_like(src)
+    B.normtest_calib_copy(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)

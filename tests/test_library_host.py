@@ -1,0 +1,183 @@
+"""CPU-only checks of libnormtest.so: it loads, exports what include/normtest.h declares, validates its
+arguments before touching the GPU, and its host-side combine / decision agrees with the oracle."""
+import ctypes
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2412_21124_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FULL = B.NT_DO_STATS | B.NT_DO_ADAMW
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "normtest.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(normtest_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert {"normtest_step", "normtest_combine", "normtest_workspace_bytes", "normtest_tile_coords",
+            "normtest_strerror", "normtest_calib_copy"} <= set(names)
+    L = B.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_struct_layouts_match_header():
+    assert ctypes.sizeof(B.nt_hyper) == 6 * 8 + 4 * 8 + 4 + 4
+    assert ctypes.sizeof(B.nt_result) == 9 * 8 + 8 + 4 + 4
+    assert ctypes.sizeof(B.nt_shard_info) == 4 + 4 + 8 + 8
+
+
+def test_workspace_and_tiles():
+    for J in (2, 8, 16, 17, 512):
+        tc = B.normtest_tile_coords(J)
+        assert tc > 0 and tc % 4 == 0
+        prev = 0
+        for d in (0, 1, tc, tc + 1, 5000 * tc, 1_500_000_000):
+            ntiles = max(1, -(-d // tc))
+            need = B.normtest_workspace_bytes(J, d)
+            # three doubles per tile, plus a small second level for long vectors
+            assert 24 * ntiles <= need <= 24 * ntiles + 48 * (ntiles // 1024 + 1)
+            assert need >= prev and need % 8 == 0
+            prev = need
+    assert B.normtest_tile_coords(1) == 0
+    assert B.normtest_workspace_bytes(1, 10) == 0 and B.normtest_workspace_bytes(4, -1) == 0
+
+
+def _call(J=4, d=64, ld=None, gdtype=B.NT_F32, grads=0x1000, w=0x2000, m=0x3000, v=0x4000, gbar=None,
+          hyper=None, shard=None, ws=0x5000, ws_bytes=1 << 20, result=0x6000):
+    """normtest_step with fabricated pointers: only legal for calls that must be rejected before any launch."""
+    hyper = hyper if hyper is not None else B.make_hyper(step=1, b_k=32, flags=FULL)
+    return B.lib().normtest_step(grads, gdtype, J, d, d if ld is None else ld, w, m, v, gbar,
+                                 ctypes.byref(hyper), ctypes.byref(shard) if shard else None,
+                                 ws, ws_bytes, result, None)
+
+
+def test_bad_arguments_are_rejected_before_any_launch():
+    bad = B.NT_ERR_BAD_ARG
+    assert _call(J=1) == bad
+    assert _call(d=-1) == bad
+    assert _call(d=64, ld=63) == bad
+    assert _call(grads=None) == bad
+    assert _call(w=None) == bad
+    assert _call(result=None) == bad
+    assert _call(ws=None) == bad
+    assert _call(result=0x6004) == bad                       # result not 8-byte aligned
+    assert _call(grads=0x1002) == bad                        # fp32 rows not 4-byte aligned
+    assert _call(gdtype=B.NT_BF16, grads=0x1001) == bad
+    assert _call(w=0x2002) == bad
+    assert _call(gdtype=7) == B.NT_ERR_UNSUPPORTED
+    assert _call(ws_bytes=8) == B.NT_ERR_WORKSPACE_TOO_SMALL
+    for kw in (dict(eta=0.0), dict(eta=-1.0), dict(eta=math.nan), dict(step=0), dict(b_k=0), dict(b_max=-1),
+               dict(round_to=0), dict(ddof=2), dict(beta1=1.0), dict(beta2=-0.1), dict(lr=-1.0),
+               dict(eps=-1e-8), dict(weight_decay=math.inf), dict(flags=0), dict(flags=64 | FULL),
+               dict(flags=B.NT_PARTIAL | B.NT_DO_ADAMW)):
+        args = dict(step=1, b_k=32, flags=FULL)
+        args.update(kw)
+        assert _call(hyper=B.make_hyper(**args)) == bad, kw
+    assert _call(hyper=B.make_hyper(step=1, b_k=32, flags=FULL | B.NT_WRITE_GBAR), gbar=None) == bad
+    assert _call(shard=B.nt_shard_info(8, 8, 0, 64)) == bad   # shard_id out of range
+    assert _call(shard=B.nt_shard_info(0, 8, 10, 64)) == bad  # shard runs past d_global
+    # stats-only calls do not need w, m, v: this one gets past validation only to fail on the workspace
+    assert _call(w=None, m=None, v=None, hyper=B.make_hyper(b_k=32, flags=B.NT_DO_STATS), ws_bytes=0) \
+        == B.NT_ERR_WORKSPACE_TOO_SMALL
+
+
+def test_strerror():
+    assert B.normtest_strerror(0) == "success"
+    assert "argument" in B.normtest_strerror(B.NT_ERR_BAD_ARG)
+    assert "workspace" in B.normtest_strerror(B.NT_ERR_WORKSPACE_TOO_SMALL)
+    assert B.normtest_strerror(B.NT_ERR_HIP_BASE - 1)       # some HIP text
+    assert "unknown" in B.normtest_strerror(-5)
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    g = torch.zeros((4, 16))
+    z = torch.zeros(16)
+    with pytest.raises(ValueError):
+        B.normtest_step(g, z, z.clone(), z.clone(), B.make_hyper(b_k=4))
+
+
+def _part(A, Bv, C, status=B.NT_STATUS_PARTIAL_ONLY):
+    return B.nt_result(A=A, B=Bv, C=C, status=status)
+
+
+def test_combine_decision_agrees_with_oracle_on_random_sums():
+    rng = np.random.default_rng(0)
+    n_checked = 0
+    for trial in range(4000):
+        J = int(rng.integers(2, 40))
+        ddof = int(rng.integers(0, 2))
+        eta = float(rng.choice([0.05, 0.1, 0.15, 0.275, 0.5]))
+        b_k = int(rng.choice([1, 32, 256, 4096]))
+        b_max = int(rng.choice([0, 512, 8192]))
+        round_to = int(rng.choice([1, 4, 64, 128]))
+        Bv = float(10 ** rng.uniform(-6, 3))
+        C = float(10 ** rng.uniform(-8, 3))
+        A = C + Bv / J
+        hy = B.make_hyper(eta=eta, b_k=b_k, b_max=b_max, round_to=round_to, ddof=ddof)
+        got = B.normtest_combine([_part(A, Bv, C)], J, hy)
+        want = oracle.decide(A, Bv, C, J, eta, b_k, b_max, round_to, ddof)
+        assert got.T == pytest.approx(want.T, rel=1e-14)
+        assert got.gbar_sq == pytest.approx(want.gbar_sq, rel=1e-15)
+        assert got.var_l1 == pytest.approx(want.var_l1, rel=1e-15)
+        if got.T != want.T:
+            continue                                      # last-bit difference of T: ceiling may differ
+        n_checked += 1
+        assert (got.next_b, bool(got.pass_), got.status) == (want.next_b, want.passed, want.status)
+    assert n_checked > 3000
+
+
+def test_combine_special_cases_agree_with_oracle():
+    cases = [
+        (0.0, 0.0, 0.0), (2.0, 0.0, 2.0), (math.nan, 1.0, 1.0), (math.inf, 1.0, 1.0),
+        (1e300, 1e-300, 1e300), (20.0, 16.0, 16.0), (20.0, 16.0, 0.0),
+    ]
+    for A, Bv, C in cases:
+        for b_max in (0, 8192):
+            hy = B.make_hyper(eta=0.1, b_k=32, b_max=b_max, round_to=4, ddof=1)
+            status_in = B.NT_STATUS_PARTIAL_ONLY | (0 if math.isfinite(A) else B.NT_STATUS_NONFINITE)
+            got = B.normtest_combine([_part(A, Bv, C, status_in)], 4, hy)
+            want = oracle.decide(A, Bv, C, 4, 0.1, 32, b_max, 4, 1)
+            assert (got.next_b, bool(got.pass_), got.status) == (want.next_b, want.passed, want.status), (A, Bv, C)
+            assert (math.isnan(got.T) and math.isnan(want.T)) or got.T == want.T
+
+
+def test_combine_adds_shards_in_double_double():
+    # eight partial sums whose exact total is not representable after naive accumulation
+    vals = [1.0, 2.0 ** -53, 2.0 ** -53, 2.0 ** -53, 2.0 ** -53, 3.0, 2.0 ** -52, 5.0]
+    parts = [_part(x, x, x) for x in vals]
+    hy = B.make_hyper(eta=0.1, b_k=32)
+    out = B.normtest_combine(parts, 4, hy)
+    assert out.A == math.fsum(vals) and out.A + out.A_lo == math.fsum(vals)
+    # low parts carried by the shards are used
+    parts = [B.nt_result(A=1.0, A_lo=2.0 ** -54, B=1.0, C=1.0) for _ in range(4)]
+    out = B.normtest_combine(parts, 4, hy)
+    assert out.A == 4.0 + 2.0 ** -52
+    # order of the shards does not matter at double-double precision
+    rng = np.random.default_rng(1)
+    xs = (10 ** rng.uniform(-3, 3, size=64)).tolist()
+    p1 = [_part(x, x, x) for x in xs]
+    p2 = [_part(x, x, x) for x in sorted(xs)]
+    o1, o2 = B.normtest_combine(p1, 4, hy), B.normtest_combine(p2, 4, hy)
+    assert o1.A == o2.A == math.fsum(xs)
+
+
+def test_combine_rejects_bad_input():
+    hy = B.make_hyper(eta=0.1, b_k=32)
+    with pytest.raises(B.NormtestError):
+        B.normtest_combine([_part(1, 1, 1)], 1, hy)
+    with pytest.raises(B.NormtestError):
+        B.normtest_combine([_part(1, 1, 1, B.NT_STATUS_NO_STATS)], 4, hy)
+    with pytest.raises(B.NormtestError):
+        B.normtest_combine([_part(1, 1, 1)], 4, B.make_hyper(eta=0.0, b_k=32))
+    assert B.lib().normtest_combine(None, 1, 4, ctypes.byref(hy), ctypes.byref(B.nt_result())) == B.NT_ERR_BAD_ARG
