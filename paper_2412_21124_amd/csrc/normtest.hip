@@ -9,8 +9,10 @@
 // Numerics.  The centred sum C = sum_j (g_j - gbar)^2 is formed directly from the J values of a
 // coordinate held in registers, never as A - B/J (which cancels badly when the workers agree).  A
 // rounding error e in gbar only adds J e^2 to a coordinate's centred sum because the cross term
-// sums to zero.  For more than 16 rows the rows are taken 16 at a time and the chunks' means and
-// centred sums are merged with the pairwise update  M2 += M2_b + delta^2 n_a n_b / (n_a + n_b).
+// sums to zero.  For more than 16 rows the rows are taken 16 at a time, each chunk shifted by the
+// running mean so far, and the chunks' means and centred sums are merged with the pairwise update
+// M2 += M2_b + delta^2 n_a n_b / (n_a + n_b).  Row sums are carried in fp64, so the mean handed to
+// AdamW is correctly rounded even when the rows cancel.
 // Per-lane sums leave fp32 after one group of 4 or 8 coordinates; everything above is fp64 in a
 // fixed order, so results do not depend on the grid size and are reproducible bit for bit.
 #include <hip/hip_runtime.h>
@@ -214,35 +216,69 @@ __device__ inline void tile_reduce(double a, double b, double c, double (*red)[N
 // instead of held in registers), so a tile's partial sums and outputs have the same bits on either
 // path.  Coordinates at or beyond d contribute exact zeros.
 // ---------------------------------------------------------------------------------------------
+// Per-chunk bookkeeping of the J > 16 walk, shared by the fast and the guarded path so that both
+// perform the same operations.  For one coordinate and a chunk of nb rows shifted by K (the running
+// mean before the chunk, or the first row for the first chunk), sr = sum (x - K) in fp64 and
+// q = sum (x - K)^2 in fp32 have been accumulated.  Then
+//   chunk centred sum   M2_b = q - sr^2/nb
+//   chunk sum of squares  a_b = q + K (2 sr + nb K)
+//   chunk sum             s_b = nb K + sr
+// and the chunk is merged into the running (S, M2) with  M2 += M2_b + delta^2 na nb/(na + nb),
+// delta = mean_b - mean_a.  Returns the shift for the next chunk.
+__device__ inline float chunk_merge(bool first, int na, int nb, float K, double sr, float q, double& S, float& M2,
+                                    float& a) {
+  const float srf = (float)sr;
+  const float nbf = (float)nb;
+  const double inv_nb = 1.0 / (double)nb;
+  const float M2b = __builtin_fmaf(-(srf * (float)inv_nb), srf, q);
+  a += __builtin_fmaf(K, __builtin_fmaf(nbf, K, 2.0f * srf), q);
+  const double sb = __builtin_fma((double)K, (double)nb, sr);
+  if (first) {
+    S = sb;
+    M2 = M2b;
+  } else {
+    const float coef = ((float)na * nbf) / (float)(na + nb);
+    const float delta = (float)(((double)K - S * (1.0 / (double)na)) + sr * inv_nb);
+    M2 = M2 + __builtin_fmaf(delta * delta, coef, M2b);
+    S = S + sb;
+  }
+  return (float)(S * (1.0 / (double)(na + nb)));
+}
+
 template <class GT>
 __device__ inline void coord_stats_generic(const StepParams& p, int64_t i, double& S, float& M2, float& a) {
   const void* grads = p.grads;
   const int64_t ld = p.ld;
   const int J = p.J;
   a = 0.f;
-  int na = 0;
-  for (int j0 = 0; j0 < J; j0 += NT_JCHUNK) {
-    const int nb = (J - j0 < NT_JCHUNK) ? (J - j0) : NT_JCHUNK;
-    double sb = (double)GT::ld(grads, (int64_t)j0 * ld + i);
-    for (int j = 1; j < nb; ++j) sb += (double)GT::ld(grads, (int64_t)(j0 + j) * ld + i);
-    // a single chunk is centred on the overall mean, exactly as in the fast tile
-    const float mb = (J <= NT_JCHUNK) ? (float)(sb * p.inv_J) : (float)(sb * (1.0 / (double)nb));
+  if (J <= NT_JCHUNK) {
+    // all rows at once: fp64 row sum, then squares centred on the mean, exactly as in the fast tile
+    double sb = (double)GT::ld(grads, i);
+    for (int j = 1; j < J; ++j) sb += (double)GT::ld(grads, (int64_t)j * ld + i);
+    const float mb = (float)(sb * p.inv_J);
     float cb = 0.f;
-    for (int j = 0; j < nb; ++j) {
-      const float x = GT::ld(grads, (int64_t)(j0 + j) * ld + i);
+    for (int j = 0; j < J; ++j) {
+      const float x = GT::ld(grads, (int64_t)j * ld + i);
       const float r = x - mb;
       cb = __builtin_fmaf(r, r, cb);
       a = __builtin_fmaf(x, x, a);
     }
-    if (na == 0) {
-      S = sb;
-      M2 = cb;
-    } else {
-      const float coef = ((float)na * (float)nb) / (float)(na + nb);
-      const float delta = mb - (float)(S * (1.0 / (double)na));
-      M2 = M2 + __builtin_fmaf(delta * delta, coef, cb);
-      S = S + sb;
+    S = sb;
+    M2 = cb;
+    return;
+  }
+  float K = GT::ld(grads, i);
+  int na = 0;
+  for (int j0 = 0; j0 < J; j0 += NT_JCHUNK) {
+    const int nb = (J - j0 < NT_JCHUNK) ? (J - j0) : NT_JCHUNK;
+    double sr = 0.0;
+    float q = 0.f;
+    for (int j = 0; j < nb; ++j) {
+      const float r = GT::ld(grads, (int64_t)(j0 + j) * ld + i) - K;
+      sr += (double)r;
+      q = __builtin_fmaf(r, r, q);
     }
+    K = chunk_merge(na == 0, na, nb, K, sr, q, S, M2, a);
     na += nb;
   }
 }
@@ -390,59 +426,28 @@ __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fast tile, J > 16: rows are walked NT_JCHUNK at a time; per coordinate the running sum S (fp64),
-// the running centred sum M2 and the sum of squares a are carried and chunks are merged pairwise.
-// nb is the number of rows in this chunk (compile-time NB when RT is false), na the rows before it.
+// Fast tile, J > 16: rows are walked NT_JCHUNK at a time.  Inside a chunk every value is shifted by
+// K, the running mean of the rows before it, so one pass over the chunk gives both its sum and its
+// centred sum of squares without cancellation; see chunk_merge for the bookkeeping.
 // ---------------------------------------------------------------------------------------------
-template <class GT, bool FIRST, bool RT>
-__device__ inline void chunk_update(typename GT::raw_t* raw, int nb, int na, double* S, float* M2, float* a) {
+template <class GT, bool RT>
+__device__ inline void chunk_accumulate(const typename GT::raw_t* raw, int nb, const float* K, double* sr, float* q) {
   constexpr int VEC = GT::VEC;
-  double sb[VEC];
-  float mb[VEC], cb[VEC];
-#pragma unroll
-  for (int e = 0; e < VEC; ++e) sb[e] = (double)GT::val(raw[0], e);
-#pragma unroll
-  for (int j = 1; j < NT_JCHUNK; ++j)
-    if (!RT || j < nb) {
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) sb[e] += (double)GT::val(raw[j], e);
-    }
-  const double inv_nb = 1.0 / (double)nb;
 #pragma unroll
   for (int e = 0; e < VEC; ++e) {
-    mb[e] = (float)(sb[e] * inv_nb);
-    cb[e] = 0.f;
+    sr[e] = 0.0;
+    q[e] = 0.f;
   }
-#pragma unroll
-  for (int j = 0; j < NT_JCHUNK; ++j)
-    if (!RT || j < nb) forget(raw[j]);
 #pragma unroll
   for (int j = 0; j < NT_JCHUNK; ++j)
     if (!RT || j < nb) {
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
-        const float x = GT::val(raw[j], e);
-        const float r = x - mb[e];
-        cb[e] = __builtin_fmaf(r, r, cb[e]);
-        a[e] = __builtin_fmaf(x, x, a[e]);
+        const float r = GT::val(raw[j], e) - K[e];
+        sr[e] += (double)r;
+        q[e] = __builtin_fmaf(r, r, q[e]);
       }
     }
-  if constexpr (FIRST) {
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-      S[e] = sb[e];
-      M2[e] = cb[e];
-    }
-  } else {
-    const float coef = ((float)na * (float)nb) / (float)(na + nb);
-    const double inv_na = 1.0 / (double)na;
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-      const float delta = mb[e] - (float)(S[e] * inv_na);
-      M2[e] = M2[e] + __builtin_fmaf(delta * delta, coef, cb[e]);
-      S[e] = S[e] + sb[e];
-    }
-  }
 }
 
 template <class GT, int MODE, int TILE>
@@ -458,22 +463,28 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
   for (int it = 0; it < ITERS; ++it) {
     const int64_t i0 = tile * TILE + ((int64_t)it * NT_BLOCK + threadIdx.x) * VEC;
     const char* gp = gbase + i0 * GT::ESIZE;
-    double S[VEC];
-    float M2[VEC], a[VEC];
+    double S[VEC], sr[VEC];
+    float M2[VEC], a[VEC], K[VEC], q[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) a[e] = 0.f;
     typename GT::raw_t raw[NT_JCHUNK];
-    // first chunk (J > NT_JCHUNK here, so it is full)
+    // first chunk (J > NT_JCHUNK here, so it is full), shifted by the first row
 #pragma unroll
     for (int j = 0; j < NT_JCHUNK; ++j) raw[j] = GT::ldraw(gp + j * row_bytes);
-    chunk_update<GT, true, false>(raw, NT_JCHUNK, 0, S, M2, a);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) K[e] = GT::val(raw[0], e);
+    chunk_accumulate<GT, false>(raw, NT_JCHUNK, K, sr, q);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) K[e] = chunk_merge(true, 0, NT_JCHUNK, K[e], sr[e], q[e], S[e], M2[e], a[e]);
     int j0 = NT_JCHUNK;
 #pragma unroll 1
     for (; j0 + NT_JCHUNK <= J; j0 += NT_JCHUNK) {
       const char* cp = gp + (int64_t)j0 * row_bytes;
 #pragma unroll
       for (int j = 0; j < NT_JCHUNK; ++j) raw[j] = GT::ldraw(cp + j * row_bytes);
-      chunk_update<GT, false, false>(raw, NT_JCHUNK, j0, S, M2, a);
+      chunk_accumulate<GT, false>(raw, NT_JCHUNK, K, sr, q);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) K[e] = chunk_merge(false, j0, NT_JCHUNK, K[e], sr[e], q[e], S[e], M2[e], a[e]);
     }
     if (j0 < J) {
       const int nb = J - j0;
@@ -481,7 +492,9 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
 #pragma unroll
       for (int j = 0; j < NT_JCHUNK; ++j)
         if (j < nb) raw[j] = GT::ldraw(cp + j * row_bytes);
-      chunk_update<GT, false, true>(raw, nb, j0, S, M2, a);
+      chunk_accumulate<GT, true>(raw, nb, K, sr, q);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) K[e] = chunk_merge(false, j0, nb, K[e], sr[e], q[e], S[e], M2[e], a[e]);
     }
     float gb[VEC];
 #pragma unroll
@@ -501,10 +514,10 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
     if constexpr (MODE != MODE_STATS) {
       u32x4 sw[VEC / 4], sm[VEC / 4], sv[VEC / 4];
 #pragma unroll
-      for (int q = 0; q < VEC / 4; ++q) {
-        sw[q] = ld16(p.w + i0 + 4 * q);
-        sm[q] = ld16(p.m + i0 + 4 * q);
-        sv[q] = ld16(p.v + i0 + 4 * q);
+      for (int q4 = 0; q4 < VEC / 4; ++q4) {
+        sw[q4] = ld16(p.w + i0 + 4 * q4);
+        sm[q4] = ld16(p.m + i0 + 4 * q4);
+        sv[q4] = ld16(p.v + i0 + 4 * q4);
       }
       adamw_store<VEC>(p, i0, gb, sw, sm, sv);
     }

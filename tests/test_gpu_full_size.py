@@ -1,0 +1,84 @@
+"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times
+(preallocated workspace and result, torch's current stream).  The oracle streams the device-resident
+inputs to the host chunk by chunk; every sum and every updated w, m, v element is compared."""
+import math
+import time
+
+import pytest
+import torch
+
+from paper_2412_21124_amd import binding as B
+from paper_2412_21124_amd import synth
+
+import helpers as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+FULL = B.NT_DO_STATS | B.NT_DO_ADAMW
+
+
+def run_and_check(wl: synth.Workload, flags=FULL, shard=None):
+    h = wl.hyper
+    t0 = time.time()
+    w0, m0, v0 = wl.w.clone(), wl.m.clone(), wl.v.clone()
+    hy = B.make_hyper(lr=h.lr, beta1=h.beta1, beta2=h.beta2, eps=h.eps, weight_decay=h.weight_decay, eta=h.eta,
+                      step=h.step, b_k=h.b_k, b_max=h.b_max, round_to=h.round_to, ddof=h.ddof, flags=flags)
+    workspace = torch.empty(B.normtest_workspace_bytes(wl.J, wl.d), dtype=torch.uint8, device=DEV)
+    result = torch.empty(B.RESULT_BYTES, dtype=torch.uint8, device=DEV)
+    B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hy, shard=shard, workspace=workspace, result=result,
+                    stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    res = B.read_result(result).as_dict()
+    t1 = time.time()
+    ref = H.oracle_full(wl.grads, wl.d, wl.J, h)
+    t2 = time.time()
+    partial = bool(flags & B.NT_PARTIAL)
+    H.assert_stats_close(res, ref, partial=partial)
+    if partial:
+        assert res["status"] == B.NT_STATUS_PARTIAL_ONLY and res["next_b"] == h.b_k
+    else:
+        H.assert_decision_matches(res, ref, h)
+    n = H.oracle_adamw_check(wl.grads, wl.d, w0, m0, v0, wl.w, wl.m, wl.v, h)
+    assert n == wl.d
+    t3 = time.time()
+    print("%s: J=%d d=%d  gpu %.1fs  oracle stats %.1fs  adamw compare %.1fs  T=%.6g oracle T=%.6g" % (
+        wl.name, wl.J, wl.d, t1 - t0, t2 - t1, t3 - t2, res["T"], ref.dec.T), flush=True)
+    # the identity C = A - B/J holds for the GPU's own sums too (it never forms C that way)
+    assert res["C"] == pytest.approx(res["A"] - res["B"] / wl.J, rel=1e-5 * res["A"] / res["C"])
+    return res, ref
+
+
+def test_tiny_full():
+    for sigma in (1e-3, 1e-2):
+        run_and_check(synth.tiny(sigma, device=DEV))
+
+
+@pytest.mark.parametrize("ratio", [1.0, 3.0])
+def test_gpt2_small_full(ratio):
+    """d = 124,439,808 in 148 blocks with log-uniform scales; ratio 1 passes at b_k = 256, ratio 3 fails."""
+    wl = synth.gpt2_small(ratio, device=DEV)
+    assert wl.d == 124_439_808 and wl.meta["n_blocks"] == 148
+    res, ref = run_and_check(wl)
+    assert bool(res["pass"]) == (ratio < 1.94)
+
+
+def test_flat_1p5b_full():
+    """The headline workload: J=8 bf16, d=1.5e9 (ragged: not a multiple of the tile)."""
+    wl = synth.flat_1p5b(device=DEV)
+    assert wl.d == 1_500_000_000 and wl.d % B.normtest_tile_coords(8) != 0
+    run_and_check(wl)
+
+
+def test_fsdp_shard_full():
+    """One GPU's 1/8 shard of a 7e9-parameter model, J=16 micro-batch gradients, partial sums only."""
+    wl = synth.fsdp_shard(3, device=DEV)
+    shard = B.nt_shard_info(3, 8, wl.meta["shard_offset"], wl.meta["d_global"])
+    res, ref = run_and_check(wl, flags=FULL | B.NT_PARTIAL, shard=shard)
+    assert math.isnan(res["T"])
+
+
+def test_per_sample_full():
+    """b = 512 per-example gradients of a 2^24 vector with Student-t(3) noise: the row-walking kernel."""
+    wl = synth.per_sample(device=DEV)
+    assert wl.J == 512 and wl.d == 1 << 24
+    run_and_check(wl)
