@@ -57,20 +57,25 @@ class _Decision(ctypes.Structure):
 _lib = None
 
 
+def _bind(path: str):
+    """Load a build of the oracle and declare its prototypes."""
+    lib = ctypes.CDLL(path)
+    i64, dbl, vp = ctypes.c_int64, ctypes.c_double, ctypes.c_void_p
+    lib.nto_stats.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp]
+    lib.nto_stats.restype = ctypes.c_int
+    lib.nto_decide.argtypes = [dbl, dbl, dbl, i64, dbl, i64, i64, i64, ctypes.c_int32,
+                               ctypes.POINTER(_Decision)]
+    lib.nto_decide.restype = ctypes.c_int
+    lib.nto_adamw.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, dbl, dbl, dbl, dbl, dbl,
+                              i64, vp, vp, vp, vp]
+    lib.nto_adamw.restype = ctypes.c_int
+    return lib
+
+
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
-        i64, dbl, vp = ctypes.c_int64, ctypes.c_double, ctypes.c_void_p
-        lib.nto_stats.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp]
-        lib.nto_stats.restype = ctypes.c_int
-        lib.nto_decide.argtypes = [dbl, dbl, dbl, i64, dbl, i64, i64, i64, ctypes.c_int32,
-                                   ctypes.POINTER(_Decision)]
-        lib.nto_decide.restype = ctypes.c_int
-        lib.nto_adamw.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, dbl, dbl, dbl, dbl, dbl,
-                                  i64, vp, vp, vp, vp]
-        lib.nto_adamw.restype = ctypes.c_int
-        _lib = lib
+        _lib = _bind(build())
     return _lib
 
 

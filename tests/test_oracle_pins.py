@@ -306,6 +306,19 @@ def test_scale_row_permutation_and_shard_additivity():
     assert oracle.combine_chunks(parts) == pytest.approx((A, B, C), rel=1e-14)
 
 
+def test_long_sum_needs_compensation():
+    """One huge coordinate followed by many small ones: a plain running fp64 sum drops every small term."""
+    d = 1 + 4096
+    G = np.ones((2, d), dtype=np.float32)
+    G[:, 0] = 2.0 ** 27
+    A, B, C = oracle.stats(G)
+    assert A == 2.0 ** 55 + 2.0 * 4096          # exact; naive left-to-right summation returns 2^55
+    assert B == 2.0 ** 56 + 4.0 * 4096
+    assert C == 0.0
+    G[1, 1:] = 3.0                               # now C = 2 per small coordinate
+    assert oracle.stats(G)[2] == 2.0 * 4096
+
+
 def test_row_stride_is_honoured():
     wl = synth.make("t", 3, 100, sigma=1e-2, seed=4, with_state=False, ld=128)
     wl.grads[:, 100:] = 7.0  # padding must never be read
