@@ -94,6 +94,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="flat_1p5b")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink d (debugging only; the result is then not the headline)")
+    ap.add_argument("--mode", default="full", choices=["full", "stats", "adamw", "clipped"],
+                    help="full: the fused step (headline); stats / adamw: one half only; clipped: two-phase variant")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 28)
     ap.add_argument("--calib-copy-gib", type=int, default=0,
@@ -111,7 +113,13 @@ def main():
     torch.cuda.set_device(0)
     wl = make_workload(args.workload, dev, args.scale)
     h = wl.hyper
-    flags = B.NT_DO_STATS | B.NT_DO_ADAMW | (B.NT_PARTIAL if args.workload == "fsdp_shard" else 0)
+    flags = {"full": B.NT_DO_STATS | B.NT_DO_ADAMW, "stats": B.NT_DO_STATS, "adamw": B.NT_DO_ADAMW,
+             "clipped": B.NT_DO_STATS | B.NT_DO_ADAMW}[args.mode]
+    if args.workload == "fsdp_shard" and args.mode in ("full", "stats"):
+        flags |= B.NT_PARTIAL
+    # bytes per coordinate: J gradient reads; + read/write of w, m, v; the clipped variant also writes and re-reads gbar
+    bytes_per_param = wl.J * wl.grad_bytes + {"full": 24, "stats": 0, "adamw": 24, "clipped": 32}[args.mode]
+    gbar_buf = torch.empty(wl.d, dtype=torch.float32, device=dev) if args.mode == "clipped" else None
     hy = B.make_hyper(lr=h.lr, beta1=h.beta1, beta2=h.beta2, eps=h.eps, weight_decay=h.weight_decay, eta=h.eta,
                       step=h.step, b_k=h.b_k, b_max=h.b_max, round_to=h.round_to, ddof=h.ddof, flags=flags)
     workspace = torch.empty(B.normtest_workspace_bytes(wl.J, wl.d), dtype=torch.uint8, device=dev)
@@ -119,7 +127,11 @@ def main():
     stream = torch.cuda.current_stream()
 
     def step():
-        B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hy, workspace=workspace, result=result, stream=stream)
+        if args.mode == "clipped":
+            B.normtest_step_clipped(wl.grads, wl.w, wl.m, wl.v, gbar_buf, 1.0, hy, workspace=workspace,
+                                    result=result, stream=stream)
+        else:
+            B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hy, workspace=workspace, result=result, stream=stream)
 
     if args.calib_copy_gib > 0:
         src = torch.zeros(args.calib_copy_gib << 28, dtype=torch.float32, device=dev)
@@ -143,7 +155,7 @@ def main():
     ev_ms = [s.elapsed_time(e) for s, e in zip(starts, stops)]
     res = B.read_result(result).as_dict()
 
-    alg_bytes = wl.algorithmic_bytes()
+    alg_bytes = wl.d * bytes_per_param
     ms_per_step = wall * 1e3 / args.steps
     ev_avg = sum(ev_ms) / len(ev_ms)
     value = alg_bytes / (wall / args.steps) / 1e9
@@ -164,10 +176,14 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {
-            "workload": "%s: J=%d %s gradient rows, d=%d, fp32 w/m/v, stats+decision+fused AdamW in one pass" % (
-                wl.name, wl.J, "bf16" if wl.grad_bytes == 2 else "fp32", wl.d),
+            "workload": "%s: J=%d %s gradient rows, d=%d, fp32 w/m/v, %s" % (
+                wl.name, wl.J, "bf16" if wl.grad_bytes == 2 else "fp32", wl.d,
+                {"full": "stats+decision+fused AdamW in one pass", "stats": "statistics and decision only",
+                 "adamw": "mean + AdamW only (test skipped)",
+                 "clipped": "two-phase gradient-clipped step (stats+gbar, then AdamW)"}[args.mode]),
+            "mode": args.mode,
             "J": wl.J, "d": wl.d, "grad_dtype": "bf16" if wl.grad_bytes == 2 else "f32",
-            "bytes_per_param": wl.J * wl.grad_bytes + 24, "flags": flags,
+            "bytes_per_param": bytes_per_param, "flags": flags,
         },
         "result": {k: res[k] for k in ("T", "pass", "next_b", "status")},
         "roofline": {
@@ -180,10 +196,10 @@ def main():
             "launch_ms_avg": ev_avg,
             "launch_ms_min": min(ev_ms),
             "algorithmic_bytes": alg_bytes,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if args.scale == 1.0 else None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if (args.scale == 1.0 and args.mode == "full") else None,
         },
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.mode == "full":
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample)
     print(json.dumps(out))
 

@@ -87,13 +87,15 @@ typedef struct {
   double gbar_sq;          /* ||gbar||^2 = B/J^2                         (NaN if NT_PARTIAL or no stats)           */
   double var_l1;           /* C/(J - ddof)                                                                        */
   double T;                /* var_l1 / (eta^2 gbar_sq)                                                            */
+  double clip_coef;        /* factor applied to gbar before AdamW: 1 unless normtest_step_clipped cut the norm    */
   int64_t next_b;          /* b_{k+1}                                                                             */
   int32_t pass;            /* 1 iff not (T > b_k)                                                                 */
   uint32_t status;         /* NT_STATUS_* bits                                                                    */
 } nt_result;
 
-/* Number of coordinates per partial-sum tile for J rows.  Results are bit-identical for any split of
- * a vector into calls whose boundaries are multiples of this (same J, dtype and alignment class). */
+/* Alignment, in coordinates, of the partial-sum tiles for J rows (every tile size divides it).  Results are
+ * bit-identical for any split of a vector into calls whose boundaries are multiples of this, for the
+ * same J, dtype and flags. */
 int64_t normtest_tile_coords(int64_t J);
 
 /* Bytes of device workspace normtest_step needs for J rows of d coordinates (0 if J or d is invalid). */
@@ -130,6 +132,38 @@ int normtest_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int6
  */
 int normtest_combine(const nt_result* partials, int32_t n, int64_t J, const nt_hyper* hyper,
                      nt_result* out);
+
+/*
+ * Gradient-clipped step in two phases.  The paper's runs clip the global gradient norm (Sec. 5, training
+ * specifications; hyper-parameter tables: "gradient clipping 1.0"); Alg. 1 omits it and the paper gives no
+ * formula, so the usual convention is taken: gbar is scaled by c = min(1, max_norm / (||gbar|| + 1e-6)).
+ * ||gbar|| is only known after the whole statistics pass, so this cannot be one pass:
+ *   phase 1  statistics as in normtest_step, and gbar (fp32) stored to gbar_buf;
+ *   phase 2  AdamW on c * gbar, with c read from result_dev on the device (no host round trip).
+ * Arguments as in normtest_step; gbar_buf: device fp32[d], required; max_norm > 0 (<= 0: no clipping,
+ * c = 1, and w, m, v come out bit-identical to normtest_step).  hyper->flags must contain NT_DO_STATS and
+ * NT_DO_ADAMW and not NT_PARTIAL (a shard cannot know the global norm: see normtest_adamw_gbar).
+ * The test statistic uses the unclipped gbar.  result_dev->clip_coef reports c.
+ */
+int normtest_step_clipped(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld,
+                          float* w, float* m, float* v, float* gbar_buf, double max_norm,
+                          const nt_hyper* hyper, const nt_shard_info* shard,
+                          void* workspace, size_t workspace_bytes,
+                          nt_result* result_dev, void* hip_stream);
+
+/*
+ * Phase 2 on its own: AdamW (Alg. 1's update lines) on scale * gbar for a mean gradient that is already in
+ * device memory (gbar: fp32[d], e.g. written by an earlier NT_WRITE_GBAR call).  scale = grad_scale, times
+ * result_dev->clip_coef if result_dev (device or pinned host) is not NULL.  FSDP use: each shard runs
+ * normtest_step with NT_DO_STATS | NT_PARTIAL | NT_WRITE_GBAR, the host combines the partial sums, computes
+ * normtest_clip_coef and passes it here as grad_scale.  Only the AdamW fields and the step of hyper are read.
+ */
+int normtest_adamw_gbar(const float* gbar, int64_t d, float* w, float* m, float* v,
+                        const nt_hyper* hyper, double grad_scale, const nt_result* result_dev,
+                        void* hip_stream);
+
+/* Host helper: min(1, max_norm / (sqrt(gbar_sq) + 1e-6)); 1 if max_norm <= 0. */
+double normtest_clip_coef(double gbar_sq, double max_norm);
 
 /* Plain streaming copy of `bytes` bytes (device to device, 16-byte aligned, bytes % 16 == 0) with the
  * same load/store instructions as the step kernel: a yardstick for achievable HBM bandwidth and for

@@ -67,8 +67,10 @@ def _bind(path: str):
                                ctypes.POINTER(_Decision)]
     lib.nto_decide.restype = ctypes.c_int
     lib.nto_adamw.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, dbl, dbl, dbl, dbl, dbl,
-                              i64, vp, vp, vp, vp]
+                              i64, dbl, vp, vp, vp, vp]
     lib.nto_adamw.restype = ctypes.c_int
+    lib.nto_clip_coef.argtypes = [dbl, dbl]
+    lib.nto_clip_coef.restype = dbl
     return lib
 
 
@@ -149,8 +151,13 @@ def decide(A, B, C, J, eta, b_k, b_max=0, round_to=1, ddof=1) -> Decision:
     return Decision(out.gbar_sq, out.var_l1, out.T, int(out.next_b), bool(out.pass_), int(out.status))
 
 
-def adamw(G, w, m, v, lr, beta1, beta2, eps, weight_decay, step, want_gbar=False):
-    """One AdamW step on the mean of the rows of G; returns fp64 (w', m', v'[, gbar])."""
+def clip_coef(gbar_sq: float, max_norm: float) -> float:
+    """min(1, max_norm / (||gbar|| + 1e-6)); 1 when max_norm <= 0 (no clipping)."""
+    return float(_load().nto_clip_coef(gbar_sq, max_norm))
+
+
+def adamw(G, w, m, v, lr, beta1, beta2, eps, weight_decay, step, want_gbar=False, grad_scale=1.0):
+    """One AdamW step on grad_scale * (mean of the rows of G); returns fp64 (w', m', v'[, gbar])."""
     ptr, dtype, J, ld, n = _grad_args(G)
     for x in (w, m, v):
         if x.dtype != np.float32 or x.ndim != 1 or x.shape[0] != n or not x.flags.c_contiguous:
@@ -159,7 +166,7 @@ def adamw(G, w, m, v, lr, beta1, beta2, eps, weight_decay, step, want_gbar=False
     go = np.empty(n, dtype=np.float64) if want_gbar else None
     if n:
         rc = _load().nto_adamw(ptr, dtype, J, ld, n, w.ctypes.data, m.ctypes.data, v.ctypes.data,
-                               lr, beta1, beta2, eps, weight_decay, step,
+                               lr, beta1, beta2, eps, weight_decay, step, grad_scale,
                                wo.ctypes.data, mo.ctypes.data, vo.ctypes.data,
                                go.ctypes.data if want_gbar else None)
         if rc:

@@ -168,16 +168,31 @@ int nto_decide(double A, double B, double C, int64_t J, double eta, int64_t b_k,
 }
 
 /*
+ * Global-norm gradient clipping, used in the paper's runs (Sec. 5, training specifications; the
+ * hyper-parameter tables list "gradient clipping 1.0") but not part of Alg. 1.  The paper gives no
+ * formula; this is the usual convention: the whole gradient is scaled by
+ *   min(1, max_norm / (||gbar|| + 1e-6)).
+ * max_norm <= 0 means no clipping.
+ */
+double nto_clip_coef(double gbar_sq, double max_norm) {
+  double c;
+  if (!(max_norm > 0.0)) return 1.0;
+  c = max_norm / (sqrt(gbar_sq) + 1e-6);
+  return c < 1.0 ? c : 1.0;
+}
+
+/*
  * AdamW on the mean gradient for n coordinates (Alg. 1):
  *   m' = beta1 m + (1-beta1) gbar          v' = beta2 v + (1-beta2) gbar^2
  *   mhat = m'/(1-beta1^k)                  vhat = v'/(1-beta2^k)
  *   w' = (1 - lr*wd) w - lr * mhat / (sqrt(vhat) + eps)
  * w, m, v are the fp32 state before the step; outputs stay in fp64.
- * gbar_out (may be NULL) receives the mean gradient.
+ * grad_scale multiplies the mean gradient before it enters the moments (1 = Alg. 1 as written;
+ * nto_clip_coef(...) = the clipped variant).  gbar_out (may be NULL) receives the unscaled mean.
  */
 int nto_adamw(const void *grads, int dtype, int64_t J, int64_t ld, int64_t n, const float *w,
               const float *m, const float *v, double lr, double beta1, double beta2, double eps,
-              double wd, int64_t step, double *w_out, double *m_out, double *v_out,
+              double wd, int64_t step, double grad_scale, double *w_out, double *m_out, double *v_out,
               double *gbar_out) {
   double bc1, bc2;
   if (!grads || !w || !m || !v || !w_out || !m_out || !v_out || J < 1 || n < 0 || ld < n || step < 1 ||
@@ -186,11 +201,12 @@ int nto_adamw(const void *grads, int dtype, int64_t J, int64_t ld, int64_t n, co
   bc1 = 1.0 - pow(beta1, (double)step);
   bc2 = 1.0 - pow(beta2, (double)step);
   for (int64_t i = 0; i < n; ++i) {
-    double s = 0.0, gbar, mn, vn, mhat, vhat;
+    double s = 0.0, gbar, g, mn, vn, mhat, vhat;
     for (int64_t j = 0; j < J; ++j) s += widen(grads, dtype, j * ld + i);
     gbar = s / (double)J;
-    mn = beta1 * (double)m[i] + (1.0 - beta1) * gbar;
-    vn = beta2 * (double)v[i] + (1.0 - beta2) * gbar * gbar;
+    g = grad_scale * gbar;
+    mn = beta1 * (double)m[i] + (1.0 - beta1) * g;
+    vn = beta2 * (double)v[i] + (1.0 - beta2) * g * g;
     mhat = mn / bc1;
     vhat = vn / bc2;
     w_out[i] = (1.0 - lr * wd) * (double)w[i] - lr * mhat / (sqrt(vhat) + eps);

@@ -46,7 +46,7 @@ class nt_result(ctypes.Structure):
         ("A", ctypes.c_double), ("B", ctypes.c_double), ("C", ctypes.c_double),
         ("A_lo", ctypes.c_double), ("B_lo", ctypes.c_double), ("C_lo", ctypes.c_double),
         ("gbar_sq", ctypes.c_double), ("var_l1", ctypes.c_double), ("T", ctypes.c_double),
-        ("next_b", ctypes.c_int64), ("pass_", ctypes.c_int32), ("status", ctypes.c_uint32),
+        ("clip_coef", ctypes.c_double), ("next_b", ctypes.c_int64), ("pass_", ctypes.c_int32), ("status", ctypes.c_uint32),
     ]
 
     def as_dict(self) -> dict:
@@ -84,6 +84,14 @@ def lib(path: Optional[str] = None):
         L.normtest_combine.argtypes = [ctypes.POINTER(nt_result), ctypes.c_int32, i64,
                                        ctypes.POINTER(nt_hyper), ctypes.POINTER(nt_result)]
         L.normtest_combine.restype = ctypes.c_int
+        L.normtest_step_clipped.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, ctypes.c_double,
+                                            ctypes.POINTER(nt_hyper), ctypes.POINTER(nt_shard_info),
+                                            vp, ctypes.c_size_t, vp, vp]
+        L.normtest_step_clipped.restype = ctypes.c_int
+        L.normtest_adamw_gbar.argtypes = [vp, i64, vp, vp, vp, ctypes.POINTER(nt_hyper), ctypes.c_double, vp, vp]
+        L.normtest_adamw_gbar.restype = ctypes.c_int
+        L.normtest_clip_coef.argtypes = [ctypes.c_double, ctypes.c_double]
+        L.normtest_clip_coef.restype = ctypes.c_double
         L.normtest_calib_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.normtest_calib_copy.restype = ctypes.c_int
         L.normtest_strerror.argtypes = [ctypes.c_int]
@@ -162,6 +170,65 @@ def normtest_step(grads: torch.Tensor, w: Optional[torch.Tensor], m: Optional[to
     # keep the scratch alive until the stream has consumed it
     workspace.record_stream(stream)
     return result
+
+
+def normtest_step_clipped(grads: torch.Tensor, w: torch.Tensor, m: torch.Tensor, v: torch.Tensor,
+                          gbar_buf: torch.Tensor, max_norm: float, hyper: nt_hyper, *, d: Optional[int] = None,
+                          shard: Optional[nt_shard_info] = None, workspace: Optional[torch.Tensor] = None,
+                          result: Optional[torch.Tensor] = None,
+                          stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Two-phase gradient-clipped step (statistics + gbar, then AdamW on the clipped gbar); see normtest_step."""
+    if grads.dim() != 2 or (grads.shape[1] > 1 and grads.stride(1) != 1):
+        raise ValueError("grads must be (J, ld) with a contiguous last axis")
+    J = grads.shape[0]
+    ld = grads.stride(0) if J > 1 else grads.shape[1]
+    d = grads.shape[1] if d is None else d
+    dev = grads.device
+    if dev.type != "cuda":
+        raise ValueError("normtest_step_clipped needs device tensors; there is no CPU path")
+    for name, t in (("w", w), ("m", m), ("v", v), ("gbar_buf", gbar_buf)):
+        if t is None or t.dtype != torch.float32 or t.device != dev or not t.is_contiguous() or t.numel() < d:
+            raise ValueError("%s must be a contiguous float32 tensor of >= d elements on %s" % (name, dev))
+    if workspace is None:
+        workspace = torch.empty(max(normtest_workspace_bytes(J, d), 8), dtype=torch.uint8, device=dev)
+    if result is None:
+        result = torch.empty(RESULT_BYTES, dtype=torch.uint8, device=dev)
+    if stream is None:
+        stream = torch.cuda.current_stream(dev)
+    with torch.cuda.device(dev):
+        rc = lib().normtest_step_clipped(_ptr(grads), _gdtype(grads), J, d, ld, _ptr(w), _ptr(m), _ptr(v),
+                                         _ptr(gbar_buf), float(max_norm), ctypes.byref(hyper),
+                                         ctypes.byref(shard) if shard is not None else None,
+                                         _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                         _ptr(result), ctypes.c_void_p(stream.cuda_stream))
+    if rc != NT_OK:
+        raise NormtestError(rc, "normtest_step_clipped")
+    workspace.record_stream(stream)
+    return result
+
+
+def normtest_adamw_gbar(gbar: torch.Tensor, w: torch.Tensor, m: torch.Tensor, v: torch.Tensor, hyper: nt_hyper,
+                        grad_scale: float = 1.0, *, d: Optional[int] = None, result: Optional[torch.Tensor] = None,
+                        stream: Optional[torch.cuda.Stream] = None) -> None:
+    """AdamW on grad_scale (* result.clip_coef) * gbar for a mean gradient already in device memory."""
+    d = gbar.numel() if d is None else d
+    dev = gbar.device
+    if dev.type != "cuda":
+        raise ValueError("normtest_adamw_gbar needs device tensors; there is no CPU path")
+    for name, t in (("gbar", gbar), ("w", w), ("m", m), ("v", v)):
+        if t.dtype != torch.float32 or t.device != dev or not t.is_contiguous() or t.numel() < d:
+            raise ValueError("%s must be a contiguous float32 tensor of >= d elements on %s" % (name, dev))
+    if stream is None:
+        stream = torch.cuda.current_stream(dev)
+    with torch.cuda.device(dev):
+        rc = lib().normtest_adamw_gbar(_ptr(gbar), d, _ptr(w), _ptr(m), _ptr(v), ctypes.byref(hyper),
+                                       float(grad_scale), _ptr(result), ctypes.c_void_p(stream.cuda_stream))
+    if rc != NT_OK:
+        raise NormtestError(rc, "normtest_adamw_gbar")
+
+
+def normtest_clip_coef(gbar_sq: float, max_norm: float) -> float:
+    return float(lib().normtest_clip_coef(gbar_sq, max_norm))
 
 
 def read_result(result: torch.Tensor) -> nt_result:

@@ -25,13 +25,28 @@
 #include "normtest.h"
 
 #ifndef NT_BLOCK
-#define NT_BLOCK 1024         // threads per block of the streaming kernel
+#define NT_BLOCK 1024         // threads per block, J <= 16, fused step and AdamW-only
 #endif
-#ifndef NT_ITERS_SMALL
-#define NT_ITERS_SMALL 1      // block sweeps per partial-sum tile, J <= 16
+#ifndef NT_ITERS
+#define NT_ITERS 1            // block sweeps per partial-sum tile for that class
+#endif
+#ifndef NT_BLOCK_STATS
+#define NT_BLOCK_STATS 512    // threads per block, J <= 16, statistics only: read-only, few bytes per lane, so
+#endif                        // smaller blocks that each walk a longer tile measured best
+#ifndef NT_ITERS_STATS
+#define NT_ITERS_STATS 8
+#endif
+#ifndef NT_BLOCK_ADAMW
+#define NT_BLOCK_ADAMW 1024   // threads per block, J <= 16, AdamW only (test skipped)
+#endif
+#ifndef NT_ITERS_ADAMW
+#define NT_ITERS_ADAMW 1
+#endif
+#ifndef NT_BLOCK_LARGE
+#define NT_BLOCK_LARGE 256    // threads per block, J > 16 (rows are walked inside each sweep), all modes
 #endif
 #ifndef NT_ITERS_LARGE
-#define NT_ITERS_LARGE 1      // block sweeps per tile, J > 16 (rows are walked inside each sweep)
+#define NT_ITERS_LARGE 2
 #endif
 #ifndef NT_BLOCKS_PER_CU
 #define NT_BLOCKS_PER_CU 4096 // grid = min(tiles, CUs * this); blocks stride over tiles beyond that
@@ -51,6 +66,12 @@
 #ifndef NT_REUNPACK
 #define NT_REUNPACK 0         // 1: make the compiler widen the packed rows again in the second pass
 #endif
+#ifndef NT_XCD_MAP
+#define NT_XCD_MAP 0          // experiment: block-to-tile map that keeps each XCD on a contiguous range
+#endif
+#ifndef NT_STATE_FIRST
+#define NT_STATE_FIRST 0      // experiment: issue the w, m, v loads before the gradient rows
+#endif
 #ifndef NT_UNROLL
 #define NT_UNROLL 1           // unroll factor of the per-tile sweep loop
 #endif
@@ -59,8 +80,8 @@
 #endif
 
 #define NT_VEC 4              // coordinates per lane and sweep: 16-byte fp32 accesses, 8-byte bf16 row loads
-#define NT_TILE_SMALL (NT_BLOCK * NT_VEC * NT_ITERS_SMALL)
-#define NT_TILE_LARGE (NT_BLOCK * NT_VEC * NT_ITERS_LARGE)
+#define NT_TILE_MAX 16384      // every tile size divides this: the alignment that keeps shard results bit-identical
+#define NT_AUX_BLOCK 1024     // threads per block of the AdamW-from-gbar and copy kernels
 
 #define NT_PRAGMA_(x) _Pragma(#x)
 #define NT_PRAGMA_UNROLL(n) NT_PRAGMA_(unroll n)
@@ -184,7 +205,8 @@ __device__ inline double wave_sum(double x) {
 
 // Block partial of one tile -> partials[3*tile ..].  `buf` alternates between tiles so that one
 // barrier per tile is enough.
-__device__ inline void tile_reduce(double a, double b, double c, double (*red)[NT_BLOCK / 64][3], int buf,
+template <int BLOCK>
+__device__ inline void tile_reduce(double a, double b, double c, double (*red)[BLOCK / 64][3], int buf,
                                    double* partials, int64_t tile) {
   a = wave_sum(a);
   b = wave_sum(b);
@@ -199,7 +221,7 @@ __device__ inline void tile_reduce(double a, double b, double c, double (*red)[N
   if (threadIdx.x == 0) {
     double sa = red[buf][0][0], sb = red[buf][0][1], sc = red[buf][0][2];
 #pragma unroll
-    for (int wv = 1; wv < NT_BLOCK / 64; ++wv) {
+    for (int wv = 1; wv < BLOCK / 64; ++wv) {
       sa += red[buf][wv][0];
       sb += red[buf][wv][1];
       sc += red[buf][wv][2];
@@ -283,14 +305,14 @@ __device__ inline void coord_stats_generic(const StepParams& p, int64_t i, doubl
   }
 }
 
-template <class GT, int MODE>
-__device__ inline void guarded_tile(const StepParams& p, int64_t tile, int tile_coords, double (*red)[NT_BLOCK / 64][3],
+template <class GT, int MODE, int BLOCK>
+__device__ inline void guarded_tile(const StepParams& p, int64_t tile, int tile_coords, double (*red)[BLOCK / 64][3],
                                     int buf) {
   constexpr int VEC = GT::VEC;
-  const int iters = tile_coords / (NT_BLOCK * VEC);
+  const int iters = tile_coords / (BLOCK * VEC);
   double accA = 0.0, accB = 0.0, accC = 0.0;
   for (int it = 0; it < iters; ++it) {
-    const int64_t i0 = tile * (int64_t)tile_coords + ((int64_t)it * NT_BLOCK + threadIdx.x) * VEC;
+    const int64_t i0 = tile * (int64_t)tile_coords + ((int64_t)it * BLOCK + threadIdx.x) * VEC;
     float a[VEC], b[VEC], c[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
@@ -321,7 +343,7 @@ __device__ inline void guarded_tile(const StepParams& p, int64_t tile, int tile_
       accC += (double)lane_tree<VEC>(c);
     }
   }
-  if constexpr (MODE != MODE_ADAMW) tile_reduce(accA, accB, accC, red, buf, p.partials, tile);
+  if constexpr (MODE != MODE_ADAMW) tile_reduce<BLOCK>(accA, accB, accC, red, buf, p.partials, tile);
 }
 
 // AdamW on VEC coordinates whose state was loaded as 16-byte vectors, then the 16-byte stores.
@@ -361,21 +383,19 @@ __device__ inline void gbar_store(const StepParams& p, int64_t i0, const float* 
 // registers; needs 16-byte aligned rows and state and a tile that lies wholly below d.
 // The row sum is carried in fp64 so that the mean is correctly rounded even when the rows cancel.
 // ---------------------------------------------------------------------------------------------
-template <class GT, int J, int MODE, int TILE>
-__device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red)[NT_BLOCK / 64][3], int buf) {
+template <class GT, int J, int MODE, int BLOCK, int ITERS>
+__device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red)[BLOCK / 64][3], int buf) {
   constexpr int VEC = GT::VEC;
-  constexpr int ITERS = TILE / (NT_BLOCK * VEC);
-  static_assert(TILE % (NT_BLOCK * VEC) == 0, "tile must be a whole number of block sweeps");
+  constexpr int TILE = BLOCK * VEC * ITERS;
   const char* gbase = (const char*)p.grads;
   const int64_t row_bytes = p.ld * GT::ESIZE;
   double accA = 0.0, accB = 0.0, accC = 0.0;
   NT_PRAGMA_UNROLL(NT_UNROLL)
   for (int it = 0; it < ITERS; ++it) {
-    const int64_t i0 = tile * TILE + ((int64_t)it * NT_BLOCK + threadIdx.x) * VEC;
+    const int64_t i0 = tile * TILE + ((int64_t)it * BLOCK + threadIdx.x) * VEC;
     typename GT::raw_t raw[J];
-#pragma unroll
-    for (int j = 0; j < J; ++j) raw[j] = GT::ldraw(gbase + j * row_bytes + i0 * GT::ESIZE);
     u32x4 sw[VEC / 4], sm[VEC / 4], sv[VEC / 4];
+#if NT_STATE_FIRST
     if constexpr (MODE != MODE_STATS) {
 #pragma unroll
       for (int q = 0; q < VEC / 4; ++q) {
@@ -384,6 +404,19 @@ __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red
         sv[q] = ld16(p.v + i0 + 4 * q);
       }
     }
+#endif
+#pragma unroll
+    for (int j = 0; j < J; ++j) raw[j] = GT::ldraw(gbase + j * row_bytes + i0 * GT::ESIZE);
+#if !NT_STATE_FIRST
+    if constexpr (MODE != MODE_STATS) {
+#pragma unroll
+      for (int q = 0; q < VEC / 4; ++q) {
+        sw[q] = ld16(p.w + i0 + 4 * q);
+        sm[q] = ld16(p.m + i0 + 4 * q);
+        sv[q] = ld16(p.v + i0 + 4 * q);
+      }
+    }
+#endif
     double s[VEC];
     float gb[VEC];
 #pragma unroll
@@ -422,7 +455,7 @@ __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red
     if constexpr (MODE != MODE_STATS) adamw_store<VEC>(p, i0, gb, sw, sm, sv);
     if (p.gbar) gbar_store<VEC>(p, i0, gb);
   }
-  if constexpr (MODE != MODE_ADAMW) tile_reduce(accA, accB, accC, red, buf, p.partials, tile);
+  if constexpr (MODE != MODE_ADAMW) tile_reduce<BLOCK>(accA, accB, accC, red, buf, p.partials, tile);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -450,18 +483,17 @@ __device__ inline void chunk_accumulate(const typename GT::raw_t* raw, int nb, c
     }
 }
 
-template <class GT, int MODE, int TILE>
-__device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double (*red)[NT_BLOCK / 64][3], int buf) {
+template <class GT, int MODE, int BLOCK, int ITERS>
+__device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double (*red)[BLOCK / 64][3], int buf) {
   constexpr int VEC = GT::VEC;
-  constexpr int ITERS = TILE / (NT_BLOCK * VEC);
-  static_assert(TILE % (NT_BLOCK * VEC) == 0, "tile must be a whole number of block sweeps");
+  constexpr int TILE = BLOCK * VEC * ITERS;
   const char* gbase = (const char*)p.grads;
   const int64_t row_bytes = p.ld * GT::ESIZE;
   const int J = p.J;
   double accA = 0.0, accB = 0.0, accC = 0.0;
 #pragma unroll 1
   for (int it = 0; it < ITERS; ++it) {
-    const int64_t i0 = tile * TILE + ((int64_t)it * NT_BLOCK + threadIdx.x) * VEC;
+    const int64_t i0 = tile * TILE + ((int64_t)it * BLOCK + threadIdx.x) * VEC;
     const char* gp = gbase + i0 * GT::ESIZE;
     double S[VEC], sr[VEC];
     float M2[VEC], a[VEC], K[VEC], q[VEC];
@@ -523,7 +555,7 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
     }
     if (p.gbar) gbar_store<VEC>(p, i0, gb);
   }
-  if constexpr (MODE != MODE_ADAMW) tile_reduce(accA, accB, accC, red, buf, p.partials, tile);
+  if constexpr (MODE != MODE_ADAMW) tile_reduce<BLOCK>(accA, accB, accC, red, buf, p.partials, tile);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -532,21 +564,31 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
 // takes it first so that the slow tile overlaps with everything else.
 // J_T = 0 selects the J > 16 row-walking variant.
 // ---------------------------------------------------------------------------------------------
-template <class GT, int J_T, int MODE, int TILE>
-__global__ __launch_bounds__(NT_BLOCK, NT_WAVES_PER_EU) void k_step(StepParams p, int64_t nfull, int64_t ntiles) {
-  __shared__ double red[2][NT_BLOCK / 64][3];
+template <class GT, int J_T, int MODE, int BLOCK, int ITERS>
+__global__ __launch_bounds__(BLOCK, NT_WAVES_PER_EU) void k_step(StepParams p, int64_t nfull, int64_t ntiles) {
+  constexpr int TILE = BLOCK * GT::VEC * ITERS;
+  static_assert(NT_TILE_MAX % TILE == 0, "tile sizes must divide NT_TILE_MAX");
+  __shared__ double red[2][BLOCK / 64][3];
   int buf = 0;
   const int64_t nrest = ntiles - nfull;  // guarded tiles (0 or 1 on the aligned path)
+#if NT_XCD_MAP
+  // experiment: consecutive block ids land on different XCDs; give each XCD its own contiguous eighth
+  const int64_t per = (ntiles + 7) / 8;
+  for (int64_t t0 = blockIdx.x; t0 < per * 8; t0 += gridDim.x) {
+    const int64_t t = (t0 % 8) * per + t0 / 8;
+    if (t >= ntiles) continue;
+#else
   for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+#endif
     // rotate: the first nrest slots are the guarded tiles nfull.., then the fast tiles 0..nfull-1
     const int64_t tile = (t < nrest) ? nfull + t : t - nrest;
     if (tile < nfull) {
       if constexpr (J_T > 0)
-        fast_tile<GT, J_T, MODE, TILE>(p, tile, red, buf);
+        fast_tile<GT, J_T, MODE, BLOCK, ITERS>(p, tile, red, buf);
       else
-        fast_tile_multi<GT, MODE, TILE>(p, tile, red, buf);
+        fast_tile_multi<GT, MODE, BLOCK, ITERS>(p, tile, red, buf);
     } else {
-      guarded_tile<GT, MODE>(p, tile, TILE, red, buf);
+      guarded_tile<GT, MODE, BLOCK>(p, tile, TILE, red, buf);
     }
     buf ^= 1;
   }
@@ -572,10 +614,18 @@ __host__ __device__ inline dd dd_add(dd x, dd y) {
 struct DecideParams {
   int64_t J;
   double eta;
+  double max_norm;  // gradient-norm bound of the clipped variant, <= 0: none
   int64_t b_k, b_max, round_to;
   int32_t ddof;
   uint32_t flags;
 };
+
+// Global-norm clipping factor (training specifications of Sec. 5; usual convention with the 1e-6 guard).
+__host__ __device__ inline double clip_coef(double gbar_sq, double max_norm) {
+  if (!(max_norm > 0.0)) return 1.0;
+  const double c = max_norm / (sqrt(gbar_sq) + 1e-6);
+  return c < 1.0 ? c : 1.0;
+}
 
 // From the sums in r->A, r->B, r->C to ||gbar||^2, ||Var||_1, T, pass and next_b (Alg. 1: test
 // statistic, strict comparison with b_k, ceiling, rounding through micro-batch, minibatch and
@@ -587,6 +637,7 @@ __host__ __device__ inline void decide(const DecideParams& q, nt_result* r) {
   r->next_b = q.b_k;
   r->gbar_sq = r->B / (Jd * Jd);
   r->var_l1 = r->C / (double)(q.J - q.ddof);
+  r->clip_coef = clip_coef(r->gbar_sq, q.max_norm);
   if (!(__builtin_isfinite(r->A) && __builtin_isfinite(r->B) && __builtin_isfinite(r->C))) {
     r->status |= NT_STATUS_NONFINITE;
     r->T = __builtin_nan("");
@@ -711,6 +762,7 @@ __global__ __launch_bounds__(NT_FIN_THREADS) void k_finalize(const double* in, i
   if (!stats) {
     r.A = r.B = r.C = r.A_lo = r.B_lo = r.C_lo = nan;
     r.gbar_sq = r.var_l1 = r.T = nan;
+    r.clip_coef = 1.0;
     r.pass = 1;
     r.next_b = q.b_k;
     r.status = NT_STATUS_NO_STATS;
@@ -720,6 +772,7 @@ __global__ __launch_bounds__(NT_FIN_THREADS) void k_finalize(const double* in, i
     r.C = tot[2].hi; r.C_lo = tot[2].lo;
     if (q.flags & NT_PARTIAL) {
       r.gbar_sq = r.var_l1 = r.T = nan;
+      r.clip_coef = 1.0;
       r.pass = 1;
       r.next_b = q.b_k;
       r.status = NT_STATUS_PARTIAL_ONLY;
@@ -732,8 +785,35 @@ __global__ __launch_bounds__(NT_FIN_THREADS) void k_finalize(const double* in, i
   *out = r;
 }
 
-__global__ __launch_bounds__(NT_BLOCK) void k_copy16(f32x4* dst, const u32x4* src, int64_t n16) {
-  for (int64_t i = (int64_t)blockIdx.x * NT_BLOCK + threadIdx.x; i < n16; i += (int64_t)gridDim.x * NT_BLOCK) {
+// Phase 2 of the clipped variant: AdamW on scale * gbar, gbar read from memory.  One sweep per block,
+// 4 coordinates per lane; lanes whose 4 coordinates are not all below d, or unaligned buffers, go
+// element by element.
+__global__ __launch_bounds__(NT_AUX_BLOCK) void k_adamw_gbar(StepParams p, const float* gbar, float grad_scale,
+                                                         const nt_result* res, int aligned) {
+  float scale = grad_scale;
+  if (res) scale *= (float)res->clip_coef;
+  const int64_t i0 = ((int64_t)blockIdx.x * NT_AUX_BLOCK + threadIdx.x) * NT_VEC;
+  if (i0 >= p.d) return;
+  if (aligned && i0 + NT_VEC <= p.d) {
+    const u32x4 sg = ld16(gbar + i0);
+    u32x4 sw = ld16(p.w + i0), sm = ld16(p.m + i0), sv = ld16(p.v + i0);
+    float gb[NT_VEC];
+#pragma unroll
+    for (int e = 0; e < NT_VEC; ++e) gb[e] = scale * __builtin_bit_cast(float, (uint32_t)sg[e]);
+    adamw_store<NT_VEC>(p, i0, gb, &sw, &sm, &sv);
+  } else {
+    for (int64_t i = i0; i < i0 + NT_VEC && i < p.d; ++i) {
+      float w = p.w[i], m = p.m[i], v = p.v[i];
+      adamw_coord(p, scale * gbar[i], w, m, v);
+      p.w[i] = w;
+      p.m[i] = m;
+      p.v[i] = v;
+    }
+  }
+}
+
+__global__ __launch_bounds__(NT_AUX_BLOCK) void k_copy16(f32x4* dst, const u32x4* src, int64_t n16) {
+  for (int64_t i = (int64_t)blockIdx.x * NT_AUX_BLOCK + threadIdx.x; i < n16; i += (int64_t)gridDim.x * NT_AUX_BLOCK) {
     u32x4 x = ld_vec<NT_NT_COPY, u32x4>(src + i);
     f32x4 y = __builtin_bit_cast(f32x4, x);
 #if NT_NT_COPY
@@ -761,7 +841,23 @@ int cu_count() {
   return n;
 }
 
-inline int64_t tile_coords(int64_t J) { return J <= NT_JCHUNK ? NT_TILE_SMALL : NT_TILE_LARGE; }
+// Launch class of a call: block size and sweeps per tile.  Every tile is block * NT_VEC * sweeps
+// coordinates and divides NT_TILE_MAX.
+struct TileCfg {
+  int block, iters;
+  int64_t coords() const { return (int64_t)block * NT_VEC * iters; }
+};
+inline TileCfg tile_cfg(int64_t J, int mode) {
+  if (J > NT_JCHUNK) return {NT_BLOCK_LARGE, NT_ITERS_LARGE};
+  if (mode == MODE_STATS) return {NT_BLOCK_STATS, NT_ITERS_STATS};
+  if (mode == MODE_ADAMW) return {NT_BLOCK_ADAMW, NT_ITERS_ADAMW};
+  return {NT_BLOCK, NT_ITERS};
+}
+// smallest tile any mode uses for this J: sizes the workspace
+inline int64_t min_tile_coords(int64_t J) {
+  const int64_t a = tile_cfg(J, MODE_FULL).coords(), b = tile_cfg(J, MODE_STATS).coords();
+  return a < b ? a : b;
+}
 
 bool hyper_ok(const nt_hyper* h, int64_t J) {
   if (!h) return false;
@@ -785,16 +881,18 @@ bool hyper_ok(const nt_hyper* h, int64_t J) {
 
 template <class GT, int MODE>
 hipError_t launch_step(const StepParams& p, int64_t nfull, int64_t ntiles, int grid, hipStream_t st) {
-  constexpr int TS = NT_TILE_SMALL, TL = NT_TILE_LARGE;
-#define NT_CASE(JJ)                                                                                        \
-  case JJ:                                                                                                 \
-    hipLaunchKernelGGL((k_step<GT, JJ, MODE, TS>), dim3(grid), dim3(NT_BLOCK), 0, st, p, nfull, ntiles); \
+  constexpr int BS = (MODE == MODE_STATS) ? NT_BLOCK_STATS : (MODE == MODE_ADAMW) ? NT_BLOCK_ADAMW : NT_BLOCK;
+  constexpr int IS = (MODE == MODE_STATS) ? NT_ITERS_STATS : (MODE == MODE_ADAMW) ? NT_ITERS_ADAMW : NT_ITERS;
+#define NT_CASE(JJ)                                                                                      \
+  case JJ:                                                                                               \
+    hipLaunchKernelGGL((k_step<GT, JJ, MODE, BS, IS>), dim3(grid), dim3(BS), 0, st, p, nfull, ntiles);  \
     break;
   switch (p.J) {
     NT_CASE(2) NT_CASE(3) NT_CASE(4) NT_CASE(5) NT_CASE(6) NT_CASE(7) NT_CASE(8) NT_CASE(9)
     NT_CASE(10) NT_CASE(11) NT_CASE(12) NT_CASE(13) NT_CASE(14) NT_CASE(15) NT_CASE(16)
     default:
-      hipLaunchKernelGGL((k_step<GT, 0, MODE, TL>), dim3(grid), dim3(NT_BLOCK), 0, st, p, nfull, ntiles);
+      hipLaunchKernelGGL((k_step<GT, 0, MODE, NT_BLOCK_LARGE, NT_ITERS_LARGE>), dim3(grid), dim3(NT_BLOCK_LARGE), 0,
+                         st, p, nfull, ntiles);
   }
 #undef NT_CASE
   return hipGetLastError();
@@ -815,25 +913,41 @@ inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 extern "C" {
 
-int64_t normtest_tile_coords(int64_t J) { return J >= 2 ? tile_coords(J) : 0; }
+int64_t normtest_tile_coords(int64_t J) { return J >= 2 ? NT_TILE_MAX : 0; }
 
 size_t normtest_workspace_bytes(int64_t J, int64_t d) {
   if (J < 2 || d < 0) return 0;
-  const int64_t tc = tile_coords(J);
+  const int64_t tc = min_tile_coords(J);
   const int64_t ntiles = (d + tc - 1) / tc;
   const int64_t n = ntiles > 0 ? ntiles : 1;
   const int64_t ngroups = ntiles > NT_DIRECT_TILES ? (ntiles + NT_GROUP_TILES - 1) / NT_GROUP_TILES : 0;
   return (size_t)(n * 3 + ngroups * 6) * sizeof(double);
 }
 
-int normtest_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld, float* w, float* m,
-                  float* v, float* gbar_out, const nt_hyper* hyper, const nt_shard_info* shard, void* workspace,
-                  size_t workspace_bytes, nt_result* result_dev, void* hip_stream) {
+// AdamW constants in fp64 on the host, rounded once to fp32.
+static void fill_adamw_params(StepParams& p, const nt_hyper* hyper) {
+  const double bc1 = 1.0 - std::pow(hyper->beta1, (double)hyper->step);
+  const double bc2 = 1.0 - std::pow(hyper->beta2, (double)hyper->step);
+  p.beta1 = (float)hyper->beta1;
+  p.omb1 = (float)(1.0 - hyper->beta1);
+  p.beta2 = (float)hyper->beta2;
+  p.omb2 = (float)(1.0 - hyper->beta2);
+  p.decay = (float)(1.0 - hyper->lr * hyper->weight_decay);
+  p.step_size = (float)(hyper->lr / bc1);
+  p.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(bc2));
+  p.eps = (float)hyper->eps;
+}
+
+// Validation shared by normtest_step and normtest_step_clipped; `flags` are the flags the kernels
+// will run with.  Nothing is enqueued here.
+static int check_step_args(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld, const float* w,
+                           const float* m, const float* v, const float* gbar_out, uint32_t flags,
+                           const nt_hyper* hyper, const nt_shard_info* shard, const void* workspace,
+                           size_t workspace_bytes, const nt_result* result_dev) {
   if (gdtype != NT_F32 && gdtype != NT_BF16) return NT_ERR_UNSUPPORTED;
   if (J < 2 || J > (1 << 20) || d < 0 || ld < d) return NT_ERR_BAD_ARG;
   if (!hyper_ok(hyper, J) || !result_dev || !workspace) return NT_ERR_BAD_ARG;
   if (((uintptr_t)result_dev & 7u) || ((uintptr_t)workspace & 7u)) return NT_ERR_BAD_ARG;
-  const uint32_t flags = hyper->flags;
   if (d > 0 && !grads) return NT_ERR_BAD_ARG;
   if (d > 0 && (flags & NT_DO_ADAMW) && (!w || !m || !v)) return NT_ERR_BAD_ARG;
   if (d > 0 && (flags & NT_WRITE_GBAR) && !gbar_out) return NT_ERR_BAD_ARG;
@@ -847,11 +961,17 @@ int normtest_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int6
       return NT_ERR_BAD_ARG;
   }
   if (workspace_bytes < normtest_workspace_bytes(J, d)) return NT_ERR_WORKSPACE_TOO_SMALL;
+  return NT_OK;
+}
 
-  hipStream_t st = (hipStream_t)hip_stream;
-  const int64_t tc = tile_coords(J);
-  const int64_t ntiles = (d + tc - 1) / tc;
+// Enqueue the streaming kernel and the reduction/decision kernels.  Arguments are already validated.
+static int enqueue_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld, float* w, float* m,
+                        float* v, float* gbar_out, uint32_t flags, const nt_hyper* hyper, double max_norm,
+                        void* workspace, nt_result* result_dev, hipStream_t st) {
+  const int esize = gdtype == NT_F32 ? 4 : 2;
   const int mode = (flags & NT_DO_STATS) ? ((flags & NT_DO_ADAMW) ? MODE_FULL : MODE_STATS) : MODE_ADAMW;
+  const int64_t tc = tile_cfg(J, mode).coords();
+  const int64_t ntiles = (d + tc - 1) / tc;
 
   StepParams p;
   std::memset(&p, 0, sizeof(p));
@@ -865,19 +985,7 @@ int normtest_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int6
   p.gbar = (flags & NT_WRITE_GBAR) ? gbar_out : nullptr;
   p.partials = (double*)workspace;
   p.inv_J = 1.0 / (double)J;
-  if (flags & NT_DO_ADAMW) {
-    // scalar constants in fp64 on the host, rounded once to fp32
-    const double bc1 = 1.0 - std::pow(hyper->beta1, (double)hyper->step);
-    const double bc2 = 1.0 - std::pow(hyper->beta2, (double)hyper->step);
-    p.beta1 = (float)hyper->beta1;
-    p.omb1 = (float)(1.0 - hyper->beta1);
-    p.beta2 = (float)hyper->beta2;
-    p.omb2 = (float)(1.0 - hyper->beta2);
-    p.decay = (float)(1.0 - hyper->lr * hyper->weight_decay);
-    p.step_size = (float)(hyper->lr / bc1);
-    p.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(bc2));
-    p.eps = (float)hyper->eps;
-  }
+  if (flags & NT_DO_ADAMW) fill_adamw_params(p, hyper);
 
   if (ntiles > 0) {
     bool al = aligned16(grads) && ((ld * esize) % 16 == 0);
@@ -885,7 +993,12 @@ int normtest_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int6
     if (p.gbar) al = al && aligned16(p.gbar);
     const int64_t nfull = al ? d / tc : 0;
     const int64_t max_grid = (int64_t)cu_count() * NT_BLOCKS_PER_CU;
-    const int grid = (int)(ntiles < max_grid ? ntiles : max_grid);
+#if NT_XCD_MAP
+    const int64_t want_grid = ((ntiles + 7) / 8) * 8;
+#else
+    const int64_t want_grid = ntiles;
+#endif
+    const int grid = (int)(want_grid < max_grid ? want_grid : max_grid);
     const hipError_t e = (gdtype == NT_F32) ? launch_step_mode<F32>(mode, p, nfull, ntiles, grid, st)
                                             : launch_step_mode<BF16>(mode, p, nfull, ntiles, grid, st);
     if (e != hipSuccess) return hip_code(e);
@@ -894,6 +1007,7 @@ int normtest_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int6
   DecideParams q;
   q.J = J;
   q.eta = hyper->eta;
+  q.max_norm = max_norm;
   q.b_k = hyper->b_k;
   q.b_max = hyper->b_max;
   q.round_to = hyper->round_to;
@@ -912,6 +1026,71 @@ int normtest_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int6
   }
   return hip_code(hipGetLastError());
 }
+
+// Enqueue AdamW on scale * gbar (phase 2 of the clipped variant).  Arguments are already validated.
+static int enqueue_adamw_gbar(const float* gbar, int64_t d, float* w, float* m, float* v, const nt_hyper* hyper,
+                              double grad_scale, const nt_result* result_dev, hipStream_t st) {
+  if (d == 0) return NT_OK;
+  StepParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.d = d;
+  p.w = w;
+  p.m = m;
+  p.v = v;
+  fill_adamw_params(p, hyper);
+  const int aligned = aligned16(gbar) && aligned16(w) && aligned16(m) && aligned16(v);
+  const int64_t per_block = (int64_t)NT_AUX_BLOCK * NT_VEC;
+  const int64_t grid = (d + per_block - 1) / per_block;
+  hipLaunchKernelGGL(k_adamw_gbar, dim3((unsigned)grid), dim3(NT_AUX_BLOCK), 0, st, p, gbar, (float)grad_scale, result_dev,
+                     aligned);
+  return hip_code(hipGetLastError());
+}
+
+int normtest_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld, float* w, float* m,
+                  float* v, float* gbar_out, const nt_hyper* hyper, const nt_shard_info* shard, void* workspace,
+                  size_t workspace_bytes, nt_result* result_dev, void* hip_stream) {
+  if (!hyper) return NT_ERR_BAD_ARG;
+  const int rc = check_step_args(grads, gdtype, J, d, ld, w, m, v, gbar_out, hyper->flags, hyper, shard, workspace,
+                                 workspace_bytes, result_dev);
+  if (rc != NT_OK) return rc;
+  return enqueue_step(grads, gdtype, J, d, ld, w, m, v, gbar_out, hyper->flags, hyper, 0.0, workspace, result_dev,
+                      (hipStream_t)hip_stream);
+}
+
+int normtest_step_clipped(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld, float* w, float* m,
+                          float* v, float* gbar_buf, double max_norm, const nt_hyper* hyper,
+                          const nt_shard_info* shard, void* workspace, size_t workspace_bytes, nt_result* result_dev,
+                          void* hip_stream) {
+  if (!hyper || std::isnan(max_norm)) return NT_ERR_BAD_ARG;
+  const uint32_t need = NT_DO_STATS | NT_DO_ADAMW;
+  if ((hyper->flags & need) != need || (hyper->flags & NT_PARTIAL)) return NT_ERR_BAD_ARG;
+  // validate as the fused step with the mean written out (this also checks w, m, v and the AdamW scalars)
+  const int rc = check_step_args(grads, gdtype, J, d, ld, w, m, v, gbar_buf, hyper->flags | NT_WRITE_GBAR, hyper,
+                                 shard, workspace, workspace_bytes, result_dev);
+  if (rc != NT_OK) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int rc1 = enqueue_step(grads, gdtype, J, d, ld, nullptr, nullptr, nullptr, gbar_buf,
+                               NT_DO_STATS | NT_WRITE_GBAR, hyper, max_norm, workspace, result_dev, st);
+  if (rc1 != NT_OK) return rc1;
+  return enqueue_adamw_gbar(gbar_buf, d, w, m, v, hyper, 1.0, result_dev, st);
+}
+
+int normtest_adamw_gbar(const float* gbar, int64_t d, float* w, float* m, float* v, const nt_hyper* hyper,
+                        double grad_scale, const nt_result* result_dev, void* hip_stream) {
+  if (!hyper || d < 0 || !std::isfinite(grad_scale)) return NT_ERR_BAD_ARG;
+  if (hyper->step < 1 || !(hyper->lr >= 0.0) || !std::isfinite(hyper->lr) ||
+      !(hyper->beta1 >= 0.0 && hyper->beta1 < 1.0) || !(hyper->beta2 >= 0.0 && hyper->beta2 < 1.0) ||
+      !(hyper->eps >= 0.0) || !std::isfinite(hyper->eps) || !(hyper->weight_decay >= 0.0) ||
+      !std::isfinite(hyper->weight_decay))
+    return NT_ERR_BAD_ARG;
+  if (d > 0 && (!gbar || !w || !m || !v)) return NT_ERR_BAD_ARG;
+  if (((uintptr_t)gbar & 3u) || ((uintptr_t)w & 3u) || ((uintptr_t)m & 3u) || ((uintptr_t)v & 3u) ||
+      ((uintptr_t)result_dev & 7u))
+    return NT_ERR_BAD_ARG;
+  return enqueue_adamw_gbar(gbar, d, w, m, v, hyper, grad_scale, result_dev, (hipStream_t)hip_stream);
+}
+
+double normtest_clip_coef(double gbar_sq, double max_norm) { return clip_coef(gbar_sq, max_norm); }
 
 int normtest_combine(const nt_result* partials, int32_t n, int64_t J, const nt_hyper* hyper, nt_result* out) {
   if (!partials || !out || n < 1 || J < 2 || !hyper) return NT_ERR_BAD_ARG;
@@ -951,6 +1130,7 @@ int normtest_combine(const nt_result* partials, int32_t n, int64_t J, const nt_h
   q.b_k = hyper->b_k;
   q.b_max = hyper->b_max;
   q.round_to = hyper->round_to;
+  q.max_norm = 0.0;
   q.ddof = hyper->ddof;
   q.flags = NT_DO_STATS;
   decide(q, &r);
@@ -962,10 +1142,10 @@ int normtest_calib_copy(void* dst, const void* src, size_t bytes, void* hip_stre
   if (!dst || !src || !aligned16(dst) || !aligned16(src) || (bytes & 15u)) return NT_ERR_BAD_ARG;
   if (bytes == 0) return NT_OK;
   const int64_t n16 = (int64_t)(bytes / 16);
-  const int64_t want = (n16 + NT_BLOCK - 1) / NT_BLOCK;
+  const int64_t want = (n16 + NT_AUX_BLOCK - 1) / NT_AUX_BLOCK;
   const int64_t max_grid = (int64_t)cu_count() * NT_BLOCKS_PER_CU;
   const int grid = (int)(want < max_grid ? want : max_grid);
-  hipLaunchKernelGGL(k_copy16, dim3(grid), dim3(NT_BLOCK), 0, (hipStream_t)hip_stream, (f32x4*)dst,
+  hipLaunchKernelGGL(k_copy16, dim3(grid), dim3(NT_AUX_BLOCK), 0, (hipStream_t)hip_stream, (f32x4*)dst,
                      (const u32x4*)src, n16);
   return hip_code(hipGetLastError());
 }

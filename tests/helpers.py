@@ -106,7 +106,7 @@ def assert_state_close(name: str, got: np.ndarray, want: np.ndarray, rtol: float
 
 
 def oracle_adamw_check(grads, d, w0, m0, v0, w1, m1, v1, h: synth.Hyper, ranges=None,
-                       chunk: int = ORACLE_CHUNK, threads: int | None = None, gbar=None):
+                       chunk: int = ORACLE_CHUNK, threads: int | None = None, gbar=None, grad_scale: float = 1.0):
     """Compare the GPU's updated state (w1, m1, v1) with the oracle's AdamW on the pre-step state
     (w0, m0, v0), over all of [0, d) or over the given coordinate ranges.  rms is taken per range."""
     threads = n_threads() if threads is None else threads
@@ -118,7 +118,7 @@ def oracle_adamw_check(grads, d, w0, m0, v0, w1, m1, v1, h: synth.Hyper, ranges=
         G = synth.grads_as_numpy(grads, lo, hi)
         a = [t[lo:hi].cpu().numpy() for t in (w0, m0, v0)]
         out = oracle.adamw(G, a[0], a[1], a[2], h.lr, h.beta1, h.beta2, h.eps, h.weight_decay, h.step,
-                           want_gbar=gbar is not None)
+                           want_gbar=gbar is not None, grad_scale=grad_scale)
         for name, got, want in zip("wmv", (w1, m1, v1), out[:3]):
             assert_state_close("%s[%d:%d]" % (name, lo, hi), got[lo:hi].cpu().numpy(), want)
         if gbar is not None:

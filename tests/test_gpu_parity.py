@@ -203,9 +203,9 @@ def test_stats_only_leaves_state_untouched():
     # state pointers may be absent altogether
     res2 = gpu_step(wl.grads, None, None, None, wl.hyper, flags=B.NT_DO_STATS)
     assert res2 == res
-    # and the sums are the same bits as in the fused step
+    # the fused step adds the same per-lane fp32 terms, in fp64 but over differently sized tiles
     res3 = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper, flags=FULL)
-    assert (res3["A"], res3["B"], res3["C"]) == (res["A"], res["B"], res["C"])
+    assert (res3["A"], res3["B"], res3["C"]) == pytest.approx((res["A"], res["B"], res["C"]), rel=1e-13)
 
 
 def test_adamw_only_reports_no_stats():
@@ -280,6 +280,103 @@ def test_threshold_and_cap():
     wl2.hyper.b_k = 4096
     res, ref = full_parity(wl2)
     assert res["pass"] == 1 and res["next_b"] == 4096
+
+
+# ------------------------------------------------------------------ gradient-clipped two-phase variant
+
+def clipped_step(wl, max_norm, d=None):
+    d = wl.d if d is None else d
+    gbar = torch.full((max(d, 1),), 7.0, dtype=torch.float32, device=wl.grads.device)
+    res = B.normtest_step_clipped(wl.grads, wl.w, wl.m, wl.v, gbar, max_norm, hyper_of(wl.hyper), d=d)
+    torch.cuda.synchronize()
+    return B.read_result(res).as_dict(), gbar
+
+
+@pytest.mark.parametrize("J,gdtype,d", [(8, torch.bfloat16, 5 * 4096 + 123), (4, torch.float32, 1 << 20),
+                                        (40, torch.bfloat16, 3 * 4096 + 5), (16, torch.bfloat16, 4096)])
+def test_clipped_step_matches_oracle(J, gdtype, d):
+    wl = synth.make("t", J, d, gdtype=gdtype, sigma=1e-2, seed=21, device=DEV,
+                    hyper=synth.Hyper(b_k=64, round_to=J, step=4))
+    ref = H.oracle_full(wl.grads, d, J, wl.hyper)
+    norm = math.sqrt(ref.dec.gbar_sq)
+    for max_norm, clipped in ((0.5 * norm, True), (2.0 * norm, False)):
+        w0, m0, v0 = wl.w.clone(), wl.m.clone(), wl.v.clone()
+        res, gbar = clipped_step(wl, max_norm)
+        H.assert_stats_close(res, ref)                      # the test uses the unclipped mean
+        H.assert_decision_matches(res, ref, wl.hyper)
+        coef = oracle.clip_coef(ref.dec.gbar_sq, max_norm)
+        assert (coef < 1.0) == clipped
+        assert res["clip_coef"] == pytest.approx(coef, rel=1e-6)
+        H.oracle_adamw_check(wl.grads, d, w0, m0, v0, wl.w, wl.m, wl.v, wl.hyper, gbar=gbar, grad_scale=coef)
+
+
+def test_clipped_step_without_bound_equals_fused_step_bit_for_bit():
+    wl = synth.make("t", 8, 9 * 4096 + 77, gdtype=torch.bfloat16, seed=22, device=DEV)
+    state0 = (wl.w.clone(), wl.m.clone(), wl.v.clone())
+    fused = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper)
+    fused_state = (wl.w.clone(), wl.m.clone(), wl.v.clone())
+    for max_norm in (0.0, 1e30):
+        for t, s in zip((wl.w, wl.m, wl.v), state0):
+            t.copy_(s)
+        res, _ = clipped_step(wl, max_norm)
+        assert res["clip_coef"] == 1.0
+        for k in ("A", "B", "C", "T"):
+            assert res[k] == pytest.approx(fused[k], rel=1e-13), k
+        for k in ("next_b", "pass", "status"):
+            assert res[k] == fused[k], k
+        for a, b in zip((wl.w, wl.m, wl.v), fused_state):
+            assert torch.equal(a, b)
+
+
+def test_clipped_shards_via_host_combine_equal_one_call():
+    """FSDP flow: per-shard statistics with the mean written out, host combine, then AdamW on each shard
+    with the host-computed factor; same bits as one clipped call over the whole vector."""
+    J = 16
+    tc = B.normtest_tile_coords(J)
+    d = 6 * tc + 1001
+    wl = synth.make("t", J, d, gdtype=torch.bfloat16, sigma=1e-2, seed=23, device=DEV)
+    state0 = (wl.w.clone(), wl.m.clone(), wl.v.clone())
+    ref = H.oracle_full(wl.grads, d, J, wl.hyper)
+    max_norm = 0.3 * math.sqrt(ref.dec.gbar_sq)
+    whole, gbar_whole = clipped_step(wl, max_norm)
+    whole_state = (wl.w.clone(), wl.m.clone(), wl.v.clone())
+    for t, s in zip((wl.w, wl.m, wl.v), state0):
+        t.copy_(s)
+    cuts = [0, 2 * tc, 5 * tc, d]
+    gbar = torch.zeros(d, dtype=torch.float32, device=DEV)
+    parts = []
+    flags = B.NT_DO_STATS | B.NT_PARTIAL | B.NT_WRITE_GBAR
+    for lo, hi in zip(cuts[:-1], cuts[1:]):
+        r = B.normtest_step(wl.grads[:, lo:hi], None, None, None, hyper_of(wl.hyper, flags), gbar_out=gbar[lo:hi])
+        torch.cuda.synchronize()
+        parts.append(B.read_result(r))
+    comb = B.normtest_combine(parts, J, hyper_of(wl.hyper))
+    coef = B.normtest_clip_coef(comb.gbar_sq, max_norm)
+    assert coef == whole["clip_coef"] and coef < 1.0
+    assert torch.equal(gbar, gbar_whole)
+    for lo, hi in zip(cuts[:-1], cuts[1:]):
+        B.normtest_adamw_gbar(gbar[lo:hi], wl.w[lo:hi], wl.m[lo:hi], wl.v[lo:hi], hyper_of(wl.hyper), coef)
+    torch.cuda.synchronize()
+    for a, b in zip((wl.w, wl.m, wl.v), whole_state):
+        assert torch.equal(a, b)
+    assert (comb.T, comb.next_b, comb.pass_) == (whole["T"], whole["next_b"], whole["pass"])
+
+
+def test_adamw_gbar_misaligned_matches_aligned():
+    d = 4096 + 333
+    wl = synth.make("t", 4, d, seed=24, device=DEV)
+    gbar = torch.randn(d + 1, device=DEV) * 1e-2
+    ref = [t.clone() for t in (wl.w, wl.m, wl.v)]
+    B.normtest_adamw_gbar(gbar[:d].clone(), ref[0], ref[1], ref[2], hyper_of(wl.hyper), 0.75)
+    off = [torch.zeros(d + 1, device=DEV)[1:] for _ in range(3)]
+    for t, s in zip(off, (wl.w, wl.m, wl.v)):
+        t.copy_(s)
+    g1 = gbar.clone()
+    g1[1:] = gbar[:d]
+    B.normtest_adamw_gbar(g1[1:], off[0], off[1], off[2], hyper_of(wl.hyper), 0.75, d=d)
+    torch.cuda.synchronize()
+    for a, b in zip(off, ref):
+        assert torch.equal(a, b)
 
 
 def test_calib_copy():

@@ -24,7 +24,8 @@ def declared_functions():
 def test_every_declared_symbol_is_exported():
     names = declared_functions()
     assert {"normtest_step", "normtest_combine", "normtest_workspace_bytes", "normtest_tile_coords",
-            "normtest_strerror", "normtest_calib_copy"} <= set(names)
+            "normtest_strerror", "normtest_calib_copy", "normtest_step_clipped", "normtest_adamw_gbar",
+            "normtest_clip_coef"} <= set(names)
     L = B.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -32,20 +33,21 @@ def test_every_declared_symbol_is_exported():
 
 def test_struct_layouts_match_header():
     assert ctypes.sizeof(B.nt_hyper) == 6 * 8 + 4 * 8 + 4 + 4
-    assert ctypes.sizeof(B.nt_result) == 9 * 8 + 8 + 4 + 4
+    assert ctypes.sizeof(B.nt_result) == 10 * 8 + 8 + 4 + 4
     assert ctypes.sizeof(B.nt_shard_info) == 4 + 4 + 8 + 8
 
 
 def test_workspace_and_tiles():
     for J in (2, 8, 16, 17, 512):
         tc = B.normtest_tile_coords(J)
-        assert tc > 0 and tc % 4 == 0
+        assert tc == 16384
         prev = 0
         for d in (0, 1, tc, tc + 1, 5000 * tc, 1_500_000_000):
-            ntiles = max(1, -(-d // tc))
             need = B.normtest_workspace_bytes(J, d)
-            # three doubles per tile, plus a small second level for long vectors
-            assert 24 * ntiles <= need <= 24 * ntiles + 48 * (ntiles // 1024 + 1)
+            # three doubles per tile; tiles are at most tc and at least 1024 coordinates; plus a small second level
+            lo = 24 * max(1, -(-d // tc))
+            hi = 24 * max(1, -(-d // 1024))
+            assert lo <= need <= hi + hi // 256 + 64
             assert need >= prev and need % 8 == 0
             prev = need
     assert B.normtest_tile_coords(1) == 0
@@ -89,6 +91,44 @@ def test_bad_arguments_are_rejected_before_any_launch():
     # stats-only calls do not need w, m, v: this one gets past validation only to fail on the workspace
     assert _call(w=None, m=None, v=None, hyper=B.make_hyper(b_k=32, flags=B.NT_DO_STATS), ws_bytes=0) \
         == B.NT_ERR_WORKSPACE_TOO_SMALL
+
+
+def test_clipped_entry_points_validate_before_launch():
+    L = B.lib()
+    hy = B.make_hyper(step=1, b_k=32, flags=FULL)
+    args = lambda **kw: dict(dict(grads=0x1000, gdtype=B.NT_F32, J=4, d=64, ld=64, w=0x2000, m=0x3000, v=0x4000,
+                                  gbar=0x7000, max_norm=1.0, hyper=hy, ws=0x5000, ws_bytes=1 << 20,
+                                  result=0x6000), **kw)
+
+    def call(a):
+        return L.normtest_step_clipped(a["grads"], a["gdtype"], a["J"], a["d"], a["ld"], a["w"], a["m"], a["v"],
+                                       a["gbar"], a["max_norm"], ctypes.byref(a["hyper"]), None, a["ws"],
+                                       a["ws_bytes"], a["result"], None)
+
+    bad = B.NT_ERR_BAD_ARG
+    assert call(args(gbar=None)) == bad
+    assert call(args(w=None)) == bad
+    assert call(args(J=1)) == bad
+    assert call(args(max_norm=math.nan)) == bad
+    assert call(args(hyper=B.make_hyper(step=1, b_k=32, flags=B.NT_DO_STATS))) == bad          # needs AdamW too
+    assert call(args(hyper=B.make_hyper(step=1, b_k=32, flags=FULL | B.NT_PARTIAL))) == bad     # no global norm in a shard
+    assert call(args(ws_bytes=0)) == B.NT_ERR_WORKSPACE_TOO_SMALL
+    # phase 2 alone
+    f = L.normtest_adamw_gbar
+    assert f(None, 64, 0x2000, 0x3000, 0x4000, ctypes.byref(hy), 1.0, None, None) == bad
+    assert f(0x7000, -1, 0x2000, 0x3000, 0x4000, ctypes.byref(hy), 1.0, None, None) == bad
+    assert f(0x7000, 64, 0x2000, 0x3000, 0x4000, ctypes.byref(hy), math.inf, None, None) == bad
+    assert f(0x7002, 64, 0x2000, 0x3000, 0x4000, ctypes.byref(hy), 1.0, None, None) == bad
+    assert f(0x7000, 64, 0x2000, 0x3000, 0x4000, ctypes.byref(B.make_hyper(step=0)), 1.0, None, None) == bad
+    assert f(0x7000, 0, None, None, None, ctypes.byref(hy), 1.0, None, None) == B.NT_OK               # d = 0: nothing to do
+
+
+def test_clip_coef_matches_oracle():
+    for gsq, mx in ((4.0, 1.0), (0.25, 1.0), (1.0, 1.0), (0.0, 1.0), (9.0, 0.0), (9.0, -1.0), (1e-30, 1e-3),
+                    (math.inf, 1.0)):
+        assert B.normtest_clip_coef(gsq, mx) == oracle.clip_coef(gsq, mx)
+    assert B.normtest_clip_coef(4.0, 1.0) == pytest.approx(1.0 / (2.0 + 1e-6), rel=1e-15)
+    assert B.normtest_clip_coef(0.25, 1.0) == 1.0
 
 
 def test_strerror():

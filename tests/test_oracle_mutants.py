@@ -33,8 +33,13 @@ MUTANTS = [
     ("no_cap", "if (b_max > 0 && nb > b_max) {", "if (0) {"),
     ("cap_may_shrink", "if (nb < b_k) nb = b_k;", ""),
     ("zero_norm_passes", "out->T = INFINITY;\n      out->pass = 0;", "out->T = INFINITY;\n      out->pass = 1;"),
-    ("m_weights_swapped", "mn = beta1 * (double)m[i] + (1.0 - beta1) * gbar;", "mn = (1.0 - beta1) * (double)m[i] + beta1 * gbar;"),
-    ("v_not_squared", "vn = beta2 * (double)v[i] + (1.0 - beta2) * gbar * gbar;", "vn = beta2 * (double)v[i] + (1.0 - beta2) * gbar;"),
+    ("m_weights_swapped", "mn = beta1 * (double)m[i] + (1.0 - beta1) * g;", "mn = (1.0 - beta1) * (double)m[i] + beta1 * g;"),
+    ("v_not_squared", "vn = beta2 * (double)v[i] + (1.0 - beta2) * g * g;", "vn = beta2 * (double)v[i] + (1.0 - beta2) * g;"),
+    ("scale_ignored", "g = grad_scale * gbar;", "g = gbar;"),
+    ("scale_only_first_moment", "vn = beta2 * (double)v[i] + (1.0 - beta2) * g * g;", "vn = beta2 * (double)v[i] + (1.0 - beta2) * gbar * gbar;"),
+    ("clip_never", "return c < 1.0 ? c : 1.0;", "return 1.0;"),
+    ("clip_always", "return c < 1.0 ? c : 1.0;", "return c;"),
+    ("clip_uses_squared_norm", "c = max_norm / (sqrt(gbar_sq) + 1e-6);", "c = max_norm / (gbar_sq + 1e-6);"),
     ("bias1_uses_beta2", "bc1 = 1.0 - pow(beta1, (double)step);", "bc1 = 1.0 - pow(beta2, (double)step);"),
     ("bias2_missing", "vhat = vn / bc2;", "vhat = vn;"),
     ("bias1_missing", "mhat = mn / bc1;", "mhat = mn;"),
@@ -42,7 +47,7 @@ MUTANTS = [
     ("no_weight_decay", "w_out[i] = (1.0 - lr * wd) * (double)w[i]", "w_out[i] = (double)w[i]"),
     ("decay_not_scaled_by_lr", "w_out[i] = (1.0 - lr * wd) * (double)w[i]", "w_out[i] = (1.0 - wd) * (double)w[i]"),
     ("update_sign", "(double)w[i] - lr * mhat", "(double)w[i] + lr * mhat"),
-    ("adamw_mean_not_divided", "gbar = s / (double)J;\n    mn =", "gbar = s;\n    mn ="),
+    ("adamw_mean_not_divided", "gbar = s / (double)J;\n    g =", "gbar = s;\n    g ="),
     ("compensation_dropped", "s[1] += (s[0] - t) + x;", "s[1] += 0.0;"),
 ]
 
@@ -73,6 +78,7 @@ def battery():
         lambda: P.test_zero_variance_when_rows_identical(4),
         P.test_scale_row_permutation_and_shard_additivity,
         P.test_long_sum_needs_compensation,
+        P.test_clipped_step_matches_library_clipping,
     ]
     return checks
 

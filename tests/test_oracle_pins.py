@@ -259,6 +259,37 @@ def test_matches_library_adamw_over_steps():
         w, m, v = wo.astype(np.float32), mo.astype(np.float32), vo.astype(np.float32)
 
 
+def test_clipped_step_matches_library_clipping():
+    """Global-norm clipping (Sec. 5 training specifications) against torch's clip_grad_norm_ followed by
+    torch.optim.AdamW, in fp64: one case where the norm exceeds the bound and one where it does not."""
+    d, J = 300, 4
+    hp = dict(lr=4e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    rng = np.random.default_rng(11)
+    for gscale, max_norm, expect_clipped in ((1.0, 1.0, True), (1e-3, 1.0, False), (1.0, 0.0, False)):
+        G = (gscale * rng.standard_normal((J, d))).astype(np.float32)
+        w = (0.02 * rng.standard_normal(d)).astype(np.float32)
+        m = (0.02 * rng.standard_normal(d)).astype(np.float32)
+        v = ((0.02 * rng.standard_normal(d)) ** 2).astype(np.float32)
+        A, B, C = oracle.stats(G)
+        coef = oracle.clip_coef(B / J**2, max_norm)
+        assert (coef < 1.0) == expect_clipped
+        wo, mo, vo = oracle.adamw(G, w, m, v, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"],
+                                  hp["weight_decay"], 5, grad_scale=coef)
+        p = torch.nn.Parameter(torch.from_numpy(w).double())
+        opt = torch.optim.AdamW([p], lr=hp["lr"], betas=(hp["beta1"], hp["beta2"]), eps=hp["eps"],
+                                weight_decay=hp["weight_decay"])
+        opt.state[p] = {"step": torch.tensor(4.0), "exp_avg": torch.from_numpy(m).double(),
+                        "exp_avg_sq": torch.from_numpy(v).double()}
+        p.grad = torch.from_numpy(G.astype(np.float64).mean(axis=0))
+        if max_norm > 0:
+            total = torch.nn.utils.clip_grad_norm_([p], max_norm)
+            assert float(total) == pytest.approx(math.sqrt(B) / J, rel=1e-12)
+        opt.step()
+        np.testing.assert_allclose(wo, p.detach().numpy(), rtol=1e-11, atol=1e-18)
+        np.testing.assert_allclose(mo, opt.state[p]["exp_avg"].numpy(), rtol=1e-11, atol=1e-300)
+        np.testing.assert_allclose(vo, opt.state[p]["exp_avg_sq"].numpy(), rtol=1e-11, atol=1e-300)
+
+
 def test_adamw_first_step_is_a_sign_step():
     """m = v = 0, k = 1: mhat = gbar, vhat = gbar^2, so w' = (1 - lr wd) w - lr gbar / (|gbar| + eps)."""
     d, J = 1031, 8
