@@ -153,7 +153,8 @@ def normtest_step(grads: torch.Tensor, w: Optional[torch.Tensor], m: Optional[to
             if t.dtype != torch.float32 or t.device != dev or not t.is_contiguous() or t.numel() < d:
                 raise ValueError("%s must be a contiguous float32 tensor of >= d elements on %s" % (name, dev))
     need = normtest_workspace_bytes(J, d)
-    if workspace is None:
+    own_workspace = workspace is None
+    if own_workspace:
         workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=dev)
     if result is None:
         result = torch.empty(RESULT_BYTES, dtype=torch.uint8, device=dev)
@@ -167,8 +168,8 @@ def normtest_step(grads: torch.Tensor, w: Optional[torch.Tensor], m: Optional[to
                                  _ptr(result), ctypes.c_void_p(stream.cuda_stream))
     if rc != NT_OK:
         raise NormtestError(rc, "normtest_step")
-    # keep the scratch alive until the stream has consumed it
-    workspace.record_stream(stream)
+    if own_workspace:
+        workspace.record_stream(stream)   # keep the scratch alive until the stream has consumed it
     return result
 
 
@@ -189,7 +190,8 @@ def normtest_step_clipped(grads: torch.Tensor, w: torch.Tensor, m: torch.Tensor,
     for name, t in (("w", w), ("m", m), ("v", v), ("gbar_buf", gbar_buf)):
         if t is None or t.dtype != torch.float32 or t.device != dev or not t.is_contiguous() or t.numel() < d:
             raise ValueError("%s must be a contiguous float32 tensor of >= d elements on %s" % (name, dev))
-    if workspace is None:
+    own_workspace = workspace is None
+    if own_workspace:
         workspace = torch.empty(max(normtest_workspace_bytes(J, d), 8), dtype=torch.uint8, device=dev)
     if result is None:
         result = torch.empty(RESULT_BYTES, dtype=torch.uint8, device=dev)
@@ -203,7 +205,8 @@ def normtest_step_clipped(grads: torch.Tensor, w: torch.Tensor, m: torch.Tensor,
                                          _ptr(result), ctypes.c_void_p(stream.cuda_stream))
     if rc != NT_OK:
         raise NormtestError(rc, "normtest_step_clipped")
-    workspace.record_stream(stream)
+    if own_workspace:
+        workspace.record_stream(stream)
     return result
 
 

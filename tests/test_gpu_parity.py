@@ -379,6 +379,79 @@ def test_adamw_gbar_misaligned_matches_aligned():
         assert torch.equal(a, b)
 
 
+# ------------------------------------------------------------------ memory safety and graph capture
+
+@pytest.mark.parametrize("J,gdtype,flags", [(8, torch.bfloat16, FULL), (4, torch.float32, FULL),
+                                            (33, torch.bfloat16, FULL), (8, torch.bfloat16, B.NT_DO_STATS),
+                                            (16, torch.bfloat16, B.NT_DO_ADAMW)])
+def test_canaries_around_every_buffer_survive(J, gdtype, flags):
+    """Every buffer the library may write sits between guard words; after a step (ragged d, with and
+    without alignment) the guards and everything past d are untouched."""
+    d = 2 * 16384 + 3001
+    guard = 64
+    for off in (0, 1):                                     # off = 1 breaks 16-byte alignment: guarded kernel path
+        wl = synth.make("t", J, d, gdtype=gdtype, seed=31, device=DEV)
+        bufs = {}
+        for name, src in (("w", wl.w), ("m", wl.m), ("v", wl.v), ("gbar", torch.zeros(d, device=DEV))):
+            big = torch.full((guard + off + d + guard,), 123.25, dtype=torch.float32, device=DEV)
+            big[guard + off:guard + off + d] = src
+            bufs[name] = big
+        need = B.normtest_workspace_bytes(J, d)
+        ws = torch.full((guard * 8 + need + guard * 8,), 0x5A, dtype=torch.uint8, device=DEV)
+        resbuf = torch.full((guard * 8 + B.RESULT_BYTES + guard * 8,), 0x5A, dtype=torch.uint8, device=DEV)
+        view = lambda n: bufs[n][guard + off:guard + off + d]
+        res = B.normtest_step(wl.grads, view("w"), view("m"), view("v"), hyper_of(wl.hyper, flags | B.NT_WRITE_GBAR),
+                              gbar_out=view("gbar"), workspace=ws[guard * 8:guard * 8 + need],
+                              result=resbuf[guard * 8:guard * 8 + B.RESULT_BYTES])
+        torch.cuda.synchronize()
+        for name, big in bufs.items():
+            assert bool((big[:guard + off] == 123.25).all()) and bool((big[guard + off + d:] == 123.25).all()), name
+        assert bool((ws[:guard * 8] == 0x5A).all()) and bool((ws[guard * 8 + need:] == 0x5A).all())
+        assert bool((resbuf[:guard * 8] == 0x5A).all()) and bool((resbuf[guard * 8 + B.RESULT_BYTES:] == 0x5A).all())
+        r = B.read_result(res)
+        assert r.status in (0, B.NT_STATUS_NO_STATS)
+
+
+def test_step_can_be_captured_in_a_hip_graph():
+    """The step allocates nothing and records only kernel launches, so it can be captured; every replay,
+    with eager work and synchronisation in between, must reproduce the eager result bit for bit."""
+    wl = synth.make("t", 8, 5 * 16384 + 99, gdtype=torch.bfloat16, seed=32, device=DEV)
+    state0 = [t.clone() for t in (wl.w, wl.m, wl.v)]
+    hy = hyper_of(wl.hyper)
+    ws = torch.empty(B.normtest_workspace_bytes(wl.J, wl.d), dtype=torch.uint8, device=DEV)
+    result = torch.zeros(B.RESULT_BYTES, dtype=torch.uint8, device=DEV)
+    # eager reference: two consecutive steps
+    eager = []
+    for _ in range(2):
+        B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hy, workspace=ws, result=result)
+        torch.cuda.synchronize()
+        eager.append((B.read_result(result).as_dict(), [t.clone() for t in (wl.w, wl.m, wl.v)]))
+    for t, s in zip((wl.w, wl.m, wl.v), state0):
+        t.copy_(s)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hy, workspace=ws, result=result, stream=side)   # warm-up
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hy, workspace=ws, result=result,
+                        stream=torch.cuda.current_stream())
+    for rounds in range(2):
+        for t, s in zip((wl.w, wl.m, wl.v), state0):
+            t.copy_(s)
+        for k in range(2):
+            result.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            got = B.read_result(result).as_dict()
+            assert got == eager[k][0]
+            for a, b in zip((wl.w, wl.m, wl.v), eager[k][1]):
+                assert torch.equal(a, b)
+            _ = (torch.randn(1 << 16, device=DEV) * 2).sum().item()        # unrelated eager work between replays
+
+
 def test_calib_copy():
     src = torch.randn(1 << 20, device=DEV)
     dst = torch.zeros_like(src)

@@ -92,11 +92,11 @@ def first_failure(checks):
     return None
 
 
-def compile_variant(src_text: str, out_path: str) -> str:
+def compile_variant(src_text: str, out_path: str, extra=()) -> str:
     c_path = out_path[:-3] + ".c"
     with open(c_path, "w") as f:
         f.write(src_text)
-    subprocess.run(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fno-fast-math", "-ffp-contract=off",
+    subprocess.run(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fno-fast-math", "-ffp-contract=off", *extra,
                     "-o", out_path, c_path, "-lm"], check=True)
     return out_path
 
@@ -111,6 +111,14 @@ def swap_oracle(monkeypatch):
 def test_unmodified_source_passes_every_pin(tmp_path, swap_oracle):
     swap_oracle(compile_variant(open(SRC).read(), str(tmp_path / "clean.so")))
     assert first_failure(battery()) is None
+
+
+def test_oracle_is_clean_under_the_undefined_behaviour_sanitizer(tmp_path, swap_oracle, capfd):
+    """The whole pin battery on a -fsanitize=undefined build of the oracle: no report may be printed."""
+    swap_oracle(compile_variant(open(SRC).read(), str(tmp_path / "ubsan.so"), extra=("-g", "-fsanitize=undefined")))
+    assert first_failure(battery()) is None
+    err = capfd.readouterr().err
+    assert "runtime error" not in err, err
 
 
 @pytest.mark.parametrize("name,find,repl", MUTANTS, ids=[m[0] for m in MUTANTS])
