@@ -63,14 +63,8 @@
 #ifndef NT_NT_COPY
 #define NT_NT_COPY 1          // nontemporal hint in the calibration copy kernel
 #endif
-#ifndef NT_REUNPACK
-#define NT_REUNPACK 0         // 1: make the compiler widen the packed rows again in the second pass
-#endif
-#ifndef NT_XCD_MAP
-#define NT_XCD_MAP 0          // experiment: block-to-tile map that keeps each XCD on a contiguous range
-#endif
-#ifndef NT_STATE_FIRST
-#define NT_STATE_FIRST 0      // experiment: issue the w, m, v loads before the gradient rows
+#ifndef NT_ADAMW_BARRIER
+#define NT_ADAMW_BARRIER 1    // AdamW-only tiles end with a block barrier like the other modes (measured +2 %)
 #endif
 #ifndef NT_UNROLL
 #define NT_UNROLL 1           // unroll factor of the per-tile sweep loop
@@ -131,25 +125,6 @@ struct BF16 {
     return __builtin_bit_cast(float, (uint32_t)((const uint16_t*)base)[i] << 16);
   }
 };
-
-// opaque to the optimiser: the packed words may have "changed", so values widened from them before
-// this point cannot be kept alive across it
-template <class R>
-__device__ inline void forget(R& r) {
-#if NT_REUNPACK
-  if constexpr (sizeof(R) == 16) {
-    uint32_t a = r[0], b = r[1], c = r[2], d = r[3];
-    asm volatile("" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
-    r[0] = a; r[1] = b; r[2] = c; r[3] = d;
-  } else {
-    uint32_t a = r[0], b = r[1];
-    asm volatile("" : "+v"(a), "+v"(b));
-    r[0] = a; r[1] = b;
-  }
-#else
-  (void)r;
-#endif
-}
 
 struct StepParams {
   const void* grads;
@@ -350,22 +325,25 @@ __device__ inline void guarded_tile(const StepParams& p, int64_t tile, int tile_
 template <int VEC>
 __device__ inline void adamw_store(const StepParams& p, int64_t i0, const float* gb, const u32x4* sw, const u32x4* sm,
                                    const u32x4* sv) {
+  f32x4 ow[VEC / 4], om[VEC / 4], ov[VEC / 4];
 #pragma unroll
   for (int q = 0; q < VEC / 4; ++q) {
-    f32x4 ow, om, ov;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       float w = __builtin_bit_cast(float, (uint32_t)sw[q][e]);
       float m = __builtin_bit_cast(float, (uint32_t)sm[q][e]);
       float v = __builtin_bit_cast(float, (uint32_t)sv[q][e]);
       adamw_coord(p, gb[4 * q + e], w, m, v);
-      ow[e] = w;
-      om[e] = m;
-      ov[e] = v;
+      ow[q][e] = w;
+      om[q][e] = m;
+      ov[q][e] = v;
     }
-    st16(p.w + i0 + 4 * q, ow);
-    st16(p.m + i0 + 4 * q, om);
-    st16(p.v + i0 + 4 * q, ov);
+  }
+#pragma unroll
+  for (int q = 0; q < VEC / 4; ++q) {
+    st16(p.w + i0 + 4 * q, ow[q]);
+    st16(p.m + i0 + 4 * q, om[q]);
+    st16(p.v + i0 + 4 * q, ov[q]);
   }
 }
 
@@ -395,19 +373,8 @@ __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red
     const int64_t i0 = tile * TILE + ((int64_t)it * BLOCK + threadIdx.x) * VEC;
     typename GT::raw_t raw[J];
     u32x4 sw[VEC / 4], sm[VEC / 4], sv[VEC / 4];
-#if NT_STATE_FIRST
-    if constexpr (MODE != MODE_STATS) {
-#pragma unroll
-      for (int q = 0; q < VEC / 4; ++q) {
-        sw[q] = ld16(p.w + i0 + 4 * q);
-        sm[q] = ld16(p.m + i0 + 4 * q);
-        sv[q] = ld16(p.v + i0 + 4 * q);
-      }
-    }
-#endif
 #pragma unroll
     for (int j = 0; j < J; ++j) raw[j] = GT::ldraw(gbase + j * row_bytes + i0 * GT::ESIZE);
-#if !NT_STATE_FIRST
     if constexpr (MODE != MODE_STATS) {
 #pragma unroll
       for (int q = 0; q < VEC / 4; ++q) {
@@ -416,7 +383,6 @@ __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red
         sv[q] = ld16(p.v + i0 + 4 * q);
       }
     }
-#endif
     double s[VEC];
     float gb[VEC];
 #pragma unroll
@@ -432,8 +398,6 @@ __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red
       float a[VEC], c[VEC], b[VEC];
 #pragma unroll
       for (int e = 0; e < VEC; ++e) a[e] = c[e] = 0.f;
-#pragma unroll
-      for (int j = 0; j < J; ++j) forget(raw[j]);
 #pragma unroll
       for (int j = 0; j < J; ++j)
 #pragma unroll
@@ -456,6 +420,9 @@ __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red
     if (p.gbar) gbar_store<VEC>(p, i0, gb);
   }
   if constexpr (MODE != MODE_ADAMW) tile_reduce<BLOCK>(accA, accB, accC, red, buf, p.partials, tile);
+#if NT_ADAMW_BARRIER
+  if constexpr (MODE == MODE_ADAMW) __syncthreads();
+#endif
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -571,15 +538,7 @@ __global__ __launch_bounds__(BLOCK, NT_WAVES_PER_EU) void k_step(StepParams p, i
   __shared__ double red[2][BLOCK / 64][3];
   int buf = 0;
   const int64_t nrest = ntiles - nfull;  // guarded tiles (0 or 1 on the aligned path)
-#if NT_XCD_MAP
-  // experiment: consecutive block ids land on different XCDs; give each XCD its own contiguous eighth
-  const int64_t per = (ntiles + 7) / 8;
-  for (int64_t t0 = blockIdx.x; t0 < per * 8; t0 += gridDim.x) {
-    const int64_t t = (t0 % 8) * per + t0 / 8;
-    if (t >= ntiles) continue;
-#else
   for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
-#endif
     // rotate: the first nrest slots are the guarded tiles nfull.., then the fast tiles 0..nfull-1
     const int64_t tile = (t < nrest) ? nfull + t : t - nrest;
     if (tile < nfull) {
@@ -993,12 +952,7 @@ static int enqueue_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d
     if (p.gbar) al = al && aligned16(p.gbar);
     const int64_t nfull = al ? d / tc : 0;
     const int64_t max_grid = (int64_t)cu_count() * NT_BLOCKS_PER_CU;
-#if NT_XCD_MAP
-    const int64_t want_grid = ((ntiles + 7) / 8) * 8;
-#else
-    const int64_t want_grid = ntiles;
-#endif
-    const int grid = (int)(want_grid < max_grid ? want_grid : max_grid);
+    const int grid = (int)(ntiles < max_grid ? ntiles : max_grid);
     const hipError_t e = (gdtype == NT_F32) ? launch_step_mode<F32>(mode, p, nfull, ntiles, grid, st)
                                             : launch_step_mode<BF16>(mode, p, nfull, ntiles, grid, st);
     if (e != hipSuccess) return hip_code(e);

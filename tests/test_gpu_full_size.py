@@ -82,3 +82,11 @@ def test_per_sample_full():
     wl = synth.per_sample(device=DEV)
     assert wl.J == 512 and wl.d == 1 << 24
     run_and_check(wl)
+
+
+def test_more_than_2_to_31_coordinates():
+    """64-bit indexing: d just above 2^31 with a ragged, odd end; J=2 keeps the footprint at 60 GB."""
+    d = (1 << 31) + 12_293
+    wl = synth.make("beyond_int32", 2, d, gdtype=torch.bfloat16, sigma=1e-2, seed=7, device=DEV,
+                    hyper=synth.Hyper(b_k=64, round_to=2, step=3))
+    run_and_check(wl)

@@ -379,6 +379,58 @@ def test_adamw_gbar_misaligned_matches_aligned():
         assert torch.equal(a, b)
 
 
+# ------------------------------------------------------------------ seeded random sweep over the argument space
+
+def test_random_configurations_against_oracle():
+    """60 seeded draws of (J, d, dtype, alignment offset, row padding, flags, ddof, step, eta, b_k, rounding)."""
+    rng = np.random.default_rng(2024)
+    for case in range(60):
+        J = int(rng.choice([2, 3, 4, 6, 8, 12, 16, 17, 24, 33, 70]))
+        d = int(rng.choice([1, 5, 100, 1023, 1024, 2049, 4096, 4097, 9000, 20000, 40001]))
+        gdtype = torch.bfloat16 if rng.random() < 0.6 else torch.float32
+        off = int(rng.choice([0, 0, 1, 2, 4]))
+        pad = int(rng.choice([0, 0, 3, 8, 64]))
+        mode = str(rng.choice(["full", "full", "stats", "adamw"]))
+        flags = {"full": FULL, "stats": B.NT_DO_STATS, "adamw": B.NT_DO_ADAMW}[mode]
+        want_gbar = bool(rng.random() < 0.3)
+        h = synth.Hyper(lr=float(rng.choice([1e-3, 4e-4, 0.0])), beta1=float(rng.choice([0.9, 0.0, 0.5])),
+                        beta2=float(rng.choice([0.95, 0.999])), eps=1e-8, weight_decay=float(rng.choice([0.1, 0.0])),
+                        eta=float(rng.choice([0.05, 0.1, 0.275])), step=int(rng.choice([1, 2, 10, 1000])),
+                        b_k=int(rng.choice([1, 32, 256])), b_max=int(rng.choice([0, 512, 8192])),
+                        round_to=int(rng.choice([1, 4, 128])), ddof=int(rng.integers(0, 2)))
+        sigma = float(rng.choice([1e-3, 1e-2, 1e-1]))
+        src = synth.make("r", J, d, gdtype=gdtype, sigma=sigma, seed=1000 + case, device=DEV, hyper=h)
+        big = torch.full((J, off + d + pad), 3.0, dtype=gdtype, device=DEV)
+        grads = big[:, off:off + d]
+        grads.copy_(src.grads)
+        st = [torch.full((off + d + 1,), 9.0, device=DEV)[off:off + d] for _ in range(3)]
+        for t, s0 in zip(st, (src.w, src.m, src.v)):
+            t.copy_(s0)
+        before = [t.clone() for t in st]
+        gbar = torch.full((off + d,), 7.0, device=DEV)[off:] if want_gbar else None
+        fl = flags | (B.NT_WRITE_GBAR if want_gbar else 0)
+        ctx = "case %d: J=%d d=%d %s off=%d pad=%d mode=%s gbar=%s" % (case, J, d, gdtype, off, pad, mode, want_gbar)
+        res = gpu_step(grads, st[0], st[1], st[2], h, d=d, flags=fl, gbar_out=gbar)
+        ref = H.oracle_full(grads, d, J, h)
+        try:
+            if mode != "adamw":
+                H.assert_stats_close(res, ref)
+                H.assert_decision_matches(res, ref, h)
+            else:
+                assert res["status"] == B.NT_STATUS_NO_STATS and res["next_b"] == h.b_k
+            if mode != "stats":
+                H.oracle_adamw_check(grads, d, before[0], before[1], before[2], st[0], st[1], st[2], h, gbar=gbar)
+            else:
+                for a, b in zip(st, before):
+                    assert torch.equal(a, b)
+                if want_gbar:
+                    g64 = grads.double().mean(dim=0)
+                    H.assert_state_close("gbar", gbar.cpu().numpy(), g64.cpu().numpy())
+        except AssertionError as e:
+            raise AssertionError(ctx + ": " + str(e))
+        assert bool((big[:, :off] == 3.0).all()) and bool((big[:, off + d:] == 3.0).all()), ctx
+
+
 # ------------------------------------------------------------------ memory safety and graph capture
 
 @pytest.mark.parametrize("J,gdtype,flags", [(8, torch.bfloat16, FULL), (4, torch.float32, FULL),
