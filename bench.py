@@ -5,7 +5,7 @@ A "step" is one pass of the whole hot path (statistics, decision, fused AdamW: `
 the headline workload: J=8 bfloat16 gradient rows of a flat d=1.5e9 vector with fp32 w, m, v, all
 resident in HBM before the timed region.  Prints one JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload flat_1p5b|gpt2_small|fsdp_shard|per_sample|tiny]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload flat_1p5b|gpt2_small|fsdp_shard|per_sample|tiny|paper_300m|paper_1.1b|paper_3.4b]
 """
 from __future__ import annotations
 
@@ -44,6 +44,10 @@ def make_workload(name: str, device: str, scale: float):
         return synth.per_sample(d=max(64, int((1 << 24) * scale) // 64 * 64), device=device)
     if name == "tiny":
         return synth.tiny(1e-2, device=device)
+    if name in ("paper_300m", "paper_1.1b", "paper_3.4b"):
+        which = name.split("_")[1]
+        wl = synth.paper_model(which, device=device)
+        return wl if scale == 1.0 else synth.paper_model(which, device=device, d=int(wl.d * scale))
     raise SystemExit("unknown workload %r" % name)
 
 

@@ -223,6 +223,17 @@ def per_sample(*, b: int = 512, d: int = 1 << 24, n_blocks: int = 64, seed: int 
                 seed=seed, device=device)
 
 
+def paper_model(which: str = "1.1b", *, J: int = 4, sigma: float = 1e-2, seed: int = 0, device="cpu",
+                d: Optional[int] = None) -> Workload:
+    """A flat vector with the parameter count of one of the paper's models (Table 4: 304.6M, 1.1B, 3.4B) and
+    J = 4 bf16 worker gradients (the data-parallel size of its runs, Tables 5-7); tiny's distribution."""
+    sizes = {"300m": 304_600_000, "1.1b": 1_100_000_000, "3.4b": 3_400_000_000}
+    d = sizes[which] if d is None else d
+    return make("paper_" + which, J, d, gdtype=torch.bfloat16, sigma=sigma, mu="normal", mu_scale=1e-2,
+                hyper=Hyper(lr=4e-4, step=10, b_k=256, b_max=8192, round_to=J * 16, ddof=1),
+                seed=seed, device=device)
+
+
 # ---- views for the oracle -----------------------------------------------------------------
 
 def grads_as_numpy(grads: torch.Tensor, lo: int = 0, hi: Optional[int] = None):

@@ -84,6 +84,16 @@ def test_per_sample_full():
     run_and_check(wl)
 
 
+def test_paper_model_sizes():
+    """J = 4 worker gradients at the parameter counts of the paper's models (Table 4); the largest, 3.4e9
+    coordinates and 109 GB of operands, is also the largest single call tested."""
+    for which in ("300m", "3.4b"):
+        wl = synth.paper_model(which, device=DEV)
+        run_and_check(wl)
+        del wl
+        torch.cuda.empty_cache()
+
+
 def test_more_than_2_to_31_coordinates():
     """64-bit indexing: d just above 2^31 with a ragged, odd end; J=2 keeps the footprint at 60 GB."""
     d = (1 << 31) + 12_293
