@@ -464,6 +464,33 @@ def test_canaries_around_every_buffer_survive(J, gdtype, flags):
         assert r.status in (0, B.NT_STATUS_NO_STATS)
 
 
+def test_result_in_pinned_host_memory_and_two_streams():
+    """The result struct may live in pinned host memory, and calls on different streams with their own
+    buffers do not interfere (the library keeps no state)."""
+    wls = [synth.make("t", 8, 6 * 16384 + 11 * k, gdtype=torch.bfloat16, seed=40 + k, device=DEV) for k in range(2)]
+    refs = []
+    for wl in wls:
+        st = [t.clone() for t in (wl.w, wl.m, wl.v)]
+        refs.append((gpu_step(wl.grads, st[0], st[1], st[2], wl.hyper), st))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    pinned = [torch.zeros(B.RESULT_BYTES, dtype=torch.uint8).pin_memory() for _ in wls]
+    ws = [torch.empty(B.normtest_workspace_bytes(wl.J, wl.d), dtype=torch.uint8, device=DEV) for wl in wls]
+    torch.cuda.synchronize()
+    for wl, s, pin, wsp in zip(wls, streams, pinned, ws):
+        s.wait_stream(torch.cuda.current_stream())
+        lib_rc = B.lib().normtest_step(wl.grads.data_ptr(), B.NT_BF16, wl.J, wl.d, wl.ld, wl.w.data_ptr(),
+                                       wl.m.data_ptr(), wl.v.data_ptr(), None, hyper_of(wl.hyper), None,
+                                       wsp.data_ptr(), wsp.numel(), pin.data_ptr(), s.cuda_stream)
+        assert lib_rc == B.NT_OK
+    for s in streams:
+        s.synchronize()
+    for wl, pin, (ref, st) in zip(wls, pinned, refs):
+        got = B.nt_result.from_buffer_copy(pin.numpy().tobytes()).as_dict()
+        assert got == ref
+        for a, b in zip((wl.w, wl.m, wl.v), st):
+            assert torch.equal(a, b)
+
+
 def test_step_can_be_captured_in_a_hip_graph():
     """The step allocates nothing and records only kernel launches, so it can be captured; every replay,
     with eager work and synchronisation in between, must reproduce the eager result bit for bit."""
