@@ -124,6 +124,19 @@ int normtest_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int6
                   nt_result* result_dev, void* hip_stream);
 
 /*
+ * The same step for gradient rows that are separate allocations (one buffer per worker or micro-batch,
+ * Sec. 3.2): grad_rows_dev is a device-resident array of J device pointers (8-byte aligned), row j
+ * holding at least d elements of type gdtype.  The table is read by the kernels, never by the host; rows
+ * that are not all 16-byte aligned take the slower path, with bit-identical results.  Everything else
+ * as in normtest_step; for the same rows the two calls return the same bits.
+ */
+int normtest_step_rows(const void* const* grad_rows_dev, nt_dtype gdtype, int64_t J, int64_t d,
+                       float* w, float* m, float* v, float* gbar_out,
+                       const nt_hyper* hyper, const nt_shard_info* shard,
+                       void* workspace, size_t workspace_bytes,
+                       nt_result* result_dev, void* hip_stream);
+
+/*
  * Host-side combination of n per-shard partial results (all host memory), Sec. 3.3 / Appendix A:
  * gradients of the shards are concatenated, so A, B, C add.  Sums (with their low parts) are added in
  * shard order in double-double arithmetic, then the same decision as in normtest_step is taken in

@@ -81,6 +81,10 @@ def lib(path: Optional[str] = None):
                                     ctypes.POINTER(nt_hyper), ctypes.POINTER(nt_shard_info),
                                     vp, ctypes.c_size_t, vp, vp]
         L.normtest_step.restype = ctypes.c_int
+        L.normtest_step_rows.argtypes = [vp, ctypes.c_int, i64, i64, vp, vp, vp, vp,
+                                         ctypes.POINTER(nt_hyper), ctypes.POINTER(nt_shard_info),
+                                         vp, ctypes.c_size_t, vp, vp]
+        L.normtest_step_rows.restype = ctypes.c_int
         L.normtest_combine.argtypes = [ctypes.POINTER(nt_result), ctypes.c_int32, i64,
                                        ctypes.POINTER(nt_hyper), ctypes.POINTER(nt_result)]
         L.normtest_combine.restype = ctypes.c_int
@@ -170,6 +174,53 @@ def normtest_step(grads: torch.Tensor, w: Optional[torch.Tensor], m: Optional[to
         raise NormtestError(rc, "normtest_step")
     if own_workspace:
         workspace.record_stream(stream)   # keep the scratch alive until the stream has consumed it
+    return result
+
+
+def make_row_table(rows) -> torch.Tensor:
+    """Device-resident table of the rows' addresses (int64[J]) for normtest_step_rows.  The caller keeps
+    the rows and the table alive until the step has run."""
+    dev = rows[0].device
+    return torch.tensor([r.data_ptr() for r in rows], dtype=torch.int64, device=dev)
+
+
+def normtest_step_rows(rows, w: Optional[torch.Tensor], m: Optional[torch.Tensor], v: Optional[torch.Tensor],
+                       hyper: nt_hyper, *, d: Optional[int] = None, table: Optional[torch.Tensor] = None,
+                       shard: Optional[nt_shard_info] = None, gbar_out: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None, result: Optional[torch.Tensor] = None,
+                       stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """normtest_step for J separately allocated gradient rows (a sequence of 1-D device tensors of one dtype)."""
+    J = len(rows)
+    dev = rows[0].device
+    if dev.type != "cuda":
+        raise ValueError("normtest_step_rows needs device tensors; there is no CPU path")
+    d = min(r.numel() for r in rows) if d is None else d
+    for r in rows:
+        if r.dtype != rows[0].dtype or r.device != dev or r.dim() != 1 or not r.is_contiguous() or r.numel() < d:
+            raise ValueError("rows must be contiguous 1-D tensors of one dtype and >= d elements on %s" % dev)
+    for name, t in (("w", w), ("m", m), ("v", v), ("gbar_out", gbar_out)):
+        if t is not None:
+            if t.dtype != torch.float32 or t.device != dev or not t.is_contiguous() or t.numel() < d:
+                raise ValueError("%s must be a contiguous float32 tensor of >= d elements on %s" % (name, dev))
+    if table is None:
+        table = make_row_table(rows)
+    own_workspace = workspace is None
+    if own_workspace:
+        workspace = torch.empty(max(normtest_workspace_bytes(J, d), 8), dtype=torch.uint8, device=dev)
+    if result is None:
+        result = torch.empty(RESULT_BYTES, dtype=torch.uint8, device=dev)
+    if stream is None:
+        stream = torch.cuda.current_stream(dev)
+    with torch.cuda.device(dev):
+        rc = lib().normtest_step_rows(_ptr(table), _gdtype(rows[0]), J, d, _ptr(w), _ptr(m), _ptr(v), _ptr(gbar_out),
+                                      ctypes.byref(hyper), ctypes.byref(shard) if shard is not None else None,
+                                      _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                      _ptr(result), ctypes.c_void_p(stream.cuda_stream))
+    if rc != NT_OK:
+        raise NormtestError(rc, "normtest_step_rows")
+    table.record_stream(stream)
+    if own_workspace:
+        workspace.record_stream(stream)
     return result
 
 

@@ -127,7 +127,7 @@ struct BF16 {
 };
 
 struct StepParams {
-  const void* grads;
+  const void* grads; // row 0 of a strided matrix, or (TABLE kernels) a device array of J row pointers
   int64_t ld;       // row stride in elements
   int64_t d;
   int J;
@@ -143,6 +143,15 @@ struct StepParams {
   float inv_sqrt_bc2;             // 1 / sqrt(1 - beta2^k)
   float eps;
 };
+
+// Start of gradient row j: base + j*ld elements, or the j-th entry of the caller's pointer table.
+template <class GT, bool TABLE>
+__device__ inline const char* row_base(const StepParams& p, int j) {
+  if constexpr (TABLE)
+    return ((const char* const*)p.grads)[j];
+  else
+    return (const char*)p.grads + (int64_t)j * p.ld * GT::ESIZE;
+}
 
 __device__ inline u32x4 ld16(const void* p) { return ld_vec<NT_NT_STATE, u32x4>(p); }
 __device__ inline void st16(void* p, f32x4 x) {
@@ -242,20 +251,18 @@ __device__ inline float chunk_merge(bool first, int na, int nb, float K, double 
   return (float)(S * (1.0 / (double)(na + nb)));
 }
 
-template <class GT>
+template <class GT, bool TABLE>
 __device__ inline void coord_stats_generic(const StepParams& p, int64_t i, double& S, float& M2, float& a) {
-  const void* grads = p.grads;
-  const int64_t ld = p.ld;
   const int J = p.J;
   a = 0.f;
   if (J <= NT_JCHUNK) {
     // all rows at once: fp64 row sum, then squares centred on the mean, exactly as in the fast tile
-    double sb = (double)GT::ld(grads, i);
-    for (int j = 1; j < J; ++j) sb += (double)GT::ld(grads, (int64_t)j * ld + i);
+    double sb = (double)GT::ld(row_base<GT, TABLE>(p, 0), i);
+    for (int j = 1; j < J; ++j) sb += (double)GT::ld(row_base<GT, TABLE>(p, j), i);
     const float mb = (float)(sb * p.inv_J);
     float cb = 0.f;
     for (int j = 0; j < J; ++j) {
-      const float x = GT::ld(grads, (int64_t)j * ld + i);
+      const float x = GT::ld(row_base<GT, TABLE>(p, j), i);
       const float r = x - mb;
       cb = __builtin_fmaf(r, r, cb);
       a = __builtin_fmaf(x, x, a);
@@ -264,14 +271,14 @@ __device__ inline void coord_stats_generic(const StepParams& p, int64_t i, doubl
     M2 = cb;
     return;
   }
-  float K = GT::ld(grads, i);
+  float K = GT::ld(row_base<GT, TABLE>(p, 0), i);
   int na = 0;
   for (int j0 = 0; j0 < J; j0 += NT_JCHUNK) {
     const int nb = (J - j0 < NT_JCHUNK) ? (J - j0) : NT_JCHUNK;
     double sr = 0.0;
     float q = 0.f;
     for (int j = 0; j < nb; ++j) {
-      const float r = GT::ld(grads, (int64_t)(j0 + j) * ld + i) - K;
+      const float r = GT::ld(row_base<GT, TABLE>(p, j0 + j), i) - K;
       sr += (double)r;
       q = __builtin_fmaf(r, r, q);
     }
@@ -280,7 +287,7 @@ __device__ inline void coord_stats_generic(const StepParams& p, int64_t i, doubl
   }
 }
 
-template <class GT, int MODE, int BLOCK>
+template <class GT, int MODE, int BLOCK, bool TABLE>
 __device__ inline void guarded_tile(const StepParams& p, int64_t tile, int tile_coords, double (*red)[BLOCK / 64][3],
                                     int buf) {
   constexpr int VEC = GT::VEC;
@@ -296,7 +303,7 @@ __device__ inline void guarded_tile(const StepParams& p, int64_t tile, int tile_
       if (i < p.d) {
         double S;
         float M2, aa;
-        coord_stats_generic<GT>(p, i, S, M2, aa);
+        coord_stats_generic<GT, TABLE>(p, i, S, M2, aa);
         const float gb = (float)(S * p.inv_J);
         const float sf = (float)S;
         a[e] = aa;
@@ -361,12 +368,10 @@ __device__ inline void gbar_store(const StepParams& p, int64_t i0, const float* 
 // registers; needs 16-byte aligned rows and state and a tile that lies wholly below d.
 // The row sum is carried in fp64 so that the mean is correctly rounded even when the rows cancel.
 // ---------------------------------------------------------------------------------------------
-template <class GT, int J, int MODE, int BLOCK, int ITERS>
+template <class GT, int J, int MODE, int BLOCK, int ITERS, bool TABLE>
 __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red)[BLOCK / 64][3], int buf) {
   constexpr int VEC = GT::VEC;
   constexpr int TILE = BLOCK * VEC * ITERS;
-  const char* gbase = (const char*)p.grads;
-  const int64_t row_bytes = p.ld * GT::ESIZE;
   double accA = 0.0, accB = 0.0, accC = 0.0;
   NT_PRAGMA_UNROLL(NT_UNROLL)
   for (int it = 0; it < ITERS; ++it) {
@@ -374,7 +379,7 @@ __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red
     typename GT::raw_t raw[J];
     u32x4 sw[VEC / 4], sm[VEC / 4], sv[VEC / 4];
 #pragma unroll
-    for (int j = 0; j < J; ++j) raw[j] = GT::ldraw(gbase + j * row_bytes + i0 * GT::ESIZE);
+    for (int j = 0; j < J; ++j) raw[j] = GT::ldraw(row_base<GT, TABLE>(p, j) + i0 * GT::ESIZE);
     if constexpr (MODE != MODE_STATS) {
 #pragma unroll
       for (int q = 0; q < VEC / 4; ++q) {
@@ -450,18 +455,16 @@ __device__ inline void chunk_accumulate(const typename GT::raw_t* raw, int nb, c
     }
 }
 
-template <class GT, int MODE, int BLOCK, int ITERS>
+template <class GT, int MODE, int BLOCK, int ITERS, bool TABLE>
 __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double (*red)[BLOCK / 64][3], int buf) {
   constexpr int VEC = GT::VEC;
   constexpr int TILE = BLOCK * VEC * ITERS;
-  const char* gbase = (const char*)p.grads;
-  const int64_t row_bytes = p.ld * GT::ESIZE;
   const int J = p.J;
   double accA = 0.0, accB = 0.0, accC = 0.0;
 #pragma unroll 1
   for (int it = 0; it < ITERS; ++it) {
     const int64_t i0 = tile * TILE + ((int64_t)it * BLOCK + threadIdx.x) * VEC;
-    const char* gp = gbase + i0 * GT::ESIZE;
+    const int64_t goff = i0 * GT::ESIZE;
     double S[VEC], sr[VEC];
     float M2[VEC], a[VEC], K[VEC], q[VEC];
 #pragma unroll
@@ -469,7 +472,7 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
     typename GT::raw_t raw[NT_JCHUNK];
     // first chunk (J > NT_JCHUNK here, so it is full), shifted by the first row
 #pragma unroll
-    for (int j = 0; j < NT_JCHUNK; ++j) raw[j] = GT::ldraw(gp + j * row_bytes);
+    for (int j = 0; j < NT_JCHUNK; ++j) raw[j] = GT::ldraw(row_base<GT, TABLE>(p, j) + goff);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) K[e] = GT::val(raw[0], e);
     chunk_accumulate<GT, false>(raw, NT_JCHUNK, K, sr, q);
@@ -478,19 +481,17 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
     int j0 = NT_JCHUNK;
 #pragma unroll 1
     for (; j0 + NT_JCHUNK <= J; j0 += NT_JCHUNK) {
-      const char* cp = gp + (int64_t)j0 * row_bytes;
 #pragma unroll
-      for (int j = 0; j < NT_JCHUNK; ++j) raw[j] = GT::ldraw(cp + j * row_bytes);
+      for (int j = 0; j < NT_JCHUNK; ++j) raw[j] = GT::ldraw(row_base<GT, TABLE>(p, j0 + j) + goff);
       chunk_accumulate<GT, false>(raw, NT_JCHUNK, K, sr, q);
 #pragma unroll
       for (int e = 0; e < VEC; ++e) K[e] = chunk_merge(false, j0, NT_JCHUNK, K[e], sr[e], q[e], S[e], M2[e], a[e]);
     }
     if (j0 < J) {
       const int nb = J - j0;
-      const char* cp = gp + (int64_t)j0 * row_bytes;
 #pragma unroll
       for (int j = 0; j < NT_JCHUNK; ++j)
-        if (j < nb) raw[j] = GT::ldraw(cp + j * row_bytes);
+        if (j < nb) raw[j] = GT::ldraw(row_base<GT, TABLE>(p, j0 + j) + goff);
       chunk_accumulate<GT, true>(raw, nb, K, sr, q);
 #pragma unroll
       for (int e = 0; e < VEC; ++e) K[e] = chunk_merge(false, j0, nb, K[e], sr[e], q[e], S[e], M2[e], a[e]);
@@ -531,23 +532,29 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
 // takes it first so that the slow tile overlaps with everything else.
 // J_T = 0 selects the J > 16 row-walking variant.
 // ---------------------------------------------------------------------------------------------
-template <class GT, int J_T, int MODE, int BLOCK, int ITERS>
+template <class GT, int J_T, int MODE, int BLOCK, int ITERS, bool TABLE>
 __global__ __launch_bounds__(BLOCK, NT_WAVES_PER_EU) void k_step(StepParams p, int64_t nfull, int64_t ntiles) {
   constexpr int TILE = BLOCK * GT::VEC * ITERS;
   static_assert(NT_TILE_MAX % TILE == 0, "tile sizes must divide NT_TILE_MAX");
   __shared__ double red[2][BLOCK / 64][3];
   int buf = 0;
+  if constexpr (TABLE) {
+    // the host cannot see the row pointers: the fast tiles need all of them 16-byte aligned
+    uintptr_t bits = 0;
+    for (int j = 0; j < p.J; ++j) bits |= (uintptr_t)row_base<GT, true>(p, j);
+    if (bits & 15u) nfull = 0;
+  }
   const int64_t nrest = ntiles - nfull;  // guarded tiles (0 or 1 on the aligned path)
   for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
     // rotate: the first nrest slots are the guarded tiles nfull.., then the fast tiles 0..nfull-1
     const int64_t tile = (t < nrest) ? nfull + t : t - nrest;
     if (tile < nfull) {
       if constexpr (J_T > 0)
-        fast_tile<GT, J_T, MODE, BLOCK, ITERS>(p, tile, red, buf);
+        fast_tile<GT, J_T, MODE, BLOCK, ITERS, TABLE>(p, tile, red, buf);
       else
-        fast_tile_multi<GT, MODE, BLOCK, ITERS>(p, tile, red, buf);
+        fast_tile_multi<GT, MODE, BLOCK, ITERS, TABLE>(p, tile, red, buf);
     } else {
-      guarded_tile<GT, MODE, BLOCK>(p, tile, TILE, red, buf);
+      guarded_tile<GT, MODE, BLOCK, TABLE>(p, tile, TILE, red, buf);
     }
     buf ^= 1;
   }
@@ -838,31 +845,31 @@ bool hyper_ok(const nt_hyper* h, int64_t J) {
   return true;
 }
 
-template <class GT, int MODE>
+template <class GT, int MODE, bool TABLE>
 hipError_t launch_step(const StepParams& p, int64_t nfull, int64_t ntiles, int grid, hipStream_t st) {
   constexpr int BS = (MODE == MODE_STATS) ? NT_BLOCK_STATS : (MODE == MODE_ADAMW) ? NT_BLOCK_ADAMW : NT_BLOCK;
   constexpr int IS = (MODE == MODE_STATS) ? NT_ITERS_STATS : (MODE == MODE_ADAMW) ? NT_ITERS_ADAMW : NT_ITERS;
 #define NT_CASE(JJ)                                                                                      \
   case JJ:                                                                                               \
-    hipLaunchKernelGGL((k_step<GT, JJ, MODE, BS, IS>), dim3(grid), dim3(BS), 0, st, p, nfull, ntiles);  \
+    hipLaunchKernelGGL((k_step<GT, JJ, MODE, BS, IS, TABLE>), dim3(grid), dim3(BS), 0, st, p, nfull, ntiles);  \
     break;
   switch (p.J) {
     NT_CASE(2) NT_CASE(3) NT_CASE(4) NT_CASE(5) NT_CASE(6) NT_CASE(7) NT_CASE(8) NT_CASE(9)
     NT_CASE(10) NT_CASE(11) NT_CASE(12) NT_CASE(13) NT_CASE(14) NT_CASE(15) NT_CASE(16)
     default:
-      hipLaunchKernelGGL((k_step<GT, 0, MODE, NT_BLOCK_LARGE, NT_ITERS_LARGE>), dim3(grid), dim3(NT_BLOCK_LARGE), 0,
-                         st, p, nfull, ntiles);
+      hipLaunchKernelGGL((k_step<GT, 0, MODE, NT_BLOCK_LARGE, NT_ITERS_LARGE, TABLE>), dim3(grid),
+                         dim3(NT_BLOCK_LARGE), 0, st, p, nfull, ntiles);
   }
 #undef NT_CASE
   return hipGetLastError();
 }
 
-template <class GT>
+template <class GT, bool TABLE>
 hipError_t launch_step_mode(int mode, const StepParams& p, int64_t nfull, int64_t ntiles, int grid, hipStream_t st) {
   switch (mode) {
-    case MODE_FULL: return launch_step<GT, MODE_FULL>(p, nfull, ntiles, grid, st);
-    case MODE_STATS: return launch_step<GT, MODE_STATS>(p, nfull, ntiles, grid, st);
-    default: return launch_step<GT, MODE_ADAMW>(p, nfull, ntiles, grid, st);
+    case MODE_FULL: return launch_step<GT, MODE_FULL, TABLE>(p, nfull, ntiles, grid, st);
+    case MODE_STATS: return launch_step<GT, MODE_STATS, TABLE>(p, nfull, ntiles, grid, st);
+    default: return launch_step<GT, MODE_ADAMW, TABLE>(p, nfull, ntiles, grid, st);
   }
 }
 
@@ -924,8 +931,9 @@ static int check_step_args(const void* grads, nt_dtype gdtype, int64_t J, int64_
 }
 
 // Enqueue the streaming kernel and the reduction/decision kernels.  Arguments are already validated.
-static int enqueue_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld, float* w, float* m,
-                        float* v, float* gbar_out, uint32_t flags, const nt_hyper* hyper, double max_norm,
+// `table`: grads is a device array of J row pointers instead of the first row of a strided matrix.
+static int enqueue_step(const void* grads, bool table, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld, float* w,
+                        float* m, float* v, float* gbar_out, uint32_t flags, const nt_hyper* hyper, double max_norm,
                         void* workspace, nt_result* result_dev, hipStream_t st) {
   const int esize = gdtype == NT_F32 ? 4 : 2;
   const int mode = (flags & NT_DO_STATS) ? ((flags & NT_DO_ADAMW) ? MODE_FULL : MODE_STATS) : MODE_ADAMW;
@@ -947,14 +955,20 @@ static int enqueue_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d
   if (flags & NT_DO_ADAMW) fill_adamw_params(p, hyper);
 
   if (ntiles > 0) {
-    bool al = aligned16(grads) && ((ld * esize) % 16 == 0);
+    // row alignment: checked here for a strided matrix, by the kernel itself for a pointer table
+    bool al = table || (aligned16(grads) && ((ld * esize) % 16 == 0));
     if (mode != MODE_STATS) al = al && aligned16(w) && aligned16(m) && aligned16(v);
     if (p.gbar) al = al && aligned16(p.gbar);
     const int64_t nfull = al ? d / tc : 0;
     const int64_t max_grid = (int64_t)cu_count() * NT_BLOCKS_PER_CU;
     const int grid = (int)(ntiles < max_grid ? ntiles : max_grid);
-    const hipError_t e = (gdtype == NT_F32) ? launch_step_mode<F32>(mode, p, nfull, ntiles, grid, st)
-                                            : launch_step_mode<BF16>(mode, p, nfull, ntiles, grid, st);
+    hipError_t e;
+    if (table)
+      e = (gdtype == NT_F32) ? launch_step_mode<F32, true>(mode, p, nfull, ntiles, grid, st)
+                             : launch_step_mode<BF16, true>(mode, p, nfull, ntiles, grid, st);
+    else
+      e = (gdtype == NT_F32) ? launch_step_mode<F32, false>(mode, p, nfull, ntiles, grid, st)
+                             : launch_step_mode<BF16, false>(mode, p, nfull, ntiles, grid, st);
     if (e != hipSuccess) return hip_code(e);
   }
 
@@ -1007,8 +1021,20 @@ int normtest_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int6
   const int rc = check_step_args(grads, gdtype, J, d, ld, w, m, v, gbar_out, hyper->flags, hyper, shard, workspace,
                                  workspace_bytes, result_dev);
   if (rc != NT_OK) return rc;
-  return enqueue_step(grads, gdtype, J, d, ld, w, m, v, gbar_out, hyper->flags, hyper, 0.0, workspace, result_dev,
-                      (hipStream_t)hip_stream);
+  return enqueue_step(grads, false, gdtype, J, d, ld, w, m, v, gbar_out, hyper->flags, hyper, 0.0, workspace,
+                      result_dev, (hipStream_t)hip_stream);
+}
+
+int normtest_step_rows(const void* const* grad_rows_dev, nt_dtype gdtype, int64_t J, int64_t d, float* w, float* m,
+                       float* v, float* gbar_out, const nt_hyper* hyper, const nt_shard_info* shard, void* workspace,
+                       size_t workspace_bytes, nt_result* result_dev, void* hip_stream) {
+  if (!hyper || ((uintptr_t)grad_rows_dev & 7u)) return NT_ERR_BAD_ARG;
+  // the table stands in for the matrix; its entries cannot be inspected from the host
+  const int rc = check_step_args(grad_rows_dev, gdtype, J, d, d, w, m, v, gbar_out, hyper->flags, hyper, shard,
+                                 workspace, workspace_bytes, result_dev);
+  if (rc != NT_OK) return rc;
+  return enqueue_step(grad_rows_dev, true, gdtype, J, d, d, w, m, v, gbar_out, hyper->flags, hyper, 0.0, workspace,
+                      result_dev, (hipStream_t)hip_stream);
 }
 
 int normtest_step_clipped(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld, float* w, float* m,
@@ -1023,7 +1049,7 @@ int normtest_step_clipped(const void* grads, nt_dtype gdtype, int64_t J, int64_t
                                  shard, workspace, workspace_bytes, result_dev);
   if (rc != NT_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
-  const int rc1 = enqueue_step(grads, gdtype, J, d, ld, nullptr, nullptr, nullptr, gbar_buf,
+  const int rc1 = enqueue_step(grads, false, gdtype, J, d, ld, nullptr, nullptr, nullptr, gbar_buf,
                                NT_DO_STATS | NT_WRITE_GBAR, hyper, max_norm, workspace, result_dev, st);
   if (rc1 != NT_OK) return rc1;
   return enqueue_adamw_gbar(gbar_buf, d, w, m, v, hyper, 1.0, result_dev, st);

@@ -379,6 +379,37 @@ def test_adamw_gbar_misaligned_matches_aligned():
         assert torch.equal(a, b)
 
 
+# ------------------------------------------------------------------ rows given as separate allocations
+
+@pytest.mark.parametrize("J,gdtype,flags", [(8, torch.bfloat16, FULL), (4, torch.float32, FULL),
+                                            (37, torch.bfloat16, FULL), (8, torch.bfloat16, B.NT_DO_STATS)])
+def test_row_table_gives_the_same_bits_as_the_strided_matrix(J, gdtype, flags):
+    d = 3 * 16384 + 2222
+    wl = synth.make("t", J, d, gdtype=gdtype, sigma=1e-2, seed=50 + J, device=DEV)
+    state0 = [t.clone() for t in (wl.w, wl.m, wl.v)]
+    ref = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper, flags=flags)
+    ref_state = [t.clone() for t in (wl.w, wl.m, wl.v)]
+    oracle_ref = H.oracle_full(wl.grads, d, J, wl.hyper)
+    H.assert_stats_close(ref, oracle_ref)
+    for misalign in (False, True):
+        # separate allocations of different lengths, in shuffled address order; optionally one row off by one element
+        rows = []
+        for j in range(J):
+            buf = torch.full((d + 64 + 8 * j,), 5.0, dtype=gdtype, device=DEV)
+            off = 1 if (misalign and j == J // 2) else 0
+            r = buf[off:off + d]
+            r.copy_(wl.grads[j, :d])
+            rows.append(r)
+        for t, s0 in zip((wl.w, wl.m, wl.v), state0):
+            t.copy_(s0)
+        res = B.normtest_step_rows(rows, wl.w, wl.m, wl.v, hyper_of(wl.hyper, flags))
+        torch.cuda.synchronize()
+        got = B.read_result(res).as_dict()
+        assert got == ref
+        for a, b in zip((wl.w, wl.m, wl.v), ref_state):
+            assert torch.equal(a, b)
+
+
 # ------------------------------------------------------------------ seeded random sweep over the argument space
 
 def test_random_configurations_against_oracle():

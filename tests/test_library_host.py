@@ -25,7 +25,7 @@ def test_every_declared_symbol_is_exported():
     names = declared_functions()
     assert {"normtest_step", "normtest_combine", "normtest_workspace_bytes", "normtest_tile_coords",
             "normtest_strerror", "normtest_calib_copy", "normtest_step_clipped", "normtest_adamw_gbar",
-            "normtest_clip_coef"} <= set(names)
+            "normtest_clip_coef", "normtest_step_rows"} <= set(names)
     L = B.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -121,6 +121,25 @@ def test_clipped_entry_points_validate_before_launch():
     assert f(0x7002, 64, 0x2000, 0x3000, 0x4000, ctypes.byref(hy), 1.0, None, None) == bad
     assert f(0x7000, 64, 0x2000, 0x3000, 0x4000, ctypes.byref(B.make_hyper(step=0)), 1.0, None, None) == bad
     assert f(0x7000, 0, None, None, None, ctypes.byref(hy), 1.0, None, None) == B.NT_OK               # d = 0: nothing to do
+
+
+def test_rows_entry_point_validates_before_launch():
+    L = B.lib()
+    hy = B.make_hyper(step=1, b_k=32, flags=FULL)
+
+    def call(table=0x1000, gdtype=B.NT_BF16, J=4, d=64, w=0x2000, m=0x3000, v=0x4000, hyper=hy, ws=0x5000,
+             ws_bytes=1 << 20, result=0x6000):
+        return L.normtest_step_rows(table, gdtype, J, d, w, m, v, None, ctypes.byref(hyper), None, ws, ws_bytes,
+                                    result, None)
+
+    bad = B.NT_ERR_BAD_ARG
+    assert call(table=None) == bad
+    assert call(table=0x1004) == bad            # the table itself must be 8-byte aligned
+    assert call(J=1) == bad
+    assert call(d=-5) == bad
+    assert call(w=None) == bad
+    assert call(gdtype=9) == B.NT_ERR_UNSUPPORTED
+    assert call(ws_bytes=0) == B.NT_ERR_WORKSPACE_TOO_SMALL
 
 
 def test_clip_coef_matches_oracle():
