@@ -101,7 +101,7 @@ def main():
     ap.add_argument("--mode", default="full", choices=["full", "stats", "adamw", "clipped"],
                     help="full: the fused step (headline); stats / adamw: one half only; clipped: two-phase variant")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=1 << 28)
+    ap.add_argument("--cpu-sample", type=int, default=1 << 29)
     ap.add_argument("--calib-copy-gib", type=int, default=0,
                     help="also run the library's plain copy kernel once on this many GiB (known traffic for scaling byte counters)")
     args = ap.parse_args()

@@ -36,8 +36,9 @@ def build_library(out: str = LIB, defines: dict | None = None, quiet: bool = Tru
 
 
 def ensure_built() -> str:
-    """Path of the built library; builds it only if nothing is there."""
-    if not os.path.exists(LIB):
+    """Path of the built library; builds it if nothing is there or a source is newer than the build."""
+    header = os.path.join(INCLUDE, "normtest.h")
+    if not os.path.exists(LIB) or os.path.getmtime(LIB) < max(os.path.getmtime(SRC), os.path.getmtime(header)):
         build_library()
     return LIB
 

@@ -80,7 +80,10 @@
 #define NT_PRAGMA_(x) _Pragma(#x)
 #define NT_PRAGMA_UNROLL(n) NT_PRAGMA_(unroll n)
 
-#define NT_JCHUNK 16          // rows held in registers at once
+#define NT_JCHUNK 16          // up to this many rows a coordinate's values are all held in registers
+#ifndef NT_MCHUNK
+#define NT_MCHUNK 16          // beyond that, rows are walked this many at a time (2 .. NT_JCHUNK + 1; 16 measured best)
+#endif
 #define NT_FIN_THREADS 1024
 #define NT_GROUP_THREADS 256   // first-stage reduction: threads per block
 #define NT_GROUP_TILES 2048    // ... and tile partials per block
@@ -273,8 +276,8 @@ __device__ inline void coord_stats_generic(const StepParams& p, int64_t i, doubl
   }
   float K = GT::ld(row_base<GT, TABLE>(p, 0), i);
   int na = 0;
-  for (int j0 = 0; j0 < J; j0 += NT_JCHUNK) {
-    const int nb = (J - j0 < NT_JCHUNK) ? (J - j0) : NT_JCHUNK;
+  for (int j0 = 0; j0 < J; j0 += NT_MCHUNK) {
+    const int nb = (J - j0 < NT_MCHUNK) ? (J - j0) : NT_MCHUNK;
     double sr = 0.0;
     float q = 0.f;
     for (int j = 0; j < nb; ++j) {
@@ -431,7 +434,7 @@ __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fast tile, J > 16: rows are walked NT_JCHUNK at a time.  Inside a chunk every value is shifted by
+// Fast tile, J > 16: rows are walked NT_MCHUNK at a time.  Inside a chunk every value is shifted by
 // K, the running mean of the rows before it, so one pass over the chunk gives both its sum and its
 // centred sum of squares without cancellation; see chunk_merge for the bookkeeping.
 // ---------------------------------------------------------------------------------------------
@@ -444,7 +447,7 @@ __device__ inline void chunk_accumulate(const typename GT::raw_t* raw, int nb, c
     q[e] = 0.f;
   }
 #pragma unroll
-  for (int j = 0; j < NT_JCHUNK; ++j)
+  for (int j = 0; j < NT_MCHUNK; ++j)
     if (!RT || j < nb) {
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
@@ -469,28 +472,28 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
     float M2[VEC], a[VEC], K[VEC], q[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) a[e] = 0.f;
-    typename GT::raw_t raw[NT_JCHUNK];
-    // first chunk (J > NT_JCHUNK here, so it is full), shifted by the first row
+    typename GT::raw_t raw[NT_MCHUNK];
+    // first chunk (J > NT_JCHUNK >= NT_MCHUNK - 1 here, so it is full), shifted by the first row
 #pragma unroll
-    for (int j = 0; j < NT_JCHUNK; ++j) raw[j] = GT::ldraw(row_base<GT, TABLE>(p, j) + goff);
+    for (int j = 0; j < NT_MCHUNK; ++j) raw[j] = GT::ldraw(row_base<GT, TABLE>(p, j) + goff);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) K[e] = GT::val(raw[0], e);
-    chunk_accumulate<GT, false>(raw, NT_JCHUNK, K, sr, q);
+    chunk_accumulate<GT, false>(raw, NT_MCHUNK, K, sr, q);
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) K[e] = chunk_merge(true, 0, NT_JCHUNK, K[e], sr[e], q[e], S[e], M2[e], a[e]);
-    int j0 = NT_JCHUNK;
+    for (int e = 0; e < VEC; ++e) K[e] = chunk_merge(true, 0, NT_MCHUNK, K[e], sr[e], q[e], S[e], M2[e], a[e]);
+    int j0 = NT_MCHUNK;
 #pragma unroll 1
-    for (; j0 + NT_JCHUNK <= J; j0 += NT_JCHUNK) {
+    for (; j0 + NT_MCHUNK <= J; j0 += NT_MCHUNK) {
 #pragma unroll
-      for (int j = 0; j < NT_JCHUNK; ++j) raw[j] = GT::ldraw(row_base<GT, TABLE>(p, j0 + j) + goff);
-      chunk_accumulate<GT, false>(raw, NT_JCHUNK, K, sr, q);
+      for (int j = 0; j < NT_MCHUNK; ++j) raw[j] = GT::ldraw(row_base<GT, TABLE>(p, j0 + j) + goff);
+      chunk_accumulate<GT, false>(raw, NT_MCHUNK, K, sr, q);
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) K[e] = chunk_merge(false, j0, NT_JCHUNK, K[e], sr[e], q[e], S[e], M2[e], a[e]);
+      for (int e = 0; e < VEC; ++e) K[e] = chunk_merge(false, j0, NT_MCHUNK, K[e], sr[e], q[e], S[e], M2[e], a[e]);
     }
     if (j0 < J) {
       const int nb = J - j0;
 #pragma unroll
-      for (int j = 0; j < NT_JCHUNK; ++j)
+      for (int j = 0; j < NT_MCHUNK; ++j)
         if (j < nb) raw[j] = GT::ldraw(row_base<GT, TABLE>(p, j0 + j) + goff);
       chunk_accumulate<GT, true>(raw, nb, K, sr, q);
 #pragma unroll
