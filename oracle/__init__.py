@@ -69,6 +69,8 @@ def _bind(path: str):
     lib.nto_adamw.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, dbl, dbl, dbl, dbl, dbl,
                               i64, dbl, vp, vp, vp, vp]
     lib.nto_adamw.restype = ctypes.c_int
+    lib.nto_coord_test.argtypes = [vp, ctypes.c_int, i64, i64, i64, dbl, i64, ctypes.c_int32, dbl, vp]
+    lib.nto_coord_test.restype = ctypes.c_int
     lib.nto_clip_coef.argtypes = [dbl, dbl]
     lib.nto_clip_coef.restype = dbl
     return lib
@@ -149,6 +151,21 @@ def decide(A, B, C, J, eta, b_k, b_max=0, round_to=1, ddof=1) -> Decision:
     if rc:
         raise ValueError("nto_decide rejected its arguments")
     return Decision(out.gbar_sq, out.var_l1, out.T, int(out.next_b), bool(out.pass_), int(out.status))
+
+
+def coord_test(G: np.ndarray, eta: float, b_k: int, ddof: int = 1, band: float = 0.0):
+    """Coordinate-wise test: (fail, near, pass) counts over the columns of G; `near` = within the relative
+    band of equality (0 when band = 0)."""
+    ptr, dtype, J, ld, n = _grad_args(G)
+    out = np.zeros(3, dtype=np.int64)
+    if n:
+        rc = _load().nto_coord_test(ptr, dtype, J, ld, n, eta, b_k, ddof, band, out.ctypes.data)
+        if rc:
+            raise ValueError("nto_coord_test rejected its arguments")
+    else:
+        if J - ddof < 1 or not eta > 0 or b_k < 1:
+            raise ValueError("nto_coord_test rejected its arguments")
+    return int(out[0]), int(out[1]), int(out[2])
 
 
 def clip_coef(gbar_sq: float, max_norm: float) -> float:

@@ -168,6 +168,42 @@ int nto_decide(double A, double B, double C, int64_t J, double eta, int64_t b_k,
 }
 
 /*
+ * Coordinate-wise form of the test.  The analysis (Sec. 4, Prop. 1; App. B remark) asks the norm-test
+ * condition of every coordinate i separately; with the same estimators as the aggregate test this reads
+ *   Var_i / b_k <= eta^2 gbar_i^2,   Var_i = sum_j (g_j[i] - gbar_i)^2 / (J - ddof),
+ * and a coordinate fails when the inequality is violated strictly (as T > b_k in Alg. 1).  The paper
+ * does not run this variant (Sec. 5) and prints no batch-size rule for it, so only the count of failing
+ * coordinates is defined here.  out[0] += coordinates that fail by more than the relative band,
+ * out[1] += coordinates within the band of equality (either answer is acceptable for an fp32 kernel),
+ * out[2] += coordinates that pass by more than the band.  band = 0 gives the plain fp64 decision
+ * (equality counts as pass).
+ */
+int nto_coord_test(const void *grads, int dtype, int64_t J, int64_t ld, int64_t n, double eta, int64_t b_k,
+                   int32_t ddof, double band, int64_t *out) {
+  if (!grads || !out || J < 1 || J - ddof < 1 || n < 0 || ld < n || !(eta > 0.0) || b_k < 1 || band < 0.0 ||
+      (dtype != NTO_F32 && dtype != NTO_BF16) || (ddof != 0 && ddof != 1))
+    return -1;
+  for (int64_t i = 0; i < n; ++i) {
+    double s = 0.0, c = 0.0, gbar, var, rhs;
+    for (int64_t j = 0; j < J; ++j) s += widen(grads, dtype, j * ld + i);
+    gbar = s / (double)J;
+    for (int64_t j = 0; j < J; ++j) {
+      double r = widen(grads, dtype, j * ld + i) - gbar;
+      c += r * r;
+    }
+    var = c / (double)(J - ddof);
+    rhs = eta * eta * (double)b_k * gbar * gbar;
+    if (var > rhs * (1.0 + band))
+      out[0] += 1;
+    else if (band > 0.0 && rhs > 0.0 && var >= rhs * (1.0 - band))
+      out[1] += 1;
+    else
+      out[2] += 1;
+  }
+  return 0;
+}
+
+/*
  * Global-norm gradient clipping, used in the paper's runs (Sec. 5, training specifications; the
  * hyper-parameter tables list "gradient clipping 1.0") but not part of Alg. 1.  The paper gives no
  * formula; this is the usual convention: the whole gradient is scaled by

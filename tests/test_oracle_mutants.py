@@ -12,14 +12,17 @@ import test_oracle_pins as P
 
 SRC = os.path.join(os.path.dirname(oracle.__file__), "normtest_oracle.c")
 
-# (name, text to find, replacement): each `find` occurs exactly once in the source
+# (name, text to find, replacement[, which occurrence]): without the fourth entry `find` must occur exactly once
 MUTANTS = [
-    ("mean_not_divided", "gbar = s / (double)J;\n    for (int64_t j = 0; j < J; ++j) {\n      double r", "gbar = s;\n    for (int64_t j = 0; j < J; ++j) {\n      double r"),
+    ("mean_not_divided", "gbar = s / (double)J;\n    for (int64_t j = 0; j < J; ++j) {\n      double r", "gbar = s;\n    for (int64_t j = 0; j < J; ++j) {\n      double r", 0),
+    ("coord_mean_not_divided", "gbar = s / (double)J;\n    for (int64_t j = 0; j < J; ++j) {\n      double r", "gbar = s;\n    for (int64_t j = 0; j < J; ++j) {\n      double r", 1),
     ("B_not_squared", "csum_add(acc + 2, s * s);", "csum_add(acc + 2, s);"),
-    ("residual_not_squared", "c += r * r;", "c += r;"),
+    ("residual_not_squared", "c += r * r;", "c += r;", 0),
+    ("coord_residual_not_squared", "c += r * r;", "c += r;", 1),
     ("A_not_squared", "a += g * g;", "a += g;"),
     ("transposed_index", "double g = widen(grads, dtype, j * ld + i);", "double g = widen(grads, dtype, i * J + j);"),
-    ("residual_other_row", "double r = widen(grads, dtype, j * ld + i) - gbar;", "double r = widen(grads, dtype, i) - gbar;"),
+    ("residual_other_row", "double r = widen(grads, dtype, j * ld + i) - gbar;", "double r = widen(grads, dtype, i) - gbar;", 0),
+    ("coord_residual_other_row", "double r = widen(grads, dtype, j * ld + i) - gbar;", "double r = widen(grads, dtype, i) - gbar;", 1),
     ("bf16_shift", "u = (uint32_t)h << 16;", "u = (uint32_t)h << 15;"),
     ("gbar_sq_over_J", "out->gbar_sq = B / (Jd * Jd);", "out->gbar_sq = B / Jd;"),
     ("ddof_ignored", "out->var_l1 = C / (double)(J - ddof);", "out->var_l1 = C / (double)J;"),
@@ -37,6 +40,11 @@ MUTANTS = [
     ("v_not_squared", "vn = beta2 * (double)v[i] + (1.0 - beta2) * g * g;", "vn = beta2 * (double)v[i] + (1.0 - beta2) * g;"),
     ("scale_ignored", "g = grad_scale * gbar;", "g = gbar;"),
     ("scale_only_first_moment", "vn = beta2 * (double)v[i] + (1.0 - beta2) * g * g;", "vn = beta2 * (double)v[i] + (1.0 - beta2) * gbar * gbar;"),
+    ("coord_rhs_without_batch", "rhs = eta * eta * (double)b_k * gbar * gbar;", "rhs = eta * eta * gbar * gbar;"),
+    ("coord_rhs_mean_not_squared", "rhs = eta * eta * (double)b_k * gbar * gbar;", "rhs = eta * eta * (double)b_k * gbar;"),
+    ("coord_ddof_ignored", "var = c / (double)(J - ddof);", "var = c / (double)J;"),
+    ("coord_equality_fails", "if (var > rhs * (1.0 + band))", "if (var >= rhs * (1.0 + band))"),
+    ("coord_inequality_flipped", "if (var > rhs * (1.0 + band))", "if (var < rhs * (1.0 + band))"),
     ("clip_never", "return c < 1.0 ? c : 1.0;", "return 1.0;"),
     ("clip_always", "return c < 1.0 ? c : 1.0;", "return c;"),
     ("clip_uses_squared_norm", "c = max_norm / (sqrt(gbar_sq) + 1e-6);", "c = max_norm / (gbar_sq + 1e-6);"),
@@ -62,6 +70,8 @@ def battery():
             checks.append(lambda c=c, b=b: P.test_golden_statistic(c, b))
     for c in adam_cases:
         checks.append(lambda c=c: P.test_golden_adamw(c))
+    for c in [c for c in P.GOLDEN_CASES if any(k.startswith("coord_") for k in c)]:
+        checks.append(lambda c=c: P.test_golden_coordinatewise(c, False))
     for J, d, b in ((3, 3, False), (4, 16, True), (5, 1, False), (8, 16, False)):
         checks.append(lambda J=J, d=d, b=b: P.test_brute_force_exact_rational(J, d, b))
     checks += [
@@ -79,6 +89,7 @@ def battery():
         P.test_scale_row_permutation_and_shard_additivity,
         P.test_long_sum_needs_compensation,
         P.test_clipped_step_matches_library_clipping,
+        lambda: P.test_coordinatewise_brute_force_and_invariants(3),
     ]
     return checks
 
@@ -121,9 +132,19 @@ def test_oracle_is_clean_under_the_undefined_behaviour_sanitizer(tmp_path, swap_
     assert "runtime error" not in err, err
 
 
-@pytest.mark.parametrize("name,find,repl", MUTANTS, ids=[m[0] for m in MUTANTS])
-def test_each_planted_mistake_is_caught(name, find, repl, tmp_path, swap_oracle):
-    text = open(SRC).read()
-    assert text.count(find) == 1, "mutation target must occur exactly once: %r" % find
-    swap_oracle(compile_variant(text.replace(find, repl), str(tmp_path / (name + ".so"))))
+def plant(text: str, find: str, repl: str, which=None) -> str:
+    if which is None:
+        assert text.count(find) == 1, "mutation target must occur exactly once: %r" % find
+        return text.replace(find, repl)
+    pos = -1
+    for _ in range(which + 1):
+        pos = text.index(find, pos + 1)
+    return text[:pos] + repl + text[pos + len(find):]
+
+
+@pytest.mark.parametrize("mutant", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_each_planted_mistake_is_caught(mutant, tmp_path, swap_oracle):
+    name, find, repl = mutant[:3]
+    text = plant(open(SRC).read(), find, repl, mutant[3] if len(mutant) > 3 else None)
+    swap_oracle(compile_variant(text, str(tmp_path / (name + ".so"))))
     assert first_failure(battery()) is not None, "no pin noticed the planted mistake %r" % name

@@ -99,6 +99,62 @@ def test_golden_adamw(case):
     assert vo[0] == pytest.approx(float(case["expect_v"]), rel=tol)
 
 
+@pytest.mark.parametrize("case", [c for c in GOLDEN_CASES if any(k.startswith("coord_") for k in c)],
+                         ids=lambda c: c["name"])
+@pytest.mark.parametrize("as_bf16", [False, True])
+def test_golden_coordinatewise(case, as_bf16):
+    G = np.array(case["g"], dtype=np.float32)
+    Gin = bf16_bits(G) if as_bf16 else G
+    n_checked = 0
+    for key, val in case.items():
+        if not key.startswith("coord_"):
+            continue
+        _, dd, bk = key.split("_")
+        fail, near, ok = oracle.coord_test(Gin, float(case["eta"]), int(bk[2:]), int(dd[4:]))
+        assert (fail, near) == (int(val), 0) and fail + ok == G.shape[1], key
+        n_checked += 1
+    assert n_checked >= 2
+
+
+@pytest.mark.parametrize("J", [2, 3, 4, 8])
+def test_coordinatewise_brute_force_and_invariants(J):
+    rng = np.random.default_rng(50 + J)
+    d = 200
+    G = rng.integers(-40, 41, size=(J, d)).astype(np.float32) / 16.0
+    G[:, :10] = G[0, :10]                       # identical entries: zero spread, passes unless the mean is zero
+    G[:, 10:14] = 0.0                           # all zero: 0 > 0 is false, passes
+    G[0, 14], G[1, 14] = 1.0, -1.0              # zero mean (for J = 2) or small mean with spread
+    for ddof in (0, 1):
+        for eta, b_k in ((Fraction(1, 2), 1), (Fraction(1, 4), 7), (Fraction(1, 8), 300)):
+            exact_fail = exact_eq = 0
+            for i in range(d):
+                col = [Fraction(float(x)) for x in G[:, i]]
+                mean = sum(col) / J
+                var = sum((x - mean) ** 2 for x in col) / (J - ddof)
+                rhs = eta * eta * b_k * mean * mean
+                exact_fail += var > rhs
+                exact_eq += (var == rhs and rhs > 0)
+            fail, near, ok = oracle.coord_test(G, float(eta), b_k, ddof)
+            assert near == 0 and fail + ok == d
+            assert exact_fail <= fail + exact_eq and fail <= exact_fail + exact_eq   # equality is decided by rounding
+            # the band only moves coordinates between the classes
+            f2, n2, o2 = oracle.coord_test(G, float(eta), b_k, ddof, band=1e-5)
+            assert f2 + n2 + o2 == d and f2 <= fail and o2 <= ok
+            # scaling every row by a power of two changes nothing
+            assert oracle.coord_test(G * np.float32(8.0), float(eta), b_k, ddof) == (fail, near, ok)
+            # a larger batch can only make coordinates pass
+            assert oracle.coord_test(G, float(eta), b_k * 4, ddof)[0] <= fail
+    # if every coordinate passes, so does the aggregate test (sum the inequalities)
+    Gp = np.tile(np.array([[1.0], [1.25]], dtype=np.float32), (1, 50))
+    assert oracle.coord_test(Gp, 0.5, 4, 1)[0] == 0
+    A, B, C = oracle.stats(Gp)
+    assert oracle.decide(A, B, C, 2, 0.5, 4, 0, 1, 1).passed
+    # shards add up
+    whole = oracle.coord_test(G, 0.25, 7, 1)
+    parts = [oracle.coord_test(np.ascontiguousarray(G[:, lo:hi]), 0.25, 7, 1) for lo, hi in ((0, 33), (33, 150), (150, d))]
+    assert whole == tuple(sum(p[k] for p in parts) for k in range(3))
+
+
 # ---------------------------------------------------------------- brute force, exact rationals
 
 @pytest.mark.parametrize("J", [2, 3, 4, 5, 8])
