@@ -36,7 +36,8 @@ enum {
   NT_DO_STATS = 1u,   /* compute A, B, C (and, unless NT_PARTIAL, the test)                      */
   NT_DO_ADAMW = 2u,   /* update w, m, v in place with AdamW on gbar                              */
   NT_PARTIAL = 4u,    /* FSDP shard: stop at the additive sums A, B, C; decide in normtest_combine */
-  NT_WRITE_GBAR = 8u  /* also store gbar (fp32[d]) to gbar_out                                   */
+  NT_WRITE_GBAR = 8u, /* also store gbar (fp32[d]) to gbar_out                                   */
+  NT_COORD_TEST = 16u /* also count the coordinates that fail the coordinate-wise form of the test */
 };
 
 /* nt_result.status bits */
@@ -71,7 +72,7 @@ typedef struct {
   int64_t round_to;                           /* J*M (workers x accumulation steps): next_b is a multiple;     */
                                               /* 1 = the plain ceiling rule of Sec. 3.1                        */
   int32_t ddof;                               /* 0: variance / J (Alg. 1);  1: / (J-1) (sample variance)       */
-  uint32_t flags;                             /* NT_DO_* | NT_PARTIAL | NT_WRITE_GBAR                          */
+  uint32_t flags;                             /* NT_DO_* | NT_PARTIAL | NT_WRITE_GBAR | NT_COORD_TEST          */
 } nt_hyper;
 
 /* Where this call's coordinates sit in the full parameter vector (Sec. 3.3).  Informational: the sums
@@ -89,6 +90,9 @@ typedef struct {
   double T;                /* var_l1 / (eta^2 gbar_sq)                                                            */
   double clip_coef;        /* factor applied to gbar before AdamW: 1 unless normtest_step_clipped cut the norm    */
   int64_t next_b;          /* b_{k+1}                                                                             */
+  int64_t coord_fail;      /* NT_COORD_TEST: number of coordinates i with Var_i / b_k > eta^2 gbar_i^2, the          */
+                           /* coordinate-wise condition of Sec. 4 / Prop. 1 with the estimators of the aggregate     */
+                           /* test, decided per coordinate in fp32; additive over shards; -1 if not requested        */
   int32_t pass;            /* 1 iff not (T > b_k)                                                                 */
   uint32_t status;         /* NT_STATUS_* bits                                                                    */
 } nt_result;

@@ -15,7 +15,7 @@ import torch
 from . import build as _build
 
 NT_F32, NT_BF16 = 0, 1
-NT_DO_STATS, NT_DO_ADAMW, NT_PARTIAL, NT_WRITE_GBAR = 1, 2, 4, 8
+NT_DO_STATS, NT_DO_ADAMW, NT_PARTIAL, NT_WRITE_GBAR, NT_COORD_TEST = 1, 2, 4, 8, 16
 NT_STATUS_NONFINITE = 1
 NT_STATUS_ZERO_GRAD_NORM = 2
 NT_STATUS_CLAMPED = 4
@@ -46,7 +46,7 @@ class nt_result(ctypes.Structure):
         ("A", ctypes.c_double), ("B", ctypes.c_double), ("C", ctypes.c_double),
         ("A_lo", ctypes.c_double), ("B_lo", ctypes.c_double), ("C_lo", ctypes.c_double),
         ("gbar_sq", ctypes.c_double), ("var_l1", ctypes.c_double), ("T", ctypes.c_double),
-        ("clip_coef", ctypes.c_double), ("next_b", ctypes.c_int64), ("pass_", ctypes.c_int32), ("status", ctypes.c_uint32),
+        ("clip_coef", ctypes.c_double), ("next_b", ctypes.c_int64), ("coord_fail", ctypes.c_int64), ("pass_", ctypes.c_int32), ("status", ctypes.c_uint32),
     ]
 
     def as_dict(self) -> dict:

@@ -85,6 +85,7 @@
 #define NT_MCHUNK 16          // beyond that, rows are walked this many at a time (2 .. NT_JCHUNK + 1; 16 measured best)
 #endif
 #define NT_FIN_THREADS 1024
+#define NT_NV 4                // values per tile partial: A, B, C and the count of failing coordinates
 #define NT_GROUP_THREADS 256   // first-stage reduction: threads per block
 #define NT_GROUP_TILES 2048    // ... and tile partials per block
 #define NT_DIRECT_TILES 4096   // up to this many tiles the finalize kernel reads the tile partials itself
@@ -145,6 +146,7 @@ struct StepParams {
   float step_size;                // lr / (1 - beta1^k)
   float inv_sqrt_bc2;             // 1 / sqrt(1 - beta2^k)
   float eps;
+  float coord_thr;   // eta^2 b_k (J - ddof) when the coordinate-wise count is wanted, else negative
 };
 
 // Start of gradient row j: base + j*ld elements, or the j-th entry of the caller's pointer table.
@@ -193,31 +195,39 @@ __device__ inline double wave_sum(double x) {
 // Block partial of one tile -> partials[3*tile ..].  `buf` alternates between tiles so that one
 // barrier per tile is enough.
 template <int BLOCK>
-__device__ inline void tile_reduce(double a, double b, double c, double (*red)[BLOCK / 64][3], int buf,
+__device__ inline void tile_reduce(double a, double b, double c, double n, double (*red)[BLOCK / 64][NT_NV], int buf,
                                    double* partials, int64_t tile) {
   a = wave_sum(a);
   b = wave_sum(b);
   c = wave_sum(c);
+  n = wave_sum(n);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (lane == 0) {
     red[buf][wave][0] = a;
     red[buf][wave][1] = b;
     red[buf][wave][2] = c;
+    red[buf][wave][3] = n;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    double sa = red[buf][0][0], sb = red[buf][0][1], sc = red[buf][0][2];
+    double sa = red[buf][0][0], sb = red[buf][0][1], sc = red[buf][0][2], sn = red[buf][0][3];
 #pragma unroll
     for (int wv = 1; wv < BLOCK / 64; ++wv) {
       sa += red[buf][wv][0];
       sb += red[buf][wv][1];
       sc += red[buf][wv][2];
+      sn += red[buf][wv][3];
     }
-    partials[3 * tile + 0] = sa;
-    partials[3 * tile + 1] = sb;
-    partials[3 * tile + 2] = sc;
+    partials[NT_NV * tile + 0] = sa;
+    partials[NT_NV * tile + 1] = sb;
+    partials[NT_NV * tile + 2] = sc;
+    partials[NT_NV * tile + 3] = sn;
   }
 }
+
+// Coordinate-wise form of the test (Sec. 4, Prop. 1): a coordinate fails when its centred sum c exceeds
+// eta^2 b_k (J - ddof) gbar^2.  thr < 0 switches the count off.
+__device__ inline int coord_fails(float thr, float c, float gb) { return (thr >= 0.f && c > thr * (gb * gb)) ? 1 : 0; }
 
 // ---------------------------------------------------------------------------------------------
 // Guarded tile: any J, any alignment, ragged end.  Same lane-to-coordinate map and the same
@@ -291,11 +301,12 @@ __device__ inline void coord_stats_generic(const StepParams& p, int64_t i, doubl
 }
 
 template <class GT, int MODE, int BLOCK, bool TABLE>
-__device__ inline void guarded_tile(const StepParams& p, int64_t tile, int tile_coords, double (*red)[BLOCK / 64][3],
+__device__ inline void guarded_tile(const StepParams& p, int64_t tile, int tile_coords, double (*red)[BLOCK / 64][NT_NV],
                                     int buf) {
   constexpr int VEC = GT::VEC;
   const int iters = tile_coords / (BLOCK * VEC);
   double accA = 0.0, accB = 0.0, accC = 0.0;
+  int nfail = 0;
   for (int it = 0; it < iters; ++it) {
     const int64_t i0 = tile * (int64_t)tile_coords + ((int64_t)it * BLOCK + threadIdx.x) * VEC;
     float a[VEC], b[VEC], c[VEC];
@@ -312,6 +323,7 @@ __device__ inline void guarded_tile(const StepParams& p, int64_t tile, int tile_
         a[e] = aa;
         b[e] = sf * sf;
         c[e] = M2;
+        nfail += coord_fails(p.coord_thr, M2, gb);
         if constexpr (MODE != MODE_STATS) {
           float w = p.w[i], m = p.m[i], v = p.v[i];
           adamw_coord(p, gb, w, m, v);
@@ -328,7 +340,7 @@ __device__ inline void guarded_tile(const StepParams& p, int64_t tile, int tile_
       accC += (double)lane_tree<VEC>(c);
     }
   }
-  if constexpr (MODE != MODE_ADAMW) tile_reduce<BLOCK>(accA, accB, accC, red, buf, p.partials, tile);
+  if constexpr (MODE != MODE_ADAMW) tile_reduce<BLOCK>(accA, accB, accC, (double)nfail, red, buf, p.partials, tile);
 }
 
 // AdamW on VEC coordinates whose state was loaded as 16-byte vectors, then the 16-byte stores.
@@ -372,10 +384,11 @@ __device__ inline void gbar_store(const StepParams& p, int64_t i0, const float* 
 // The row sum is carried in fp64 so that the mean is correctly rounded even when the rows cancel.
 // ---------------------------------------------------------------------------------------------
 template <class GT, int J, int MODE, int BLOCK, int ITERS, bool TABLE>
-__device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red)[BLOCK / 64][3], int buf) {
+__device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red)[BLOCK / 64][NT_NV], int buf) {
   constexpr int VEC = GT::VEC;
   constexpr int TILE = BLOCK * VEC * ITERS;
   double accA = 0.0, accB = 0.0, accC = 0.0;
+  int nfail = 0;
   NT_PRAGMA_UNROLL(NT_UNROLL)
   for (int it = 0; it < ITERS; ++it) {
     const int64_t i0 = tile * TILE + ((int64_t)it * BLOCK + threadIdx.x) * VEC;
@@ -419,6 +432,7 @@ __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red
       for (int e = 0; e < VEC; ++e) {
         const float sf = (float)s[e];
         b[e] = sf * sf;
+        nfail += coord_fails(p.coord_thr, c[e], gb[e]);
       }
       accA += (double)lane_tree<VEC>(a);
       accB += (double)lane_tree<VEC>(b);
@@ -427,7 +441,7 @@ __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red
     if constexpr (MODE != MODE_STATS) adamw_store<VEC>(p, i0, gb, sw, sm, sv);
     if (p.gbar) gbar_store<VEC>(p, i0, gb);
   }
-  if constexpr (MODE != MODE_ADAMW) tile_reduce<BLOCK>(accA, accB, accC, red, buf, p.partials, tile);
+  if constexpr (MODE != MODE_ADAMW) tile_reduce<BLOCK>(accA, accB, accC, (double)nfail, red, buf, p.partials, tile);
 #if NT_ADAMW_BARRIER
   if constexpr (MODE == MODE_ADAMW) __syncthreads();
 #endif
@@ -459,11 +473,12 @@ __device__ inline void chunk_accumulate(const typename GT::raw_t* raw, int nb, c
 }
 
 template <class GT, int MODE, int BLOCK, int ITERS, bool TABLE>
-__device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double (*red)[BLOCK / 64][3], int buf) {
+__device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double (*red)[BLOCK / 64][NT_NV], int buf) {
   constexpr int VEC = GT::VEC;
   constexpr int TILE = BLOCK * VEC * ITERS;
   const int J = p.J;
   double accA = 0.0, accB = 0.0, accC = 0.0;
+  int nfail = 0;
 #pragma unroll 1
   for (int it = 0; it < ITERS; ++it) {
     const int64_t i0 = tile * TILE + ((int64_t)it * BLOCK + threadIdx.x) * VEC;
@@ -509,6 +524,7 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
       for (int e = 0; e < VEC; ++e) {
         const float sf = (float)S[e];
         b[e] = sf * sf;
+        nfail += coord_fails(p.coord_thr, M2[e], gb[e]);
       }
       accA += (double)lane_tree<VEC>(a);
       accB += (double)lane_tree<VEC>(b);
@@ -526,7 +542,7 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
     }
     if (p.gbar) gbar_store<VEC>(p, i0, gb);
   }
-  if constexpr (MODE != MODE_ADAMW) tile_reduce<BLOCK>(accA, accB, accC, red, buf, p.partials, tile);
+  if constexpr (MODE != MODE_ADAMW) tile_reduce<BLOCK>(accA, accB, accC, (double)nfail, red, buf, p.partials, tile);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -539,7 +555,7 @@ template <class GT, int J_T, int MODE, int BLOCK, int ITERS, bool TABLE>
 __global__ __launch_bounds__(BLOCK, NT_WAVES_PER_EU) void k_step(StepParams p, int64_t nfull, int64_t ntiles) {
   constexpr int TILE = BLOCK * GT::VEC * ITERS;
   static_assert(NT_TILE_MAX % TILE == 0, "tile sizes must divide NT_TILE_MAX");
-  __shared__ double red[2][BLOCK / 64][3];
+  __shared__ double red[2][BLOCK / 64][NT_NV];
   int buf = 0;
   if constexpr (TABLE) {
     // the host cannot see the row pointers: the fast tiles need all of them 16-byte aligned
@@ -655,32 +671,34 @@ __device__ inline dd dd_wave_sum(dd x) {
   return x;
 }
 
-// Sum of n entries of 3 sums each, read with `stride` doubles per entry: stride 3 = plain tile
-// partials {A, B, C}, stride 6 = double-double group partials {A, A_lo, B, B_lo, C, C_lo}.
-// All threads of the block take part; thread 0 returns the totals in tot[3].
+// Sum of n entries of NT_NV values each.  packed = false: plain tile partials {A, B, C, n_fail};
+// packed = true: double-double group partials {A, A_lo, B, B_lo, C, C_lo, n, n_lo}.
+// All threads of the block take part; thread 0 returns the totals in tot[NT_NV].
 template <int THREADS>
-__device__ inline void block_dd_sum(const double* in, int64_t n, int stride, double (*sh)[6], dd* tot) {
-  dd acc[3] = {{0.0, 0.0}, {0.0, 0.0}, {0.0, 0.0}};
+__device__ inline void block_dd_sum(const double* in, int64_t n, bool packed, double (*sh)[2 * NT_NV], dd* tot) {
+  dd acc[NT_NV];
+#pragma unroll
+  for (int k = 0; k < NT_NV; ++k) acc[k] = {0.0, 0.0};
   for (int64_t t = threadIdx.x; t < n; t += THREADS) {
 #pragma unroll
-    for (int k = 0; k < 3; ++k) {
+    for (int k = 0; k < NT_NV; ++k) {
       dd x;
-      if (stride == 3) {
-        x.hi = in[3 * t + k];
+      if (!packed) {
+        x.hi = in[NT_NV * t + k];
         x.lo = 0.0;
       } else {
-        x.hi = in[6 * t + 2 * k];
-        x.lo = in[6 * t + 2 * k + 1];
+        x.hi = in[2 * NT_NV * t + 2 * k];
+        x.lo = in[2 * NT_NV * t + 2 * k + 1];
       }
       acc[k] = dd_add(acc[k], x);
     }
   }
 #pragma unroll
-  for (int k = 0; k < 3; ++k) acc[k] = dd_wave_sum(acc[k]);
+  for (int k = 0; k < NT_NV; ++k) acc[k] = dd_wave_sum(acc[k]);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (lane == 0) {
 #pragma unroll
-    for (int k = 0; k < 3; ++k) {
+    for (int k = 0; k < NT_NV; ++k) {
       sh[wave][2 * k] = acc[k].hi;
       sh[wave][2 * k + 1] = acc[k].lo;
     }
@@ -688,7 +706,7 @@ __device__ inline void block_dd_sum(const double* in, int64_t n, int stride, dou
   __syncthreads();
   if (threadIdx.x == 0) {
 #pragma unroll
-    for (int k = 0; k < 3; ++k) {
+    for (int k = 0; k < NT_NV; ++k) {
       tot[k].hi = sh[0][2 * k];
       tot[k].lo = sh[0][2 * k + 1];
       for (int wv = 1; wv < THREADS / 64; ++wv) {
@@ -703,30 +721,33 @@ __device__ inline void block_dd_sum(const double* in, int64_t n, int stride, dou
 // double-double group partial.
 __global__ __launch_bounds__(NT_GROUP_THREADS) void k_reduce_groups(const double* partials, int64_t ntiles,
                                                                     double* groups) {
-  __shared__ double sh[NT_GROUP_THREADS / 64][6];
+  __shared__ double sh[NT_GROUP_THREADS / 64][2 * NT_NV];
   const int64_t t0 = (int64_t)blockIdx.x * NT_GROUP_TILES;
   const int64_t n = (ntiles - t0 < NT_GROUP_TILES) ? (ntiles - t0) : NT_GROUP_TILES;
-  dd tot[3];
-  block_dd_sum<NT_GROUP_THREADS>(partials + 3 * t0, n, 3, sh, tot);
+  dd tot[NT_NV];
+  block_dd_sum<NT_GROUP_THREADS>(partials + NT_NV * t0, n, false, sh, tot);
   if (threadIdx.x == 0) {
 #pragma unroll
-    for (int k = 0; k < 3; ++k) {
-      groups[6 * (int64_t)blockIdx.x + 2 * k] = tot[k].hi;
-      groups[6 * (int64_t)blockIdx.x + 2 * k + 1] = tot[k].lo;
+    for (int k = 0; k < NT_NV; ++k) {
+      groups[2 * NT_NV * (int64_t)blockIdx.x + 2 * k] = tot[k].hi;
+      groups[2 * NT_NV * (int64_t)blockIdx.x + 2 * k + 1] = tot[k].lo;
     }
   }
 }
 
 // One block: partials (tile or group) -> A, B, C in double-double, then the decision.
-__global__ __launch_bounds__(NT_FIN_THREADS) void k_finalize(const double* in, int64_t n, int stride, DecideParams q,
+__global__ __launch_bounds__(NT_FIN_THREADS) void k_finalize(const double* in, int64_t n, bool packed, DecideParams q,
                                                              nt_result* out) {
-  __shared__ double sh[NT_FIN_THREADS / 64][6];
+  __shared__ double sh[NT_FIN_THREADS / 64][2 * NT_NV];
   const bool stats = (q.flags & NT_DO_STATS) != 0;
-  dd tot[3] = {{0.0, 0.0}, {0.0, 0.0}, {0.0, 0.0}};
-  if (stats) block_dd_sum<NT_FIN_THREADS>(in, n, stride, sh, tot);
+  dd tot[NT_NV];
+#pragma unroll
+  for (int k = 0; k < NT_NV; ++k) tot[k] = {0.0, 0.0};
+  if (stats) block_dd_sum<NT_FIN_THREADS>(in, n, packed, sh, tot);
   if (threadIdx.x != 0) return;
   nt_result r;
   r.status = 0;
+  r.coord_fail = (stats && (q.flags & NT_COORD_TEST)) ? (int64_t)tot[3].hi : -1;
   const double nan = __builtin_nan("");
   if (!stats) {
     r.A = r.B = r.C = r.A_lo = r.B_lo = r.C_lo = nan;
@@ -830,10 +851,10 @@ inline int64_t min_tile_coords(int64_t J) {
 
 bool hyper_ok(const nt_hyper* h, int64_t J) {
   if (!h) return false;
-  const uint32_t known = NT_DO_STATS | NT_DO_ADAMW | NT_PARTIAL | NT_WRITE_GBAR;
+  const uint32_t known = NT_DO_STATS | NT_DO_ADAMW | NT_PARTIAL | NT_WRITE_GBAR | NT_COORD_TEST;
   if (h->flags & ~known) return false;
   if (!(h->flags & (NT_DO_STATS | NT_DO_ADAMW))) return false;
-  if ((h->flags & NT_PARTIAL) && !(h->flags & NT_DO_STATS)) return false;
+  if ((h->flags & (NT_PARTIAL | NT_COORD_TEST)) && !(h->flags & NT_DO_STATS)) return false;
   if (!(h->eta > 0.0) || !std::isfinite(h->eta)) return false;
   if (h->b_k < 1 || h->b_max < 0 || h->round_to < 1) return false;
   if (h->ddof != 0 && h->ddof != 1) return false;
@@ -890,7 +911,7 @@ size_t normtest_workspace_bytes(int64_t J, int64_t d) {
   const int64_t ntiles = (d + tc - 1) / tc;
   const int64_t n = ntiles > 0 ? ntiles : 1;
   const int64_t ngroups = ntiles > NT_DIRECT_TILES ? (ntiles + NT_GROUP_TILES - 1) / NT_GROUP_TILES : 0;
-  return (size_t)(n * 3 + ngroups * 6) * sizeof(double);
+  return (size_t)(n * NT_NV + ngroups * 2 * NT_NV) * sizeof(double);
 }
 
 // AdamW constants in fp64 on the host, rounded once to fp32.
@@ -956,6 +977,9 @@ static int enqueue_step(const void* grads, bool table, nt_dtype gdtype, int64_t 
   p.partials = (double*)workspace;
   p.inv_J = 1.0 / (double)J;
   if (flags & NT_DO_ADAMW) fill_adamw_params(p, hyper);
+  p.coord_thr = (flags & NT_COORD_TEST)
+                    ? (float)(hyper->eta * hyper->eta * (double)hyper->b_k * (double)(J - hyper->ddof))
+                    : -1.0f;
 
   if (ntiles > 0) {
     // row alignment: checked here for a strided matrix, by the kernel itself for a pointer table
@@ -987,13 +1011,13 @@ static int enqueue_step(const void* grads, bool table, nt_dtype gdtype, int64_t 
   const double* partials = (const double*)workspace;
   if ((flags & NT_DO_STATS) && ntiles > NT_DIRECT_TILES) {
     const int64_t ngroups = (ntiles + NT_GROUP_TILES - 1) / NT_GROUP_TILES;
-    double* groups = (double*)workspace + 3 * ntiles;
+    double* groups = (double*)workspace + NT_NV * ntiles;
     hipLaunchKernelGGL(k_reduce_groups, dim3((unsigned)ngroups), dim3(NT_GROUP_THREADS), 0, st, partials, ntiles, groups);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_code(e);
-    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(NT_FIN_THREADS), 0, st, (const double*)groups, ngroups, 6, q, result_dev);
+    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(NT_FIN_THREADS), 0, st, (const double*)groups, ngroups, true, q, result_dev);
   } else {
-    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(NT_FIN_THREADS), 0, st, partials, ntiles, 3, q, result_dev);
+    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(NT_FIN_THREADS), 0, st, partials, ntiles, false, q, result_dev);
   }
   return hip_code(hipGetLastError());
 }
@@ -1082,8 +1106,10 @@ int normtest_combine(const nt_result* partials, int32_t n, int64_t J, const nt_h
     return NT_ERR_BAD_ARG;
   dd tot[3] = {{0.0, 0.0}, {0.0, 0.0}, {0.0, 0.0}};
   uint32_t status = 0;
+  int64_t coord_fail = 0;  // the count is additive over shards; missing in one shard = missing in the total
   for (int32_t s = 0; s < n; ++s) {
     if (partials[s].status & NT_STATUS_NO_STATS) return NT_ERR_BAD_ARG;
+    coord_fail = (coord_fail < 0 || partials[s].coord_fail < 0) ? -1 : coord_fail + partials[s].coord_fail;
     const dd a = {partials[s].A, partials[s].A_lo}, b = {partials[s].B, partials[s].B_lo},
              c = {partials[s].C, partials[s].C_lo};
     tot[0] = dd_add(tot[0], a);
@@ -1117,6 +1143,7 @@ int normtest_combine(const nt_result* partials, int32_t n, int64_t J, const nt_h
   q.ddof = hyper->ddof;
   q.flags = NT_DO_STATS;
   decide(q, &r);
+  r.coord_fail = coord_fail;
   *out = r;
   return NT_OK;
 }

@@ -129,3 +129,26 @@ def oracle_adamw_check(grads, d, w0, m0, v0, w1, m1, v1, h: synth.Hyper, ranges=
         return sum(work(r) for r in ranges)
     with ThreadPoolExecutor(threads) as ex:
         return sum(ex.map(work, ranges))
+
+
+def oracle_coord_counts(grads, d, h: synth.Hyper, band: float = STATS_RTOL, chunk: int = ORACLE_CHUNK,
+                        threads: int | None = None):
+    """(fail, near, pass) counts of the coordinate-wise test over the first d columns, streamed in chunks."""
+    threads = n_threads() if threads is None else threads
+    ranges = [(lo, min(d, lo + chunk)) for lo in range(0, d, chunk)]
+
+    def work(r):
+        return oracle.coord_test(synth.grads_as_numpy(grads, r[0], r[1]), h.eta, h.b_k, h.ddof, band)
+
+    if len(ranges) <= 1 or threads == 1:
+        parts = [work(r) for r in ranges]
+    else:
+        with ThreadPoolExecutor(threads) as ex:
+            parts = list(ex.map(work, ranges))
+    return tuple(sum(p[k] for p in parts) for k in range(3))
+
+
+def assert_coord_count(got: int, counts):
+    """The kernel decides each coordinate in fp32: coordinates within the band of equality may fall either way."""
+    fail, near, ok = counts
+    assert fail <= got <= fail + near, "coord_fail %d not in [%d, %d]" % (got, fail, fail + near)

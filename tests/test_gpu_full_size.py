@@ -17,7 +17,9 @@ DEV = "cuda:0"
 FULL = B.NT_DO_STATS | B.NT_DO_ADAMW
 
 
-def run_and_check(wl: synth.Workload, flags=FULL, shard=None):
+def run_and_check(wl: synth.Workload, flags=FULL, shard=None, coord=False):
+    if coord:
+        flags |= B.NT_COORD_TEST
     h = wl.hyper
     t0 = time.time()
     w0, m0, v0 = wl.w.clone(), wl.m.clone(), wl.v.clone()
@@ -43,6 +45,13 @@ def run_and_check(wl: synth.Workload, flags=FULL, shard=None):
     t3 = time.time()
     print("%s: J=%d d=%d  gpu %.1fs  oracle stats %.1fs  adamw compare %.1fs  T=%.6g oracle T=%.6g" % (
         wl.name, wl.J, wl.d, t1 - t0, t2 - t1, t3 - t2, res["T"], ref.dec.T), flush=True)
+    if coord:
+        counts = H.oracle_coord_counts(wl.grads, wl.d, h)
+        H.assert_coord_count(res["coord_fail"], counts)
+        print("   coordinate-wise: %d fail (oracle %d + %d near) of %d" % (res["coord_fail"], counts[0], counts[1], wl.d),
+              flush=True)
+    else:
+        assert res["coord_fail"] == -1
     # the identity C = A - B/J holds for the GPU's own sums too (it never forms C that way)
     assert res["C"] == pytest.approx(res["A"] - res["B"] / wl.J, rel=1e-5 * res["A"] / res["C"])
     return res, ref
@@ -66,7 +75,7 @@ def test_flat_1p5b_full():
     """The headline workload: J=8 bf16, d=1.5e9 (ragged: not a multiple of the tile)."""
     wl = synth.flat_1p5b(device=DEV)
     assert wl.d == 1_500_000_000 and wl.d % B.normtest_tile_coords(8) != 0
-    run_and_check(wl)
+    run_and_check(wl, coord=True)
 
 
 def test_fsdp_shard_full():
@@ -81,7 +90,7 @@ def test_per_sample_full():
     """b = 512 per-example gradients of a 2^24 vector with Student-t(3) noise: the row-walking kernel."""
     wl = synth.per_sample(device=DEV)
     assert wl.J == 512 and wl.d == 1 << 24
-    run_and_check(wl)
+    run_and_check(wl, coord=True)
 
 
 def test_paper_model_sizes():

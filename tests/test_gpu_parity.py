@@ -379,6 +379,62 @@ def test_adamw_gbar_misaligned_matches_aligned():
         assert torch.equal(a, b)
 
 
+# ------------------------------------------------------------------ coordinate-wise form of the test
+
+@pytest.mark.parametrize("J,gdtype,d,sigma,b_k", [
+    (8, torch.bfloat16, 5 * 16384 + 321, 1e-2, 256), (8, torch.bfloat16, 40_000, 1e-3, 32),
+    (4, torch.float32, 1 << 20, 1e-2, 32), (4, torch.float32, 1 << 20, 1e-3, 8192),
+    (16, torch.bfloat16, 70_001, 3e-3, 64), (40, torch.bfloat16, 30_003, 1e-2, 512), (3, torch.float32, 9_999, 1e-2, 1)])
+def test_coordinatewise_count_matches_oracle(J, gdtype, d, sigma, b_k):
+    wl = synth.make("t", J, d, gdtype=gdtype, sigma=sigma, seed=60 + J, device=DEV,
+                    hyper=synth.Hyper(b_k=b_k, round_to=1, b_max=0))
+    state0 = [t.clone() for t in (wl.w, wl.m, wl.v)]
+    plain = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper)
+    plain_state = [t.clone() for t in (wl.w, wl.m, wl.v)]
+    assert plain["coord_fail"] == -1
+    counts = H.oracle_coord_counts(wl.grads, d, wl.hyper)
+    assert sum(counts) == d and counts[1] < max(10, d // 1000)      # the band must stay a thin sliver
+    for mode_flags in (FULL, B.NT_DO_STATS):
+        for t, s0 in zip((wl.w, wl.m, wl.v), state0):
+            t.copy_(s0)
+        res = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper, flags=mode_flags | B.NT_COORD_TEST)
+        H.assert_coord_count(res["coord_fail"], counts)
+        if mode_flags == FULL:                                          # asking for the count changes nothing else
+            for k in ("A", "B", "C", "T", "next_b", "pass", "status"):
+                assert res[k] == plain[k], k
+            for a, b in zip((wl.w, wl.m, wl.v), plain_state):
+                assert torch.equal(a, b)
+
+
+def test_coordinatewise_count_degenerate_and_sharded():
+    J, d = 8, 3 * 16384 + 500
+    wl = synth.make("t", J, d, gdtype=torch.bfloat16, sigma=1e-2, seed=61, device=DEV, hyper=synth.Hyper(b_k=64))
+    # identical rows: no spread, nothing fails; all-zero coordinates: 0 > 0 is false
+    same = wl.grads[0:1].repeat(J, 1).contiguous()
+    same[:, :100] = 0
+    res = gpu_step(same, wl.w, wl.m, wl.v, wl.hyper, flags=B.NT_DO_STATS | B.NT_COORD_TEST)
+    assert res["coord_fail"] == 0
+    # zero mean with spread fails whatever the batch size
+    same[0, :100] = 1.0
+    same[1, :100] = -1.0
+    res = gpu_step(same, wl.w, wl.m, wl.v, wl.hyper, flags=B.NT_DO_STATS | B.NT_COORD_TEST)
+    assert res["coord_fail"] == 100
+    # shards: counts add up in normtest_combine, and the guarded (misaligned) path counts the same
+    whole = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper, flags=B.NT_DO_STATS | B.NT_COORD_TEST)
+    cuts = [0, 16384, 2 * 16384, d]
+    parts = []
+    for lo, hi in zip(cuts[:-1], cuts[1:]):
+        r = B.normtest_step(wl.grads[:, lo:hi], None, None, None,
+                            hyper_of(wl.hyper, B.NT_DO_STATS | B.NT_PARTIAL | B.NT_COORD_TEST))
+        torch.cuda.synchronize()
+        parts.append(B.read_result(r))
+    assert B.normtest_combine(parts, J, hyper_of(wl.hyper)).coord_fail == whole["coord_fail"]
+    big = torch.zeros((J, d + 1), dtype=torch.bfloat16, device=DEV)
+    big[:, 1:] = wl.grads
+    off = gpu_step(big[:, 1:], wl.w, wl.m, wl.v, wl.hyper, flags=B.NT_DO_STATS | B.NT_COORD_TEST)
+    assert off["coord_fail"] == whole["coord_fail"]
+
+
 # ------------------------------------------------------------------ rows given as separate allocations
 
 @pytest.mark.parametrize("J,gdtype,flags", [(8, torch.bfloat16, FULL), (4, torch.float32, FULL),

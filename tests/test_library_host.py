@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported():
 
 def test_struct_layouts_match_header():
     assert ctypes.sizeof(B.nt_hyper) == 6 * 8 + 4 * 8 + 4 + 4
-    assert ctypes.sizeof(B.nt_result) == 10 * 8 + 8 + 4 + 4
+    assert ctypes.sizeof(B.nt_result) == 10 * 8 + 8 + 8 + 4 + 4
     assert ctypes.sizeof(B.nt_shard_info) == 4 + 4 + 8 + 8
 
 
@@ -44,9 +44,9 @@ def test_workspace_and_tiles():
         prev = 0
         for d in (0, 1, tc, tc + 1, 5000 * tc, 1_500_000_000):
             need = B.normtest_workspace_bytes(J, d)
-            # three doubles per tile; tiles are at most tc and at least 1024 coordinates; plus a small second level
-            lo = 24 * max(1, -(-d // tc))
-            hi = 24 * max(1, -(-d // 1024))
+            # four doubles per tile; tiles are at most tc and at least 1024 coordinates; plus a small second level
+            lo = 32 * max(1, -(-d // tc))
+            hi = 32 * max(1, -(-d // 1024))
             assert lo <= need <= hi + hi // 256 + 64
             assert need >= prev and need % 8 == 0
             prev = need
@@ -77,10 +77,11 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert _call(gdtype=B.NT_BF16, grads=0x1001) == bad
     assert _call(w=0x2002) == bad
     assert _call(gdtype=7) == B.NT_ERR_UNSUPPORTED
-    assert _call(ws_bytes=8) == B.NT_ERR_WORKSPACE_TOO_SMALL
+    assert _call(ws_bytes=24) == B.NT_ERR_WORKSPACE_TOO_SMALL
     for kw in (dict(eta=0.0), dict(eta=-1.0), dict(eta=math.nan), dict(step=0), dict(b_k=0), dict(b_max=-1),
                dict(round_to=0), dict(ddof=2), dict(beta1=1.0), dict(beta2=-0.1), dict(lr=-1.0),
                dict(eps=-1e-8), dict(weight_decay=math.inf), dict(flags=0), dict(flags=64 | FULL),
+               dict(flags=B.NT_COORD_TEST | B.NT_DO_ADAMW),
                dict(flags=B.NT_PARTIAL | B.NT_DO_ADAMW)):
         args = dict(step=1, b_k=32, flags=FULL)
         args.update(kw)
@@ -229,6 +230,14 @@ def test_combine_adds_shards_in_double_double():
     p2 = [_part(x, x, x) for x in sorted(xs)]
     o1, o2 = B.normtest_combine(p1, 4, hy), B.normtest_combine(p2, 4, hy)
     assert o1.A == o2.A == math.fsum(xs)
+
+
+def test_combine_adds_coordinate_counts():
+    hy = B.make_hyper(eta=0.1, b_k=32)
+    parts = [B.nt_result(A=1.0, B=1.0, C=1.0, coord_fail=k) for k in (3, 0, 11)]
+    assert B.normtest_combine(parts, 4, hy).coord_fail == 14
+    parts[1].coord_fail = -1
+    assert B.normtest_combine(parts, 4, hy).coord_fail == -1
 
 
 def test_combine_rejects_bad_input():
