@@ -36,6 +36,12 @@
 #ifndef NT_ITERS_STATS
 #define NT_ITERS_STATS 8
 #endif
+#ifndef NT_BLOCK_STATS_GBAR
+#define NT_BLOCK_STATS_GBAR 512 // statistics that also store gbar (phase 1 of the clipped variant): one write stream
+#endif                          // changes the optimum to shorter tiles
+#ifndef NT_ITERS_STATS_GBAR
+#define NT_ITERS_STATS_GBAR 2
+#endif
 #ifndef NT_BLOCK_ADAMW
 #define NT_BLOCK_ADAMW 1024   // threads per block, J <= 16, AdamW only (test skipped)
 #endif
@@ -75,7 +81,9 @@
 
 #define NT_VEC 4              // coordinates per lane and sweep: 16-byte fp32 accesses, 8-byte bf16 row loads
 #define NT_TILE_MAX 16384      // every tile size divides this: the alignment that keeps shard results bit-identical
+#ifndef NT_AUX_BLOCK
 #define NT_AUX_BLOCK 1024     // threads per block of the AdamW-from-gbar and copy kernels
+#endif
 
 #define NT_PRAGMA_(x) _Pragma(#x)
 #define NT_PRAGMA_UNROLL(n) NT_PRAGMA_(unroll n)
@@ -837,16 +845,23 @@ struct TileCfg {
   int block, iters;
   int64_t coords() const { return (int64_t)block * NT_VEC * iters; }
 };
-inline TileCfg tile_cfg(int64_t J, int mode) {
+inline TileCfg tile_cfg(int64_t J, int mode, bool gbar) {
   if (J > NT_JCHUNK) return {NT_BLOCK_LARGE, NT_ITERS_LARGE};
+  if (mode == MODE_STATS && gbar) return {NT_BLOCK_STATS_GBAR, NT_ITERS_STATS_GBAR};
   if (mode == MODE_STATS) return {NT_BLOCK_STATS, NT_ITERS_STATS};
   if (mode == MODE_ADAMW) return {NT_BLOCK_ADAMW, NT_ITERS_ADAMW};
   return {NT_BLOCK, NT_ITERS};
 }
 // smallest tile any mode uses for this J: sizes the workspace
 inline int64_t min_tile_coords(int64_t J) {
-  const int64_t a = tile_cfg(J, MODE_FULL).coords(), b = tile_cfg(J, MODE_STATS).coords();
-  return a < b ? a : b;
+  int64_t best = tile_cfg(J, MODE_FULL, false).coords();
+  const int modes[3] = {MODE_FULL, MODE_STATS, MODE_ADAMW};
+  for (int m : modes)
+    for (int g = 0; g < 2; ++g) {
+      const int64_t c = tile_cfg(J, m, g != 0).coords();
+      if (c < best) best = c;
+    }
+  return best;
 }
 
 bool hyper_ok(const nt_hyper* h, int64_t J) {
@@ -869,12 +884,10 @@ bool hyper_ok(const nt_hyper* h, int64_t J) {
   return true;
 }
 
-template <class GT, int MODE, bool TABLE>
-hipError_t launch_step(const StepParams& p, int64_t nfull, int64_t ntiles, int grid, hipStream_t st) {
-  constexpr int BS = (MODE == MODE_STATS) ? NT_BLOCK_STATS : (MODE == MODE_ADAMW) ? NT_BLOCK_ADAMW : NT_BLOCK;
-  constexpr int IS = (MODE == MODE_STATS) ? NT_ITERS_STATS : (MODE == MODE_ADAMW) ? NT_ITERS_ADAMW : NT_ITERS;
-#define NT_CASE(JJ)                                                                                      \
-  case JJ:                                                                                               \
+template <class GT, int MODE, bool TABLE, int BS, int IS>
+hipError_t launch_step_shape(const StepParams& p, int64_t nfull, int64_t ntiles, int grid, hipStream_t st) {
+#define NT_CASE(JJ)                                                                                             \
+  case JJ:                                                                                                      \
     hipLaunchKernelGGL((k_step<GT, JJ, MODE, BS, IS, TABLE>), dim3(grid), dim3(BS), 0, st, p, nfull, ntiles);  \
     break;
   switch (p.J) {
@@ -886,6 +899,20 @@ hipError_t launch_step(const StepParams& p, int64_t nfull, int64_t ntiles, int g
   }
 #undef NT_CASE
   return hipGetLastError();
+}
+
+// picks the launch class (block size, sweeps per tile) that tile_cfg() describes
+template <class GT, int MODE, bool TABLE>
+hipError_t launch_step(const StepParams& p, int64_t nfull, int64_t ntiles, int grid, hipStream_t st) {
+  if constexpr (MODE == MODE_STATS) {
+    if (p.gbar)
+      return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS_GBAR, NT_ITERS_STATS_GBAR>(p, nfull, ntiles, grid, st);
+    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS, NT_ITERS_STATS>(p, nfull, ntiles, grid, st);
+  } else if constexpr (MODE == MODE_ADAMW) {
+    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_ADAMW, NT_ITERS_ADAMW>(p, nfull, ntiles, grid, st);
+  } else {
+    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK, NT_ITERS>(p, nfull, ntiles, grid, st);
+  }
 }
 
 template <class GT, bool TABLE>
@@ -961,7 +988,7 @@ static int enqueue_step(const void* grads, bool table, nt_dtype gdtype, int64_t 
                         void* workspace, nt_result* result_dev, hipStream_t st) {
   const int esize = gdtype == NT_F32 ? 4 : 2;
   const int mode = (flags & NT_DO_STATS) ? ((flags & NT_DO_ADAMW) ? MODE_FULL : MODE_STATS) : MODE_ADAMW;
-  const int64_t tc = tile_cfg(J, mode).coords();
+  const int64_t tc = tile_cfg(J, mode, (flags & NT_WRITE_GBAR) != 0).coords();
   const int64_t ntiles = (d + tc - 1) / tc;
 
   StepParams p;
