@@ -308,7 +308,7 @@ __device__ inline void coord_stats_generic(const StepParams& p, int64_t i, doubl
   }
 }
 
-template <class GT, int MODE, int BLOCK, bool TABLE>
+template <class GT, int MODE, int BLOCK, bool TABLE, bool GBAR>
 __device__ inline void guarded_tile(const StepParams& p, int64_t tile, int tile_coords, double (*red)[BLOCK / 64][NT_NV],
                                     int buf) {
   constexpr int VEC = GT::VEC;
@@ -339,7 +339,7 @@ __device__ inline void guarded_tile(const StepParams& p, int64_t tile, int tile_
           p.m[i] = m;
           p.v[i] = v;
         }
-        if (p.gbar) p.gbar[i] = gb;
+        if (GBAR && p.gbar) p.gbar[i] = gb;
       }
     }
     if constexpr (MODE != MODE_ADAMW) {
@@ -391,13 +391,17 @@ __device__ inline void gbar_store(const StepParams& p, int64_t i0, const float* 
 // registers; needs 16-byte aligned rows and state and a tile that lies wholly below d.
 // The row sum is carried in fp64 so that the mean is correctly rounded even when the rows cancel.
 // ---------------------------------------------------------------------------------------------
-template <class GT, int J, int MODE, int BLOCK, int ITERS, bool TABLE>
+template <class GT, int J, int MODE, int BLOCK, int ITERS, bool TABLE, bool GBAR>
 __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red)[BLOCK / 64][NT_NV], int buf) {
   constexpr int VEC = GT::VEC;
   constexpr int TILE = BLOCK * VEC * ITERS;
   double accA = 0.0, accB = 0.0, accC = 0.0;
   int nfail = 0;
-  NT_PRAGMA_UNROLL(NT_UNROLL)
+  // a statistics-only sweep with few rows has little in flight per lane: overlap sweeps up to about 64 bytes
+  constexpr int ROW_BYTES = VEC * GT::ESIZE;
+  constexpr int WANT = 64 / (J * ROW_BYTES);
+  constexpr int U = (MODE == MODE_STATS && ITERS > 1) ? (WANT >= 4 ? 4 : (WANT >= 2 ? 2 : 1)) : NT_UNROLL;
+#pragma unroll U
   for (int it = 0; it < ITERS; ++it) {
     const int64_t i0 = tile * TILE + ((int64_t)it * BLOCK + threadIdx.x) * VEC;
     typename GT::raw_t raw[J];
@@ -447,7 +451,7 @@ __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red
       accC += (double)lane_tree<VEC>(c);
     }
     if constexpr (MODE != MODE_STATS) adamw_store<VEC>(p, i0, gb, sw, sm, sv);
-    if (p.gbar) gbar_store<VEC>(p, i0, gb);
+    if (GBAR && p.gbar) gbar_store<VEC>(p, i0, gb);
   }
   if constexpr (MODE != MODE_ADAMW) tile_reduce<BLOCK>(accA, accB, accC, (double)nfail, red, buf, p.partials, tile);
 #if NT_ADAMW_BARRIER
@@ -480,7 +484,7 @@ __device__ inline void chunk_accumulate(const typename GT::raw_t* raw, int nb, c
     }
 }
 
-template <class GT, int MODE, int BLOCK, int ITERS, bool TABLE>
+template <class GT, int MODE, int BLOCK, int ITERS, bool TABLE, bool GBAR>
 __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double (*red)[BLOCK / 64][NT_NV], int buf) {
   constexpr int VEC = GT::VEC;
   constexpr int TILE = BLOCK * VEC * ITERS;
@@ -548,7 +552,7 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
       }
       adamw_store<VEC>(p, i0, gb, sw, sm, sv);
     }
-    if (p.gbar) gbar_store<VEC>(p, i0, gb);
+    if (GBAR && p.gbar) gbar_store<VEC>(p, i0, gb);
   }
   if constexpr (MODE != MODE_ADAMW) tile_reduce<BLOCK>(accA, accB, accC, (double)nfail, red, buf, p.partials, tile);
 }
@@ -559,7 +563,8 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
 // takes it first so that the slow tile overlaps with everything else.
 // J_T = 0 selects the J > 16 row-walking variant.
 // ---------------------------------------------------------------------------------------------
-template <class GT, int J_T, int MODE, int BLOCK, int ITERS, bool TABLE>
+// GBAR = false compiles the gbar store out (statistics-only launch class, so that sweeps can overlap).
+template <class GT, int J_T, int MODE, int BLOCK, int ITERS, bool TABLE, bool GBAR>
 __global__ __launch_bounds__(BLOCK, NT_WAVES_PER_EU) void k_step(StepParams p, int64_t nfull, int64_t ntiles) {
   constexpr int TILE = BLOCK * GT::VEC * ITERS;
   static_assert(NT_TILE_MAX % TILE == 0, "tile sizes must divide NT_TILE_MAX");
@@ -577,11 +582,11 @@ __global__ __launch_bounds__(BLOCK, NT_WAVES_PER_EU) void k_step(StepParams p, i
     const int64_t tile = (t < nrest) ? nfull + t : t - nrest;
     if (tile < nfull) {
       if constexpr (J_T > 0)
-        fast_tile<GT, J_T, MODE, BLOCK, ITERS, TABLE>(p, tile, red, buf);
+        fast_tile<GT, J_T, MODE, BLOCK, ITERS, TABLE, GBAR>(p, tile, red, buf);
       else
-        fast_tile_multi<GT, MODE, BLOCK, ITERS, TABLE>(p, tile, red, buf);
+        fast_tile_multi<GT, MODE, BLOCK, ITERS, TABLE, GBAR>(p, tile, red, buf);
     } else {
-      guarded_tile<GT, MODE, BLOCK, TABLE>(p, tile, TILE, red, buf);
+      guarded_tile<GT, MODE, BLOCK, TABLE, GBAR>(p, tile, TILE, red, buf);
     }
     buf ^= 1;
   }
@@ -884,17 +889,18 @@ bool hyper_ok(const nt_hyper* h, int64_t J) {
   return true;
 }
 
-template <class GT, int MODE, bool TABLE, int BS, int IS>
+template <class GT, int MODE, bool TABLE, int BS, int IS, bool GBAR>
 hipError_t launch_step_shape(const StepParams& p, int64_t nfull, int64_t ntiles, int grid, hipStream_t st) {
 #define NT_CASE(JJ)                                                                                             \
   case JJ:                                                                                                      \
-    hipLaunchKernelGGL((k_step<GT, JJ, MODE, BS, IS, TABLE>), dim3(grid), dim3(BS), 0, st, p, nfull, ntiles);  \
+    hipLaunchKernelGGL((k_step<GT, JJ, MODE, BS, IS, TABLE, GBAR>), dim3(grid), dim3(BS), 0, st, p, nfull,      \
+                       ntiles);                                                                                 \
     break;
   switch (p.J) {
     NT_CASE(2) NT_CASE(3) NT_CASE(4) NT_CASE(5) NT_CASE(6) NT_CASE(7) NT_CASE(8) NT_CASE(9)
     NT_CASE(10) NT_CASE(11) NT_CASE(12) NT_CASE(13) NT_CASE(14) NT_CASE(15) NT_CASE(16)
     default:
-      hipLaunchKernelGGL((k_step<GT, 0, MODE, NT_BLOCK_LARGE, NT_ITERS_LARGE, TABLE>), dim3(grid),
+      hipLaunchKernelGGL((k_step<GT, 0, MODE, NT_BLOCK_LARGE, NT_ITERS_LARGE, TABLE, true>), dim3(grid),
                          dim3(NT_BLOCK_LARGE), 0, st, p, nfull, ntiles);
   }
 #undef NT_CASE
@@ -906,12 +912,13 @@ template <class GT, int MODE, bool TABLE>
 hipError_t launch_step(const StepParams& p, int64_t nfull, int64_t ntiles, int grid, hipStream_t st) {
   if constexpr (MODE == MODE_STATS) {
     if (p.gbar)
-      return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS_GBAR, NT_ITERS_STATS_GBAR>(p, nfull, ntiles, grid, st);
-    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS, NT_ITERS_STATS>(p, nfull, ntiles, grid, st);
+      return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS_GBAR, NT_ITERS_STATS_GBAR, true>(p, nfull, ntiles, grid,
+                                                                                                 st);
+    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS, NT_ITERS_STATS, false>(p, nfull, ntiles, grid, st);
   } else if constexpr (MODE == MODE_ADAMW) {
-    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_ADAMW, NT_ITERS_ADAMW>(p, nfull, ntiles, grid, st);
+    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_ADAMW, NT_ITERS_ADAMW, true>(p, nfull, ntiles, grid, st);
   } else {
-    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK, NT_ITERS>(p, nfull, ntiles, grid, st);
+    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK, NT_ITERS, true>(p, nfull, ntiles, grid, st);
   }
 }
 
