@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # copy-kernel calibration; None until measured for that workload.
 MEASURED_TRAFFIC_BYTES = {
     # profiles/k_step_flat_1p5b.md: FETCH_SIZE x 2.0000 + WRITE_SIZE x 1.0000 per k_step launch
-    "flat_1p5b": 6.0016e10,
+    "flat_1p5b": 6.0010e10,
 }
 
 
