@@ -182,6 +182,17 @@ int normtest_adamw_gbar(const float* gbar, int64_t d, float* w, float* m, float*
 /* Host helper: min(1, max_norm / (sqrt(gbar_sq) + 1e-6)); 1 if max_norm <= 0. */
 double normtest_clip_coef(double gbar_sq, double max_norm);
 
+/*
+ * Host helper: split a global batch size b (for instance nt_result.next_b) over J workers, accumulation
+ * steps and a bounded micro-batch (the hyper-parameter tables list a base and a maximum micro-batch size
+ * and a base number of accumulation steps; Alg. 1 itself keeps the number of steps fixed).  Keeps
+ * accum_base steps while the micro-batch fits under micro_max, otherwise uses the fewest steps for which
+ * it fits:  accum = max(accum_base, ceil(b / (J micro_max))),  micro = ceil(b / (J accum)),
+ * global_batch = J accum micro >= b.  Returns NT_OK or NT_ERR_BAD_ARG.
+ */
+int normtest_resplit(int64_t b, int64_t J, int64_t accum_base, int64_t micro_max,
+                     int64_t* micro, int64_t* accum, int64_t* global_batch);
+
 /* Plain streaming copy of `bytes` bytes (device to device, 16-byte aligned, bytes % 16 == 0) with the
  * same load/store instructions as the step kernel: a yardstick for achievable HBM bandwidth and for
  * scaling hardware byte counters.  Enqueued on the stream. */

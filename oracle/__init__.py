@@ -71,6 +71,8 @@ def _bind(path: str):
     lib.nto_adamw.restype = ctypes.c_int
     lib.nto_coord_test.argtypes = [vp, ctypes.c_int, i64, i64, i64, dbl, i64, ctypes.c_int32, dbl, vp]
     lib.nto_coord_test.restype = ctypes.c_int
+    lib.nto_resplit.argtypes = [i64, i64, i64, i64, vp, vp, vp]
+    lib.nto_resplit.restype = ctypes.c_int
     lib.nto_clip_coef.argtypes = [dbl, dbl]
     lib.nto_clip_coef.restype = dbl
     return lib
@@ -165,6 +167,15 @@ def coord_test(G: np.ndarray, eta: float, b_k: int, ddof: int = 1, band: float =
     else:
         if J - ddof < 1 or not eta > 0 or b_k < 1:
             raise ValueError("nto_coord_test rejected its arguments")
+    return int(out[0]), int(out[1]), int(out[2])
+
+
+def resplit(b: int, J: int, M_base: int, micro_max: int):
+    """(micro_batch, accumulation_steps, global_batch) for a target global batch size b."""
+    out = (ctypes.c_int64 * 3)()
+    rc = _load().nto_resplit(b, J, M_base, micro_max, ctypes.byref(out, 0), ctypes.byref(out, 8), ctypes.byref(out, 16))
+    if rc:
+        raise ValueError("nto_resplit rejected its arguments")
     return int(out[0]), int(out[1]), int(out[2])
 
 

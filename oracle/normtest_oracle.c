@@ -168,6 +168,29 @@ int nto_decide(double A, double B, double C, int64_t J, double eta, int64_t b_k,
 }
 
 /*
+ * Splitting a global batch size over J workers, M accumulation steps and a micro-batch size that has a
+ * maximum (hyper-parameter tables: base micro-batch 4, maximum micro-batch 8, base accumulation steps 16,
+ * data-parallel size 4, base global batch 256, maximum 8192).  Alg. 1 keeps M fixed and lets the
+ * micro-batch grow; the paper does not say what happens at the maximum micro-batch size.  Reading taken:
+ * keep the base M while the micro-batch fits, otherwise take the fewest accumulation steps for which it
+ * fits, then the smallest micro-batch that covers b:
+ *   M = max(M_base, ceil(b / (J * micro_max))),  micro = ceil(b / (J * M)),  global = J * M * micro >= b.
+ */
+int nto_resplit(int64_t b, int64_t J, int64_t M_base, int64_t micro_max, int64_t *micro, int64_t *M,
+                int64_t *global) {
+  int64_t per_worker, m, mb;
+  if (b < 1 || J < 1 || M_base < 1 || micro_max < 1 || !micro || !M || !global) return -1;
+  per_worker = b / J + (b % J != 0);
+  m = per_worker / micro_max + (per_worker % micro_max != 0);
+  if (m < M_base) m = M_base;
+  mb = b / (J * m) + (b % (J * m) != 0);
+  *micro = mb;
+  *M = m;
+  *global = J * m * mb;
+  return 0;
+}
+
+/*
  * Coordinate-wise form of the test.  The analysis (Sec. 4, Prop. 1; App. B remark) asks the norm-test
  * condition of every coordinate i separately; with the same estimators as the aggregate test this reads
  *   Var_i / b_k <= eta^2 gbar_i^2,   Var_i = sum_j (g_j[i] - gbar_i)^2 / (J - ddof),

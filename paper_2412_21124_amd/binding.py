@@ -96,6 +96,8 @@ def lib(path: Optional[str] = None):
         L.normtest_adamw_gbar.restype = ctypes.c_int
         L.normtest_clip_coef.argtypes = [ctypes.c_double, ctypes.c_double]
         L.normtest_clip_coef.restype = ctypes.c_double
+        L.normtest_resplit.argtypes = [i64, i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64)]
+        L.normtest_resplit.restype = ctypes.c_int
         L.normtest_calib_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.normtest_calib_copy.restype = ctypes.c_int
         L.normtest_strerror.argtypes = [ctypes.c_int]
@@ -283,6 +285,15 @@ def normtest_adamw_gbar(gbar: torch.Tensor, w: torch.Tensor, m: torch.Tensor, v:
 
 def normtest_clip_coef(gbar_sq: float, max_norm: float) -> float:
     return float(lib().normtest_clip_coef(gbar_sq, max_norm))
+
+
+def normtest_resplit(b: int, J: int, accum_base: int, micro_max: int):
+    """(micro_batch, accumulation_steps, global_batch) for a target global batch size b."""
+    micro, accum, glob = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    rc = lib().normtest_resplit(b, J, accum_base, micro_max, ctypes.byref(micro), ctypes.byref(accum), ctypes.byref(glob))
+    if rc != NT_OK:
+        raise NormtestError(rc, "normtest_resplit")
+    return micro.value, accum.value, glob.value
 
 
 def read_result(result: torch.Tensor) -> nt_result:

@@ -1133,6 +1133,20 @@ int normtest_adamw_gbar(const float* gbar, int64_t d, float* w, float* m, float*
 
 double normtest_clip_coef(double gbar_sq, double max_norm) { return clip_coef(gbar_sq, max_norm); }
 
+int normtest_resplit(int64_t b, int64_t J, int64_t accum_base, int64_t micro_max, int64_t* micro, int64_t* accum,
+                     int64_t* global_batch) {
+  if (b < 1 || J < 1 || accum_base < 1 || micro_max < 1 || !micro || !accum || !global_batch) return NT_ERR_BAD_ARG;
+  // samples each worker must see, accumulation steps needed at the largest micro-batch, never below the base
+  const int64_t per_worker = (b + J - 1) / J;
+  int64_t steps = (per_worker + micro_max - 1) / micro_max;
+  if (steps < accum_base) steps = accum_base;
+  const int64_t chunk = J * steps;
+  *micro = (b + chunk - 1) / chunk;
+  *accum = steps;
+  *global_batch = chunk * *micro;
+  return NT_OK;
+}
+
 int normtest_combine(const nt_result* partials, int32_t n, int64_t J, const nt_hyper* hyper, nt_result* out) {
   if (!partials || !out || n < 1 || J < 2 || !hyper) return NT_ERR_BAD_ARG;
   if (!(hyper->eta > 0.0) || !std::isfinite(hyper->eta) || hyper->b_k < 1 || hyper->b_max < 0 ||

@@ -25,7 +25,7 @@ def test_every_declared_symbol_is_exported():
     names = declared_functions()
     assert {"normtest_step", "normtest_combine", "normtest_workspace_bytes", "normtest_tile_coords",
             "normtest_strerror", "normtest_calib_copy", "normtest_step_clipped", "normtest_adamw_gbar",
-            "normtest_clip_coef", "normtest_step_rows"} <= set(names)
+            "normtest_clip_coef", "normtest_step_rows", "normtest_resplit"} <= set(names)
     L = B.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -141,6 +141,18 @@ def test_rows_entry_point_validates_before_launch():
     assert call(w=None) == bad
     assert call(gdtype=9) == B.NT_ERR_UNSUPPORTED
     assert call(ws_bytes=0) == B.NT_ERR_WORKSPACE_TOO_SMALL
+
+
+def test_resplit_matches_oracle():
+    rng = np.random.default_rng(4)
+    cases = [(256, 4, 16, 8), (8192, 4, 16, 8), (576, 4, 16, 8), (1, 1, 1, 1), (10**12, 8, 16, 8)]
+    cases += [(int(rng.integers(1, 10**6)), int(rng.integers(1, 65)), int(rng.integers(1, 65)), int(rng.integers(1, 33)))
+              for _ in range(3000)]
+    for c in cases:
+        assert B.normtest_resplit(*c) == oracle.resplit(*c), c
+    for bad in ((0, 4, 16, 8), (256, 0, 16, 8), (256, 4, 0, 8), (256, 4, 16, 0)):
+        with pytest.raises(B.NormtestError):
+            B.normtest_resplit(*bad)
 
 
 def test_clip_coef_matches_oracle():

@@ -45,6 +45,9 @@ MUTANTS = [
     ("coord_ddof_ignored", "var = c / (double)(J - ddof);", "var = c / (double)J;"),
     ("coord_equality_fails", "if (var > rhs * (1.0 + band))", "if (var >= rhs * (1.0 + band))"),
     ("coord_inequality_flipped", "if (var > rhs * (1.0 + band))", "if (var < rhs * (1.0 + band))"),
+    ("resplit_ignores_cap", "if (m < M_base) m = M_base;", "m = M_base;"),
+    ("resplit_floor_micro", "mb = b / (J * m) + (b % (J * m) != 0);", "mb = b / (J * m);"),
+    ("resplit_steps_from_total", "m = per_worker / micro_max + (per_worker % micro_max != 0);", "m = b / micro_max + (b % micro_max != 0);"),
     ("clip_never", "return c < 1.0 ? c : 1.0;", "return 1.0;"),
     ("clip_always", "return c < 1.0 ? c : 1.0;", "return c;"),
     ("clip_uses_squared_norm", "c = max_norm / (sqrt(gbar_sq) + 1e-6);", "c = max_norm / (gbar_sq + 1e-6);"),
@@ -90,6 +93,7 @@ def battery():
         P.test_long_sum_needs_compensation,
         P.test_clipped_step_matches_library_clipping,
         lambda: P.test_coordinatewise_brute_force_and_invariants(3),
+        P.test_resplit_reproduces_the_papers_table_values_and_invariants,
     ]
     return checks
 

@@ -477,6 +477,27 @@ def test_degenerate_inputs():
     assert dec.next_b == 4096
 
 
+def test_resplit_reproduces_the_papers_table_values_and_invariants():
+    """Hyper-parameter tables: data-parallel size 4, base micro-batch 4, maximum 8, base accumulation steps 16:
+    base global batch 256 = 4 * 16 * 4, and the maximum 8192 = 4 * 256 * 8 needs 256 steps at micro-batch 8."""
+    assert oracle.resplit(256, 4, 16, 8) == (4, 16, 256)
+    assert oracle.resplit(512, 4, 16, 8) == (8, 16, 512)             # micro-batch grows first (Alg. 1, M fixed)
+    assert oracle.resplit(576, 4, 16, 8) == (8, 18, 576)             # 576 / 4 = 144 per worker = 18 steps of 8
+    assert oracle.resplit(8192, 4, 16, 8) == (8, 256, 8192)
+    assert oracle.resplit(320, 4, 16, 8) == (5, 16, 320)
+    assert oracle.resplit(1, 4, 16, 8) == (1, 16, 64)                # never below one sample per micro-batch
+    rng = np.random.default_rng(3)
+    for _ in range(2000):
+        b = int(rng.integers(1, 20000)); J = int(rng.integers(1, 9)); Mb = int(rng.integers(1, 33)); mx = int(rng.integers(1, 17))
+        micro, M, glob = oracle.resplit(b, J, Mb, mx)
+        assert glob == J * M * micro >= b and 1 <= micro <= mx and M >= Mb
+        assert glob - b < J * M                                       # smallest multiple of J*M that covers b
+        if M > Mb:
+            assert J * (M - 1) * mx < b                               # one step fewer would not fit
+    with pytest.raises(ValueError):
+        oracle.resplit(0, 4, 16, 8)
+
+
 def test_argument_checks():
     with pytest.raises(ValueError):
         oracle.decide(1, 1, 1, 1, 0.1, 32, 0, 1, 1)      # J - ddof = 0
