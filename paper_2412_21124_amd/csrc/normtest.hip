@@ -1,10 +1,13 @@
 // libnormtest: norm-test statistics pass fused with AdamW, hand-written for gfx950 (MI355X).
 //
-// One streaming kernel reads the J gradient rows and w, m, v once, writes w, m, v once and leaves
-// three fp64 partial sums per fixed-size tile of coordinates; a one-block kernel then adds the tile
-// partials in double-double arithmetic and takes Alg. 1's decision.  The path is bound by HBM
-// bandwidth (about one flop per byte), so there is no MFMA here: the work is 128-bit coalesced
-// loads, fp32 per-coordinate arithmetic, fp64 accumulation and wave64 shuffle reductions.
+// One streaming kernel (k_step) reads the J gradient rows and w, m, v once, writes w, m, v once and
+// leaves four fp64 partial sums per fixed-size tile of coordinates (A, B, C and the count of
+// coordinates failing the coordinate-wise form of the test); k_reduce_groups / k_finalize then add the
+// tile partials in double-double arithmetic and take Alg. 1's decision on the device.  The path is
+// bound by HBM bandwidth (about two lane-operations per byte), so there is no MFMA here: the work is
+// fully coalesced 8- and 16-byte accesses, fp32 per-coordinate arithmetic, fp64 accumulation and wave64
+// shuffle reductions.  Launch shapes (block size, sweeps per tile) differ per class of call and were
+// chosen by measurement; see tile_cfg().
 //
 // Numerics.  The centred sum C = sum_j (g_j - gbar)^2 is formed directly from the J values of a
 // coordinate held in registers, never as A - B/J (which cancels badly when the workers agree).  A
@@ -13,8 +16,8 @@
 // running mean so far, and the chunks' means and centred sums are merged with the pairwise update
 // M2 += M2_b + delta^2 n_a n_b / (n_a + n_b).  Row sums are carried in fp64, so the mean handed to
 // AdamW is correctly rounded even when the rows cancel.
-// Per-lane sums leave fp32 after one group of 4 or 8 coordinates; everything above is fp64 in a
-// fixed order, so results do not depend on the grid size and are reproducible bit for bit.
+// Per-lane sums leave fp32 after one group of 4 coordinates; everything above is fp64 in a fixed
+// order, so results do not depend on the grid size and are reproducible bit for bit.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -147,7 +150,7 @@ struct StepParams {
   float* m;
   float* v;
   float* gbar;      // nullptr unless requested
-  double* partials; // 3 doubles per tile
+  double* partials; // NT_NV doubles per tile
   double inv_J;
   float beta1, omb1, beta2, omb2; // omb = 1 - beta
   float decay;                    // 1 - lr * weight_decay
@@ -186,12 +189,11 @@ __device__ inline void adamw_coord(const StepParams& p, float g, float& w, float
   w = __builtin_fmaf(p.decay, w, -upd);
 }
 
+// fixed-order sum of a lane's VEC per-coordinate terms
 template <int VEC>
 __device__ inline float lane_tree(const float* x) {
-  if constexpr (VEC == 8)
-    return ((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7]));
-  else
-    return (x[0] + x[1]) + (x[2] + x[3]);
+  static_assert(VEC == 4, "lanes own four coordinates per sweep");
+  return (x[0] + x[1]) + (x[2] + x[3]);
 }
 
 __device__ inline double wave_sum(double x) {
@@ -200,7 +202,7 @@ __device__ inline double wave_sum(double x) {
   return x;
 }
 
-// Block partial of one tile -> partials[3*tile ..].  `buf` alternates between tiles so that one
+// Block partial of one tile -> partials[NT_NV*tile ..].  `buf` alternates between tiles so that one
 // barrier per tile is enough.
 template <int BLOCK>
 __device__ inline void tile_reduce(double a, double b, double c, double n, double (*red)[BLOCK / 64][NT_NV], int buf,
@@ -237,12 +239,6 @@ __device__ inline void tile_reduce(double a, double b, double c, double n, doubl
 // eta^2 b_k (J - ddof) gbar^2.  thr < 0 switches the count off.
 __device__ inline int coord_fails(float thr, float c, float gb) { return (thr >= 0.f && c > thr * (gb * gb)) ? 1 : 0; }
 
-// ---------------------------------------------------------------------------------------------
-// Guarded tile: any J, any alignment, ragged end.  Same lane-to-coordinate map and the same
-// sequence of floating-point operations per coordinate as the fast tiles below (rows are re-read
-// instead of held in registers), so a tile's partial sums and outputs have the same bits on either
-// path.  Coordinates at or beyond d contribute exact zeros.
-// ---------------------------------------------------------------------------------------------
 // Per-chunk bookkeeping of the J > 16 walk, shared by the fast and the guarded path so that both
 // perform the same operations.  For one coordinate and a chunk of nb rows shifted by K (the running
 // mean before the chunk, or the first row for the first chunk), sr = sum (x - K) in fp64 and
@@ -272,6 +268,12 @@ __device__ inline float chunk_merge(bool first, int na, int nb, float K, double 
   return (float)(S * (1.0 / (double)(na + nb)));
 }
 
+// ---------------------------------------------------------------------------------------------
+// Guarded tile: any J, any alignment, ragged end.  Same lane-to-coordinate map and the same
+// sequence of floating-point operations per coordinate as the fast tiles below (rows are re-read
+// instead of held in registers), so a tile's partial sums and outputs have the same bits on either
+// path.  Coordinates at or beyond d contribute exact zeros.
+// ---------------------------------------------------------------------------------------------
 template <class GT, bool TABLE>
 __device__ inline void coord_stats_generic(const StepParams& p, int64_t i, double& S, float& M2, float& a) {
   const int J = p.J;
