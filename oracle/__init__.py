@@ -200,3 +200,22 @@ def adamw(G, w, m, v, lr, beta1, beta2, eps, weight_decay, step, want_gbar=False
         if rc:
             raise ValueError("nto_adamw rejected its arguments")
     return (wo, mo, vo, go) if want_gbar else (wo, mo, vo)
+
+
+def layer_stats(G: np.ndarray, offsets, eta: float, b_k: int, ddof: int = 1, band=None):
+    """The estimators of Sec. 3.2 / Alg. 1 restricted to blocks of coordinates: layer l owns columns
+    offsets[l] .. offsets[l+1]-1.  Returns one dict per layer with A, B, C, the Decision of the layer's own
+    statistic against b_k (no rounding, no cap), n, and, if `band` is given, the coordinate-wise counts."""
+    offsets = [int(o) for o in offsets]
+    n = G.shape[1]
+    if len(offsets) < 2 or offsets[0] < 0 or offsets[-1] > n or any(a > b for a, b in zip(offsets, offsets[1:])):
+        raise ValueError("offsets must ascend within [0, n]")
+    J = G.shape[0]
+    out = []
+    for lo, hi in zip(offsets, offsets[1:]):
+        A, B, C = stats(G[:, lo:hi])
+        row = dict(A=A, B=B, C=C, n=hi - lo, dec=decide(A, B, C, J, eta, b_k, 0, 1, ddof))
+        if band is not None:
+            row["coord"] = coord_test(G[:, lo:hi], eta, b_k, ddof, band)
+        out.append(row)
+    return out

@@ -37,7 +37,7 @@ def parse_golden(path):
         elif key == "g":
             cur["g"].append([float(x) for x in vals])
         else:
-            cur[key] = vals[0]
+            cur[key] = vals[0] if len(vals) == 1 else vals
     return cases
 
 
@@ -114,6 +114,50 @@ def test_golden_coordinatewise(case, as_bf16):
         assert (fail, near) == (int(val), 0) and fail + ok == G.shape[1], key
         n_checked += 1
     assert n_checked >= 2
+
+
+@pytest.mark.parametrize("as_bf16", [False, True])
+def test_golden_layers(as_bf16):
+    """Blocks of coordinates: hand-worked sums per block, an empty block, and the whole vector."""
+    case = next(c for c in GOLDEN_CASES if c["name"] == "layers_two_by_five")
+    G = np.array(case["g"], dtype=np.float32)
+    Gin = bf16_bits(G) if as_bf16 else G
+    offsets = [int(x) for x in case["layer_offsets"]]
+    rows = oracle.layer_stats(Gin, offsets, float(case["eta"]), 1, int(case["ddof"]))
+    assert len(rows) == len(offsets) - 1
+    for l, row in enumerate(rows):
+        A, B, C, T = (float(x) for x in case["expect_layer%d" % l])
+        assert (row["A"], row["B"], row["C"]) == (A, B, C)
+        assert row["n"] == offsets[l + 1] - offsets[l]
+        if math.isnan(T):
+            assert math.isnan(row["dec"].T) and row["dec"].passed
+        else:
+            assert row["dec"].T == pytest.approx(T, rel=1e-15)
+            assert row["dec"].passed == (not T > 1)
+    whole = [float(x) for x in case["expect_whole"]]
+    assert list(oracle.stats(Gin)) == whole
+    assert [sum(r[k] for r in rows) for k in "ABC"] == whole
+
+
+def test_layers_partition_the_sums_and_reject_bad_offsets():
+    rng = np.random.default_rng(5)
+    G = rng.standard_normal((5, 4001)).astype(np.float32)
+    cuts = sorted(rng.integers(0, 4002, size=9).tolist())
+    offsets = [0] + cuts + [4001]
+    rows = oracle.layer_stats(G, offsets, 0.1, 32, 1, band=0.0)
+    whole = oracle.stats(G)
+    for k, name in enumerate("ABC"):
+        assert math.fsum(r[name] for r in rows) == pytest.approx(whole[k], rel=1e-14)
+    assert sum(r["n"] for r in rows) == 4001
+    fail, near, ok = oracle.coord_test(G, 0.1, 32, 1, 0.0)
+    assert sum(r["coord"][0] for r in rows) == fail and sum(r["coord"][2] for r in rows) == ok
+    # a block is its slice: independent evaluation of one block from a copy of its columns
+    lo, hi = offsets[3], offsets[4]
+    A, B, C = exact_stats(G[:, lo:hi].astype(np.float64).tolist()) if hi - lo <= 64 else oracle.stats(np.ascontiguousarray(G[:, lo:hi]))
+    assert rows[3]["A"] == pytest.approx(float(A), rel=1e-14)
+    for bad in ([0], [0, 5000], [-1, 10], [0, 10, 5]):
+        with pytest.raises(ValueError):
+            oracle.layer_stats(G, bad, 0.1, 32)
 
 
 @pytest.mark.parametrize("J", [2, 3, 4, 8])
