@@ -47,7 +47,8 @@ enum {
   NT_STATUS_CLAMPED = 4u,        /* the rounded batch size exceeded b_max and was cut to it                      */
   NT_STATUS_PARTIAL_ONLY = 8u,   /* NT_PARTIAL: only A, B, C (and their low parts) are meaningful                */
   NT_STATUS_T_SATURATED = 16u,   /* T >= 2^62: treated as infinite                                               */
-  NT_STATUS_NO_STATS = 32u       /* NT_DO_STATS was clear: sums are NaN, pass = 1, next_b = b_k                  */
+  NT_STATUS_NO_STATS = 32u,      /* NT_DO_STATS was clear: sums are NaN, pass = 1, next_b = b_k                  */
+  NT_STATUS_BAD_RANGE = 64u      /* nt_layer_stats only: the layer's offsets were descending or outside [0, d]   */
 };
 
 /* return codes; values <= NT_ERR_HIP_BASE carry a HIP error: code = NT_ERR_HIP_BASE - hipError_t */
@@ -97,6 +98,18 @@ typedef struct {
   uint32_t status;         /* NT_STATUS_* bits                                                                    */
 } nt_result;
 
+/* One layer (a block of consecutive coordinates) of normtest_layer_stats. */
+typedef struct {
+  double A, B, C;        /* the three sums over the layer's coordinates                                          */
+  double gbar_sq;        /* B/J^2: squared norm of the layer's slice of gbar                                     */
+  double var_l1;         /* C/(J - ddof)                                                                         */
+  double T;              /* var_l1 / (eta^2 gbar_sq): Alg. 1's statistic evaluated on the layer alone            */
+  int64_t n;             /* coordinates counted (after clamping the offsets into [0, d])                         */
+  int64_t coord_fail;    /* failing coordinates in the layer if the step ran with NT_COORD_TEST, else -1         */
+  int32_t pass;          /* 1 iff not (T > b_k)                                                                  */
+  uint32_t status;       /* NT_STATUS_NONFINITE | ZERO_GRAD_NORM | T_SATURATED | NO_STATS | BAD_RANGE            */
+} nt_layer_stats;
+
 /* Alignment, in coordinates, of the partial-sum tiles for J rows (every tile size divides it).  Results are
  * bit-identical for any split of a vector into calls whose boundaries are multiples of this, for the
  * same J, dtype and flags. */
@@ -110,7 +123,8 @@ size_t normtest_workspace_bytes(int64_t J, int64_t d);
  * type gdtype).  w, m, v: device fp32[d], updated in place when NT_DO_ADAMW (may be NULL otherwise).
  * gbar_out: device fp32[d], written when NT_WRITE_GBAR, else ignored.  hyper, shard: host pointers,
  * read before returning (shard may be NULL).  workspace: device scratch of at least
- * normtest_workspace_bytes(J, d) bytes, 8-byte aligned, contents irrelevant before and after.
+ * normtest_workspace_bytes(J, d) bytes, 8-byte aligned; contents irrelevant before; afterwards it holds the
+ * call's per-tile partial sums in a private format, which only normtest_layer_stats reads.
  * result_dev: device or pinned-host nt_result, 8-byte aligned, written by the last kernel.
  * hip_stream: a hipStream_t (NULL = the default stream).
  *
@@ -178,6 +192,28 @@ int normtest_step_clipped(const void* grads, nt_dtype gdtype, int64_t J, int64_t
 int normtest_adamw_gbar(const float* gbar, int64_t d, float* w, float* m, float* v,
                         const nt_hyper* hyper, double grad_scale, const nt_result* result_dev,
                         void* hip_stream);
+
+/*
+ * Per-layer table of the statistics: A, B, C of Sec. 3.2 / Alg. 1 and the resulting T, each restricted to a
+ * block of consecutive coordinates (a parameter tensor).  The paper tests the whole vector only; nothing here
+ * feeds the batch-size decision.  Call it after normtest_step, normtest_step_rows or normtest_step_clipped,
+ * on the same stream, with the same gradients (unchanged since), gdtype, J, d, ld and workspace: the tile
+ * partial sums which that step left in the workspace are regrouped, and only the pieces of a layer that cover
+ * part of a tile are recomputed from the rows (at most two tiles' worth per layer).  eta, b_k, ddof and the
+ * coordinate-wise threshold are those of that step.
+ *   grads            as in normtest_step, or (rows_are_table != 0) the pointer table of normtest_step_rows
+ *   layer_offsets_dev  device int64[L+1], ascending, layer l = coordinates [offsets[l], offsets[l+1]);
+ *                    layers need not cover the vector and may be empty.  Read by the kernel only: offsets
+ *                    outside [0, d] or descending are clamped and the layer is flagged NT_STATUS_BAD_RANGE.
+ *   layers_dev       device or pinned-host nt_layer_stats[L], 8-byte aligned
+ * If the workspace does not hold the partial sums of a statistics step with the same gdtype, J and d, every
+ * layer comes back with NaN sums and NT_STATUS_NO_STATS.  After an NT_PARTIAL step the sums cover this
+ * shard's part of each layer (they add over shards); T is then that part's own.
+ * Returns NT_OK or a negative code; on error nothing was enqueued.
+ */
+int normtest_layer_stats(const void* grads, int rows_are_table, nt_dtype gdtype, int64_t J, int64_t d,
+                         int64_t ld, const int64_t* layer_offsets_dev, int32_t L, const void* workspace,
+                         nt_layer_stats* layers_dev, void* hip_stream);
 
 /* Host helper: min(1, max_norm / (sqrt(gbar_sq) + 1e-6)); 1 if max_norm <= 0. */
 double normtest_clip_coef(double gbar_sq, double max_norm);

@@ -22,6 +22,7 @@ NT_STATUS_CLAMPED = 4
 NT_STATUS_PARTIAL_ONLY = 8
 NT_STATUS_T_SATURATED = 16
 NT_STATUS_NO_STATS = 32
+NT_STATUS_BAD_RANGE = 64
 NT_OK, NT_ERR_BAD_ARG, NT_ERR_UNSUPPORTED, NT_ERR_WORKSPACE_TOO_SMALL, NT_ERR_HIP_BASE = 0, -1, -2, -3, -1000
 
 
@@ -58,6 +59,22 @@ class nt_result(ctypes.Structure):
 RESULT_BYTES = ctypes.sizeof(nt_result)
 
 
+class nt_layer_stats(ctypes.Structure):
+    _fields_ = [
+        ("A", ctypes.c_double), ("B", ctypes.c_double), ("C", ctypes.c_double),
+        ("gbar_sq", ctypes.c_double), ("var_l1", ctypes.c_double), ("T", ctypes.c_double),
+        ("n", ctypes.c_int64), ("coord_fail", ctypes.c_int64), ("pass_", ctypes.c_int32), ("status", ctypes.c_uint32),
+    ]
+
+    def as_dict(self) -> dict:
+        d = {k: getattr(self, k) for k, _ in self._fields_}
+        d["pass"] = d.pop("pass_")
+        return d
+
+
+LAYER_BYTES = ctypes.sizeof(nt_layer_stats)
+
+
 class NormtestError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
@@ -92,6 +109,8 @@ def lib(path: Optional[str] = None):
                                             ctypes.POINTER(nt_hyper), ctypes.POINTER(nt_shard_info),
                                             vp, ctypes.c_size_t, vp, vp]
         L.normtest_step_clipped.restype = ctypes.c_int
+        L.normtest_layer_stats.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, i64, i64, vp, ctypes.c_int32, vp, vp, vp]
+        L.normtest_layer_stats.restype = ctypes.c_int
         L.normtest_adamw_gbar.argtypes = [vp, i64, vp, vp, vp, ctypes.POINTER(nt_hyper), ctypes.c_double, vp, vp]
         L.normtest_adamw_gbar.restype = ctypes.c_int
         L.normtest_clip_coef.argtypes = [ctypes.c_double, ctypes.c_double]
@@ -281,6 +300,61 @@ def normtest_adamw_gbar(gbar: torch.Tensor, w: torch.Tensor, m: torch.Tensor, v:
                                        float(grad_scale), _ptr(result), ctypes.c_void_p(stream.cuda_stream))
     if rc != NT_OK:
         raise NormtestError(rc, "normtest_adamw_gbar")
+
+
+def normtest_layer_stats(grads, layer_offsets: torch.Tensor, workspace: torch.Tensor, *, d: Optional[int] = None,
+                         table: Optional[torch.Tensor] = None, layers: Optional[torch.Tensor] = None,
+                         stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Enqueue the per-layer table after a step that used `workspace` on the same stream.  grads: the (J, ld)
+    tensor of that step, or the sequence of rows given to normtest_step_rows (then `table` may carry the
+    address table already made).  layer_offsets: int64 device tensor of L+1 ascending offsets.  Returns the
+    device tensor (uint8[L * sizeof(nt_layer_stats)]); read it with `read_layers` after a sync."""
+    rows = None if isinstance(grads, torch.Tensor) else list(grads)
+    first = grads if rows is None else rows[0]
+    dev = first.device
+    if dev.type != "cuda":
+        raise ValueError("normtest_layer_stats needs device tensors; there is no CPU path")
+    if rows is None:
+        if grads.dim() != 2 or (grads.shape[1] > 1 and grads.stride(1) != 1):
+            raise ValueError("grads must be (J, ld) with a contiguous last axis")
+        J = grads.shape[0]
+        ld = grads.stride(0) if J > 1 else grads.shape[1]
+        d = grads.shape[1] if d is None else d
+        gptr = _ptr(grads)
+    else:
+        J = len(rows)
+        d = min(r.numel() for r in rows) if d is None else d
+        ld = d
+        if table is None:
+            table = make_row_table(rows)
+        gptr = _ptr(table)
+    if (layer_offsets.dtype != torch.int64 or layer_offsets.device != dev or layer_offsets.dim() != 1
+            or not layer_offsets.is_contiguous() or layer_offsets.numel() < 2):
+        raise ValueError("layer_offsets must be a contiguous int64 device vector of L+1 >= 2 entries")
+    L = layer_offsets.numel() - 1
+    if workspace.device != dev or workspace.numel() * workspace.element_size() < normtest_workspace_bytes(J, d):
+        raise ValueError("workspace must be the device workspace of the preceding step")
+    if layers is None:
+        layers = torch.empty(L * LAYER_BYTES, dtype=torch.uint8, device=dev)
+    elif layers.numel() * layers.element_size() < L * LAYER_BYTES:
+        raise ValueError("layers must hold L * sizeof(nt_layer_stats) bytes")
+    if stream is None:
+        stream = torch.cuda.current_stream(dev)
+    with torch.cuda.device(dev):
+        rc = lib().normtest_layer_stats(gptr, 0 if rows is None else 1, _gdtype(first), J, d, ld, _ptr(layer_offsets), L,
+                                        _ptr(workspace), _ptr(layers), ctypes.c_void_p(stream.cuda_stream))
+    if rc != NT_OK:
+        raise NormtestError(rc, "normtest_layer_stats")
+    if table is not None:
+        table.record_stream(stream)
+    return layers
+
+
+def read_layers(layers: torch.Tensor, L: Optional[int] = None):
+    """Synchronising read of a device nt_layer_stats array: a list of nt_layer_stats."""
+    host = layers.cpu().numpy().tobytes()
+    L = len(host) // LAYER_BYTES if L is None else L
+    return [nt_layer_stats.from_buffer_copy(host, l * LAYER_BYTES) for l in range(L)]
 
 
 def normtest_clip_coef(gbar_sq: float, max_norm: float) -> float:

@@ -100,6 +100,9 @@
 #define NT_GROUP_THREADS 256   // first-stage reduction: threads per block
 #define NT_GROUP_TILES 2048    // ... and tile partials per block
 #define NT_DIRECT_TILES 4096   // up to this many tiles the finalize kernel reads the tile partials itself
+#define NT_WS_HEADER 16        // doubles in front of the tile partials: a record of the step that wrote them
+#define NT_WS_MAGIC 0x4e54574f524b5350ll
+#define NT_LAYER_THREADS 1024  // per-layer kernel: one block per layer
 
 namespace {
 
@@ -620,6 +623,18 @@ struct DecideParams {
   uint32_t flags;
 };
 
+// Record of the step whose tile partials sit in a workspace, kept in its first NT_WS_HEADER doubles so that
+// normtest_layer_stats can regroup them per layer and can tell when they belong to another call.
+struct WsHeader {
+  int64_t magic;
+  int64_t tile_coords, ntiles, ngroups;  // ngroups > 0: double-double group partials follow the tile partials
+  int64_t d, J;
+  int32_t gdtype, has_stats;
+  double coord_thr;                      // threshold factor of the coordinate-wise count, negative if off
+  DecideParams q;
+};
+static_assert(sizeof(WsHeader) <= NT_WS_HEADER * sizeof(double), "workspace header too small");
+
 // Global-norm clipping factor (training specifications of Sec. 5; usual convention with the 1e-6 guard).
 __host__ __device__ inline double clip_coef(double gbar_sq, double max_norm) {
   if (!(max_norm > 0.0)) return 1.0;
@@ -686,14 +701,11 @@ __device__ inline dd dd_wave_sum(dd x) {
   return x;
 }
 
-// Sum of n entries of NT_NV values each.  packed = false: plain tile partials {A, B, C, n_fail};
-// packed = true: double-double group partials {A, A_lo, B, B_lo, C, C_lo, n, n_lo}.
-// All threads of the block take part; thread 0 returns the totals in tot[NT_NV].
+// Adds this thread's share (entries threadIdx.x, threadIdx.x + THREADS, ...) of n entries of NT_NV values
+// each into acc.  packed = false: plain tile partials {A, B, C, n_fail}; packed = true: double-double
+// group partials {A, A_lo, B, B_lo, C, C_lo, n, n_lo}.
 template <int THREADS>
-__device__ inline void block_dd_sum(const double* in, int64_t n, bool packed, double (*sh)[2 * NT_NV], dd* tot) {
-  dd acc[NT_NV];
-#pragma unroll
-  for (int k = 0; k < NT_NV; ++k) acc[k] = {0.0, 0.0};
+__device__ inline void dd_accumulate(const double* in, int64_t n, bool packed, dd* acc) {
   for (int64_t t = threadIdx.x; t < n; t += THREADS) {
 #pragma unroll
     for (int k = 0; k < NT_NV; ++k) {
@@ -708,6 +720,11 @@ __device__ inline void block_dd_sum(const double* in, int64_t n, bool packed, do
       acc[k] = dd_add(acc[k], x);
     }
   }
+}
+
+// Block total of the threads' accumulators; all threads take part, thread 0 returns the totals in tot[NT_NV].
+template <int THREADS>
+__device__ inline void block_dd_finish(dd* acc, double (*sh)[2 * NT_NV], dd* tot) {
 #pragma unroll
   for (int k = 0; k < NT_NV; ++k) acc[k] = dd_wave_sum(acc[k]);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -732,6 +749,16 @@ __device__ inline void block_dd_sum(const double* in, int64_t n, bool packed, do
   }
 }
 
+// Sum of n entries of NT_NV values each (layouts as in dd_accumulate); thread 0 returns the totals.
+template <int THREADS>
+__device__ inline void block_dd_sum(const double* in, int64_t n, bool packed, double (*sh)[2 * NT_NV], dd* tot) {
+  dd acc[NT_NV];
+#pragma unroll
+  for (int k = 0; k < NT_NV; ++k) acc[k] = {0.0, 0.0};
+  dd_accumulate<THREADS>(in, n, packed, acc);
+  block_dd_finish<THREADS>(acc, sh, tot);
+}
+
 // First stage for long vectors: block g adds tile partials [g*NT_GROUP_TILES, ...) into one
 // double-double group partial.
 __global__ __launch_bounds__(NT_GROUP_THREADS) void k_reduce_groups(const double* partials, int64_t ntiles,
@@ -752,7 +779,7 @@ __global__ __launch_bounds__(NT_GROUP_THREADS) void k_reduce_groups(const double
 
 // One block: partials (tile or group) -> A, B, C in double-double, then the decision.
 __global__ __launch_bounds__(NT_FIN_THREADS) void k_finalize(const double* in, int64_t n, bool packed, DecideParams q,
-                                                             nt_result* out) {
+                                                             nt_result* out, WsHeader hdr, WsHeader* hdr_out) {
   __shared__ double sh[NT_FIN_THREADS / 64][2 * NT_NV];
   const bool stats = (q.flags & NT_DO_STATS) != 0;
   dd tot[NT_NV];
@@ -760,6 +787,7 @@ __global__ __launch_bounds__(NT_FIN_THREADS) void k_finalize(const double* in, i
   for (int k = 0; k < NT_NV; ++k) tot[k] = {0.0, 0.0};
   if (stats) block_dd_sum<NT_FIN_THREADS>(in, n, packed, sh, tot);
   if (threadIdx.x != 0) return;
+  *hdr_out = hdr;
   nt_result r;
   r.status = 0;
   r.coord_fail = (stats && (q.flags & NT_COORD_TEST)) ? (int64_t)tot[3].hi : -1;
@@ -788,6 +816,101 @@ __global__ __launch_bounds__(NT_FIN_THREADS) void k_finalize(const double* in, i
     }
   }
   *out = r;
+}
+
+// Per-layer statistics from what a step left behind.  Layer l owns coordinates offsets[l] .. offsets[l+1]-1.
+// Block l adds the partials of the tiles that lie wholly inside the layer (through the group partials
+// where a whole group does) and recomputes, from the gradient rows, the at most two pieces at the layer's
+// ends that cover only part of a tile; then the layer's own statistic (Alg. 1's T on the layer's
+// coordinates) is formed.  Offsets are clamped into [0, d], so every access stays in bounds whatever
+// the table holds; a clamped or descending pair is reported in the layer's status.
+template <class GT, bool TABLE>
+__global__ __launch_bounds__(NT_LAYER_THREADS) void k_layer_stats(StepParams p, const int64_t* offsets,
+                                                                  const double* ws, nt_layer_stats* out) {
+  __shared__ double sh[NT_LAYER_THREADS / 64][2 * NT_NV];
+  const WsHeader h = *(const WsHeader*)ws;
+  const int l = blockIdx.x;
+  const double nan = __builtin_nan("");
+  const bool usable = h.magic == NT_WS_MAGIC && h.has_stats && h.d == p.d && h.J == (int64_t)p.J &&
+                      h.gdtype == (GT::ESIZE == 4 ? (int32_t)NT_F32 : (int32_t)NT_BF16) && h.tile_coords > 0;
+  int64_t lo = offsets[l], hi = offsets[l + 1];
+  uint32_t status = 0;
+  if (lo < 0 || lo > p.d || hi < lo || hi > p.d) status |= NT_STATUS_BAD_RANGE;
+  lo = lo < 0 ? 0 : (lo > p.d ? p.d : lo);
+  hi = hi < lo ? lo : (hi > p.d ? p.d : hi);
+  if (!usable) {
+    if (threadIdx.x == 0) {
+      nt_layer_stats r;
+      r.A = r.B = r.C = r.gbar_sq = r.var_l1 = r.T = nan;
+      r.n = hi - lo;
+      r.coord_fail = -1;
+      r.pass = 1;
+      r.status = status | NT_STATUS_NO_STATS;
+      out[l] = r;
+    }
+    return;
+  }
+  p.coord_thr = (float)h.coord_thr;
+  const int64_t tc = h.tile_coords;
+  const int64_t first = (lo + tc - 1) / tc;                      // first tile that starts at or after lo
+  const int64_t head_end = first * tc < hi ? first * tc : hi;    // head piece [lo, head_end)
+  int64_t last = first, tail_lo = hi;                            // whole tiles [first, last), tail piece [tail_lo, hi)
+  if (head_end < hi) {
+    last = hi / tc;
+    tail_lo = last * tc;
+  }
+  double a = 0.0, b = 0.0, c = 0.0;
+  int64_t nfail = 0;
+  for (int piece = 0; piece < 2; ++piece) {
+    const int64_t plo = piece ? tail_lo : lo, phi = piece ? hi : head_end;
+    for (int64_t i = plo + threadIdx.x; i < phi; i += NT_LAYER_THREADS) {
+      double S;
+      float M2, aa;
+      coord_stats_generic<GT, TABLE>(p, i, S, M2, aa);
+      const float gb = (float)(S * p.inv_J);
+      const float sf = (float)S;
+      a += (double)aa;
+      b += (double)(sf * sf);
+      c += (double)M2;
+      nfail += coord_fails(p.coord_thr, M2, gb);
+    }
+  }
+  dd acc[NT_NV] = {{a, 0.0}, {b, 0.0}, {c, 0.0}, {(double)nfail, 0.0}};
+  const double* tiles = ws + NT_WS_HEADER;
+  const double* groups = tiles + NT_NV * h.ntiles;
+  const int64_t g0 = (first + NT_GROUP_TILES - 1) / NT_GROUP_TILES, g1 = last / NT_GROUP_TILES;
+  if (h.ngroups > 0 && g0 < g1) {
+    dd_accumulate<NT_LAYER_THREADS>(tiles + NT_NV * first, g0 * NT_GROUP_TILES - first, false, acc);
+    dd_accumulate<NT_LAYER_THREADS>(groups + 2 * NT_NV * g0, g1 - g0, true, acc);
+    dd_accumulate<NT_LAYER_THREADS>(tiles + NT_NV * g1 * NT_GROUP_TILES, last - g1 * NT_GROUP_TILES, false, acc);
+  } else {
+    dd_accumulate<NT_LAYER_THREADS>(tiles + NT_NV * first, last - first, false, acc);
+  }
+  dd tot[NT_NV];
+  block_dd_finish<NT_LAYER_THREADS>(acc, sh, tot);
+  if (threadIdx.x != 0) return;
+  nt_result t;
+  t.A = tot[0].hi;
+  t.B = tot[1].hi;
+  t.C = tot[2].hi;
+  t.status = 0;
+  DecideParams q = h.q;
+  q.b_max = 0;
+  q.round_to = 1;
+  q.max_norm = 0.0;
+  decide(q, &t);
+  nt_layer_stats r;
+  r.A = t.A;
+  r.B = t.B;
+  r.C = t.C;
+  r.gbar_sq = t.gbar_sq;
+  r.var_l1 = t.var_l1;
+  r.T = t.T;
+  r.n = hi - lo;
+  r.coord_fail = (h.coord_thr >= 0.0) ? (int64_t)tot[3].hi : -1;
+  r.pass = t.pass;
+  r.status = status | (t.status & (NT_STATUS_NONFINITE | NT_STATUS_ZERO_GRAD_NORM | NT_STATUS_T_SATURATED));
+  out[l] = r;
 }
 
 // Phase 2 of the clipped variant: AdamW on scale * gbar, gbar read from memory.  One sweep per block,
@@ -947,7 +1070,7 @@ size_t normtest_workspace_bytes(int64_t J, int64_t d) {
   const int64_t ntiles = (d + tc - 1) / tc;
   const int64_t n = ntiles > 0 ? ntiles : 1;
   const int64_t ngroups = ntiles > NT_DIRECT_TILES ? (ntiles + NT_GROUP_TILES - 1) / NT_GROUP_TILES : 0;
-  return (size_t)(n * NT_NV + ngroups * 2 * NT_NV) * sizeof(double);
+  return (size_t)(NT_WS_HEADER + n * NT_NV + ngroups * 2 * NT_NV) * sizeof(double);
 }
 
 // AdamW constants in fp64 on the host, rounded once to fp32.
@@ -1010,7 +1133,7 @@ static int enqueue_step(const void* grads, bool table, nt_dtype gdtype, int64_t 
   p.m = m;
   p.v = v;
   p.gbar = (flags & NT_WRITE_GBAR) ? gbar_out : nullptr;
-  p.partials = (double*)workspace;
+  p.partials = (double*)workspace + NT_WS_HEADER;
   p.inv_J = 1.0 / (double)J;
   if (flags & NT_DO_ADAMW) fill_adamw_params(p, hyper);
   p.coord_thr = (flags & NT_COORD_TEST)
@@ -1044,16 +1167,32 @@ static int enqueue_step(const void* grads, bool table, nt_dtype gdtype, int64_t 
   q.round_to = hyper->round_to;
   q.ddof = hyper->ddof;
   q.flags = flags;
-  const double* partials = (const double*)workspace;
-  if ((flags & NT_DO_STATS) && ntiles > NT_DIRECT_TILES) {
-    const int64_t ngroups = (ntiles + NT_GROUP_TILES - 1) / NT_GROUP_TILES;
-    double* groups = (double*)workspace + NT_NV * ntiles;
+  const double* partials = (const double*)workspace + NT_WS_HEADER;
+  const bool two_level = (flags & NT_DO_STATS) && ntiles > NT_DIRECT_TILES;
+  const int64_t ngroups = two_level ? (ntiles + NT_GROUP_TILES - 1) / NT_GROUP_TILES : 0;
+  WsHeader hdr;
+  std::memset(&hdr, 0, sizeof(hdr));
+  hdr.magic = NT_WS_MAGIC;
+  hdr.tile_coords = tc;
+  hdr.ntiles = ntiles;
+  hdr.ngroups = ngroups;
+  hdr.d = d;
+  hdr.J = J;
+  hdr.gdtype = (int32_t)gdtype;
+  hdr.has_stats = (flags & NT_DO_STATS) ? 1 : 0;
+  hdr.coord_thr = (double)p.coord_thr;
+  hdr.q = q;
+  WsHeader* hdr_out = (WsHeader*)workspace;
+  if (two_level) {
+    double* groups = (double*)workspace + NT_WS_HEADER + NT_NV * ntiles;
     hipLaunchKernelGGL(k_reduce_groups, dim3((unsigned)ngroups), dim3(NT_GROUP_THREADS), 0, st, partials, ntiles, groups);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_code(e);
-    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(NT_FIN_THREADS), 0, st, (const double*)groups, ngroups, true, q, result_dev);
+    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(NT_FIN_THREADS), 0, st, (const double*)groups, ngroups, true, q, result_dev,
+                       hdr, hdr_out);
   } else {
-    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(NT_FIN_THREADS), 0, st, partials, ntiles, false, q, result_dev);
+    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(NT_FIN_THREADS), 0, st, partials, ntiles, false, q, result_dev, hdr,
+                       hdr_out);
   }
   return hip_code(hipGetLastError());
 }
@@ -1113,9 +1252,45 @@ int normtest_step_clipped(const void* grads, nt_dtype gdtype, int64_t J, int64_t
   if (rc != NT_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
   const int rc1 = enqueue_step(grads, false, gdtype, J, d, ld, nullptr, nullptr, nullptr, gbar_buf,
-                               NT_DO_STATS | NT_WRITE_GBAR, hyper, max_norm, workspace, result_dev, st);
+                               NT_DO_STATS | NT_WRITE_GBAR | (hyper->flags & NT_COORD_TEST), hyper, max_norm, workspace,
+                               result_dev, st);
   if (rc1 != NT_OK) return rc1;
   return enqueue_adamw_gbar(gbar_buf, d, w, m, v, hyper, 1.0, result_dev, st);
+}
+
+int normtest_layer_stats(const void* grads, int rows_are_table, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld,
+                         const int64_t* layer_offsets_dev, int32_t L, const void* workspace,
+                         nt_layer_stats* layers_dev, void* hip_stream) {
+  if (gdtype != NT_F32 && gdtype != NT_BF16) return NT_ERR_UNSUPPORTED;
+  if (J < 2 || J > (1 << 20) || d < 0 || (!rows_are_table && ld < d)) return NT_ERR_BAD_ARG;
+  if (L < 1 || L > (1 << 24) || !layer_offsets_dev || !workspace || !layers_dev) return NT_ERR_BAD_ARG;
+  if (((uintptr_t)layer_offsets_dev & 7u) || ((uintptr_t)workspace & 7u) || ((uintptr_t)layers_dev & 7u))
+    return NT_ERR_BAD_ARG;
+  if (d > 0 && !grads) return NT_ERR_BAD_ARG;
+  const int esize = gdtype == NT_F32 ? 4 : 2;
+  if ((uintptr_t)grads & (uintptr_t)(rows_are_table ? 7 : esize - 1)) return NT_ERR_BAD_ARG;
+  StepParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.grads = grads;
+  p.ld = rows_are_table ? d : ld;
+  p.d = d;
+  p.J = (int)J;
+  p.inv_J = 1.0 / (double)J;
+  p.coord_thr = -1.0f;  // the kernel takes the threshold of the recorded step
+  hipStream_t st = (hipStream_t)hip_stream;
+  const double* ws = (const double*)workspace;
+  if (rows_are_table) {
+    if (gdtype == NT_F32)
+      hipLaunchKernelGGL((k_layer_stats<F32, true>), dim3(L), dim3(NT_LAYER_THREADS), 0, st, p, layer_offsets_dev, ws, layers_dev);
+    else
+      hipLaunchKernelGGL((k_layer_stats<BF16, true>), dim3(L), dim3(NT_LAYER_THREADS), 0, st, p, layer_offsets_dev, ws, layers_dev);
+  } else {
+    if (gdtype == NT_F32)
+      hipLaunchKernelGGL((k_layer_stats<F32, false>), dim3(L), dim3(NT_LAYER_THREADS), 0, st, p, layer_offsets_dev, ws, layers_dev);
+    else
+      hipLaunchKernelGGL((k_layer_stats<BF16, false>), dim3(L), dim3(NT_LAYER_THREADS), 0, st, p, layer_offsets_dev, ws, layers_dev);
+  }
+  return hip_code(hipGetLastError());
 }
 
 int normtest_adamw_gbar(const float* gbar, int64_t d, float* w, float* m, float* v, const nt_hyper* hyper,

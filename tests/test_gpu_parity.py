@@ -433,6 +433,14 @@ def test_coordinatewise_count_degenerate_and_sharded():
     big[:, 1:] = wl.grads
     off = gpu_step(big[:, 1:], wl.w, wl.m, wl.v, wl.hyper, flags=B.NT_DO_STATS | B.NT_COORD_TEST)
     assert off["coord_fail"] == whole["coord_fail"]
+    # the clipped two-phase step counts too (its statistics phase uses another tile shape)
+    gbar = torch.empty(d, dtype=torch.float32, device=DEV)
+    r = B.normtest_step_clipped(wl.grads, wl.w, wl.m, wl.v, gbar, 1.0, hyper_of(wl.hyper, FULL | B.NT_COORD_TEST))
+    torch.cuda.synchronize()
+    assert B.read_result(r).coord_fail == whole["coord_fail"]
+    r = B.normtest_step_clipped(wl.grads, wl.w, wl.m, wl.v, gbar, 1.0, hyper_of(wl.hyper, FULL))
+    torch.cuda.synchronize()
+    assert B.read_result(r).coord_fail == -1
 
 
 # ------------------------------------------------------------------ rows given as separate allocations

@@ -25,7 +25,7 @@ def test_every_declared_symbol_is_exported():
     names = declared_functions()
     assert {"normtest_step", "normtest_combine", "normtest_workspace_bytes", "normtest_tile_coords",
             "normtest_strerror", "normtest_calib_copy", "normtest_step_clipped", "normtest_adamw_gbar",
-            "normtest_clip_coef", "normtest_step_rows", "normtest_resplit"} <= set(names)
+            "normtest_clip_coef", "normtest_step_rows", "normtest_resplit", "normtest_layer_stats"} <= set(names)
     L = B.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -35,6 +35,7 @@ def test_struct_layouts_match_header():
     assert ctypes.sizeof(B.nt_hyper) == 6 * 8 + 4 * 8 + 4 + 4
     assert ctypes.sizeof(B.nt_result) == 10 * 8 + 8 + 8 + 4 + 4
     assert ctypes.sizeof(B.nt_shard_info) == 4 + 4 + 8 + 8
+    assert ctypes.sizeof(B.nt_layer_stats) == 6 * 8 + 8 + 8 + 4 + 4
 
 
 def test_workspace_and_tiles():
@@ -44,9 +45,10 @@ def test_workspace_and_tiles():
         prev = 0
         for d in (0, 1, tc, tc + 1, 5000 * tc, 1_500_000_000):
             need = B.normtest_workspace_bytes(J, d)
-            # four doubles per tile; tiles are at most tc and at least 1024 coordinates; plus a small second level
-            lo = 32 * max(1, -(-d // tc))
-            hi = 32 * max(1, -(-d // 1024))
+            # a 128-byte record, four doubles per tile (tiles are at most tc and at least 1024 coordinates), and
+            # a small second level
+            lo = 128 + 32 * max(1, -(-d // tc))
+            hi = 128 + 32 * max(1, -(-d // 1024))
             assert lo <= need <= hi + hi // 256 + 64
             assert need >= prev and need % 8 == 0
             prev = need
@@ -141,6 +143,29 @@ def test_rows_entry_point_validates_before_launch():
     assert call(w=None) == bad
     assert call(gdtype=9) == B.NT_ERR_UNSUPPORTED
     assert call(ws_bytes=0) == B.NT_ERR_WORKSPACE_TOO_SMALL
+
+
+def test_layer_entry_point_validates_before_launch():
+    L = B.lib()
+
+    def call(grads=0x1000, table=0, gdtype=B.NT_BF16, J=4, d=64, ld=64, off=0x2000, n=3, ws=0x5000, out=0x6000):
+        return L.normtest_layer_stats(grads, table, gdtype, J, d, ld, off, n, ws, out, None)
+
+    bad = B.NT_ERR_BAD_ARG
+    assert call(grads=None) == bad
+    assert call(grads=0x1001) == bad
+    assert call(table=1, grads=0x1004) == bad     # a pointer table must be 8-byte aligned
+    assert call(J=1) == bad
+    assert call(d=-1) == bad
+    assert call(ld=63) == bad
+    assert call(off=None) == bad
+    assert call(off=0x2004) == bad
+    assert call(n=0) == bad
+    assert call(ws=None) == bad
+    assert call(ws=0x5004) == bad
+    assert call(out=None) == bad
+    assert call(out=0x6004) == bad
+    assert call(gdtype=5) == B.NT_ERR_UNSUPPORTED
 
 
 def test_resplit_matches_oracle():
