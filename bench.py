@@ -100,6 +100,9 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink d (debugging only; the result is then not the headline)")
     ap.add_argument("--mode", default="full", choices=["full", "stats", "adamw", "clipped"],
                     help="full: the fused step (headline); stats / adamw: one half only; clipped: two-phase variant")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="also produce the per-layer table each step: -1 = the workload's own parameter blocks, "
+                         "N > 0 = N layers of uneven, unaligned sizes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 29)
     ap.add_argument("--calib-copy-gib", type=int, default=0,
@@ -129,6 +132,26 @@ def main():
     workspace = torch.empty(B.normtest_workspace_bytes(wl.J, wl.d), dtype=torch.uint8, device=dev)
     result = torch.empty(B.RESULT_BYTES, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
+    layer_off = layer_out = None
+    if args.layers and args.mode == "adamw":
+        raise SystemExit("--layers needs a mode that computes the statistics")
+    if args.layers:
+        if args.layers < 0:
+            if not wl.meta.get("block_sizes"):
+                raise SystemExit("--layers -1 needs a workload with parameter blocks (gpt2_small, per_sample)")
+            sizes = wl.meta["block_sizes"]
+        else:
+            # sizes proportional to 1, 2, ..., N with odd remainders so that no boundary is aligned
+            tot = args.layers * (args.layers + 1) // 2
+            sizes = [max(1, (wl.d * (i + 1) // tot) | 1) for i in range(args.layers)]
+            sizes[-1] = wl.d - sum(sizes[:-1])
+            if sizes[-1] < 1:
+                raise SystemExit("--layers: too many layers for this d")
+        offs = [0]
+        for sz in sizes:
+            offs.append(offs[-1] + sz)
+        layer_off = torch.tensor(offs, dtype=torch.int64, device=dev)
+        layer_out = torch.empty(len(sizes) * B.LAYER_BYTES, dtype=torch.uint8, device=dev)
 
     def step():
         if args.mode == "clipped":
@@ -136,6 +159,8 @@ def main():
                                     result=result, stream=stream)
         else:
             B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hy, workspace=workspace, result=result, stream=stream)
+        if layer_off is not None:
+            B.normtest_layer_stats(wl.grads, layer_off, workspace, layers=layer_out, stream=stream)
 
     if args.calib_copy_gib > 0:
         src = torch.zeros(args.calib_copy_gib << 28, dtype=torch.float32, device=dev)
@@ -188,6 +213,7 @@ def main():
             "mode": args.mode,
             "J": wl.J, "d": wl.d, "grad_dtype": "bf16" if wl.grad_bytes == 2 else "f32",
             "bytes_per_param": bytes_per_param, "flags": flags,
+            "layers": 0 if layer_off is None else layer_off.numel() - 1,
         },
         "result": {k: res[k] for k in ("T", "pass", "next_b", "status")},
         "roofline": {

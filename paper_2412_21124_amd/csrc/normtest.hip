@@ -818,6 +818,44 @@ __global__ __launch_bounds__(NT_FIN_THREADS) void k_finalize(const double* in, i
   *out = r;
 }
 
+// Sums over the coordinates [plo, phi) taken one by one, NT_LAYER_THREADS apart per thread.  J_T > 0: the row
+// count is known at compile time, so the J loads of a coordinate are issued together and kept in registers;
+// the arithmetic is coord_stats_generic's, operation for operation.  J_T = 0: any J.
+template <class GT, bool TABLE, int J_T>
+__device__ inline void piece_sums(const StepParams& p, int64_t plo, int64_t phi, double& a, double& b, double& c,
+                                  int64_t& nfail) {
+#pragma unroll 2
+  for (int64_t i = plo + threadIdx.x; i < phi; i += NT_LAYER_THREADS) {
+    double S;
+    float M2, aa;
+    if constexpr (J_T > 0) {
+      float x[J_T];
+#pragma unroll
+      for (int j = 0; j < J_T; ++j) x[j] = GT::ld(row_base<GT, TABLE>(p, j), i);
+      S = (double)x[0];
+#pragma unroll
+      for (int j = 1; j < J_T; ++j) S += (double)x[j];
+      const float mb = (float)(S * p.inv_J);
+      M2 = 0.f;
+      aa = 0.f;
+#pragma unroll
+      for (int j = 0; j < J_T; ++j) {
+        const float r = x[j] - mb;
+        M2 = __builtin_fmaf(r, r, M2);
+        aa = __builtin_fmaf(x[j], x[j], aa);
+      }
+    } else {
+      coord_stats_generic<GT, TABLE>(p, i, S, M2, aa);
+    }
+    const float gb = (float)(S * p.inv_J);
+    const float sf = (float)S;
+    a += (double)aa;
+    b += (double)(sf * sf);
+    c += (double)M2;
+    nfail += coord_fails(p.coord_thr, M2, gb);
+  }
+}
+
 // Per-layer statistics from what a step left behind.  Layer l owns coordinates offsets[l] .. offsets[l+1]-1.
 // Block l adds the partials of the tiles that lie wholly inside the layer (through the group partials
 // where a whole group does) and recomputes, from the gradient rows, the at most two pieces at the layer's
@@ -863,17 +901,17 @@ __global__ __launch_bounds__(NT_LAYER_THREADS) void k_layer_stats(StepParams p, 
   int64_t nfail = 0;
   for (int piece = 0; piece < 2; ++piece) {
     const int64_t plo = piece ? tail_lo : lo, phi = piece ? hi : head_end;
-    for (int64_t i = plo + threadIdx.x; i < phi; i += NT_LAYER_THREADS) {
-      double S;
-      float M2, aa;
-      coord_stats_generic<GT, TABLE>(p, i, S, M2, aa);
-      const float gb = (float)(S * p.inv_J);
-      const float sf = (float)S;
-      a += (double)aa;
-      b += (double)(sf * sf);
-      c += (double)M2;
-      nfail += coord_fails(p.coord_thr, M2, gb);
+    if (plo >= phi) continue;
+#define NT_CASE(JJ) \
+  case JJ:          \
+    piece_sums<GT, TABLE, JJ>(p, plo, phi, a, b, c, nfail); \
+    break;
+    switch (p.J) {
+      NT_CASE(2) NT_CASE(3) NT_CASE(4) NT_CASE(5) NT_CASE(6) NT_CASE(7) NT_CASE(8) NT_CASE(9)
+      NT_CASE(10) NT_CASE(11) NT_CASE(12) NT_CASE(13) NT_CASE(14) NT_CASE(15) NT_CASE(16)
+      default: piece_sums<GT, TABLE, 0>(p, plo, phi, a, b, c, nfail);
     }
+#undef NT_CASE
   }
   dd acc[NT_NV] = {{a, 0.0}, {b, 0.0}, {c, 0.0}, {(double)nfail, 0.0}};
   const double* tiles = ws + NT_WS_HEADER;

@@ -171,7 +171,8 @@ def make(name: str, J: int, d: int, *, gdtype=torch.float32, sigma: float = 1e-2
     else:
         w = m = v = torch.empty(0, dtype=torch.float32, device=device)
     meta = dict(sigma=sigma, mu=mu, mu_scale=mu_scale, noise=noise, seed=seed,
-                n_blocks=0 if block_sizes is None else len(block_sizes))
+                n_blocks=0 if block_sizes is None else len(block_sizes),
+                block_sizes=None if block_sizes is None else list(block_sizes))
     return Workload(name, J, d, ld, grads, w, m, v, hyper or Hyper(), meta)
 
 

@@ -4,6 +4,7 @@ inputs to the host chunk by chunk; every sum and every updated w, m, v element i
 import math
 import time
 
+import numpy as np
 import pytest
 import torch
 
@@ -69,6 +70,46 @@ def test_gpt2_small_full(ratio):
     assert wl.d == 124_439_808 and wl.meta["n_blocks"] == 148
     res, ref = run_and_check(wl)
     assert bool(res["pass"]) == (ratio < 1.94)
+
+
+def test_gpt2_small_layer_table():
+    """The per-layer table at full size: the 148 parameter blocks of the 124M-parameter model (sizes from 768
+    to 38.6M coordinates, most boundaries inside a tile), every layer against the oracle on its columns."""
+    import oracle
+    wl = synth.gpt2_small(1.0, device=DEV)
+    h = wl.hyper
+    sizes = wl.meta["block_sizes"]
+    offsets = [0]
+    for s in sizes:
+        offsets.append(offsets[-1] + s)
+    assert len(sizes) == 148 and offsets[-1] == wl.d
+    hy = B.make_hyper(lr=h.lr, beta1=h.beta1, beta2=h.beta2, eps=h.eps, weight_decay=h.weight_decay, eta=h.eta,
+                      step=h.step, b_k=h.b_k, b_max=h.b_max, round_to=h.round_to, ddof=h.ddof,
+                      flags=FULL | B.NT_COORD_TEST)
+    workspace = torch.empty(B.normtest_workspace_bytes(wl.J, wl.d), dtype=torch.uint8, device=DEV)
+    off = torch.tensor(offsets, dtype=torch.int64, device=DEV)
+    res = B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hy, workspace=workspace)
+    lay = B.normtest_layer_stats(wl.grads, off, workspace)
+    torch.cuda.synchronize()
+    res = B.read_result(res).as_dict()
+    layers = [x.as_dict() for x in B.read_layers(lay)]
+    G = synth.grads_as_numpy(wl.grads, 0, wl.d)
+    ref = oracle.layer_stats(G, offsets, h.eta, h.b_k, h.ddof, band=H.STATS_RTOL)
+    for l, (got, want) in enumerate(zip(layers, ref)):
+        assert got["n"] == sizes[l] and got["status"] == 0, l
+        for k in "ABC":
+            assert got[k] == pytest.approx(want[k], rel=H.STATS_RTOL), (l, k)
+        assert got["T"] == pytest.approx(want["dec"].T, rel=2 * H.STATS_RTOL), l
+        fail, near, _ = want["coord"]
+        assert fail <= got["coord_fail"] <= fail + near, l
+    for k in "ABC":
+        assert math.fsum(x[k] for x in layers) == pytest.approx(res[k], rel=1e-7)
+    assert sum(x["coord_fail"] for x in layers) == res["coord_fail"]
+    # every block shares mu and sigma up to its scale, which cancels in T: the layers' statistics agree with the
+    # whole vector's up to sampling noise (largest for the 768-coordinate blocks)
+    Ts = np.array([x["T"] for x in layers])
+    assert np.all(np.abs(Ts / res["T"] - 1) < 0.25)
+    print("gpt2_small layers: T whole %.4g, per layer min %.4g max %.4g" % (res["T"], Ts.min(), Ts.max()), flush=True)
 
 
 def test_flat_1p5b_full():
