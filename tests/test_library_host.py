@@ -38,6 +38,45 @@ def test_struct_layouts_match_header():
     assert ctypes.sizeof(B.nt_layer_stats) == 6 * 8 + 8 + 8 + 4 + 4
 
 
+def test_plain_c_client_sees_the_layout_the_binding_assumes(tmp_path):
+    """include/normtest.h compiles as strict C99; a C program linked against the library calls the host-only
+    entry points; every struct field offset and enum value it prints equals the ctypes mirror's."""
+    import subprocess
+    libpath = B.lib()._name
+    exe = str(tmp_path / "abi_probe")
+    libdir = os.path.dirname(libpath)
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "abi_probe.c"), "-o", exe, "-L", libdir, "-lnormtest",
+                    "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib", "-Wl,--allow-shlib-undefined"], check=True)
+    out = subprocess.run([exe], check=True, capture_output=True, text=True).stdout.splitlines()
+    mirrors = {"nt_hyper": B.nt_hyper, "nt_shard_info": B.nt_shard_info, "nt_result": B.nt_result,
+               "nt_layer_stats": B.nt_layer_stats}
+    seen = {k: 0 for k in mirrors}
+    n_enum = 0
+    for line in out:
+        tok = line.split()
+        if tok[0] == "size":
+            assert ctypes.sizeof(mirrors[tok[1]]) == int(tok[2]), line
+        elif tok[0] == "field":
+            cls = mirrors[tok[1]]
+            name = "pass_" if tok[2] == "pass" else tok[2]
+            f = getattr(cls, name)
+            assert (f.offset, f.size) == (int(tok[3]), int(tok[4])), line
+            seen[tok[1]] += 1
+        elif tok[0] == "enum":
+            assert getattr(B, tok[1]) == int(tok[2]), line
+            n_enum += 1
+    for k, cls in mirrors.items():
+        assert seen[k] == len(cls._fields_), k          # every field of the mirror exists in the header and back
+    assert n_enum == 19
+    lines = {l.split()[0]: l.split()[1:] for l in out if l.split()[0] in ("combine", "resplit", "clip", "workspace", "tile", "strerror")}
+    A, Bv, C, T, passed, next_b = lines["combine"]
+    assert (float(A), float(Bv), float(C), float(T), int(passed), int(next_b)) == (50.0, 80.0, 10.0, 2.0, 0, 2)
+    assert [int(x) for x in lines["resplit"]] == [8, 256, 8192]
+    assert float(lines["clip"][0]) == pytest.approx(1.0 / (2.0 + 1e-6), rel=1e-15)
+    assert int(lines["workspace"][0]) == B.normtest_workspace_bytes(8, 1000000) and int(lines["workspace"][2]) == 16384
+
+
 def test_workspace_and_tiles():
     for J in (2, 8, 16, 17, 512):
         tc = B.normtest_tile_coords(J)
