@@ -313,7 +313,33 @@ __device__ inline void coord_stats_generic(const StepParams& p, int64_t i, doubl
   }
 }
 
-template <class GT, int MODE, int BLOCK, bool TABLE, bool GBAR>
+// The same for a row count known at compile time (2 .. NT_JCHUNK): the J loads of a coordinate are issued
+// together and kept in registers; the arithmetic is coord_stats_generic's, operation for operation.
+// J_T = 0 forwards to the generic form.
+template <class GT, bool TABLE, int J_T>
+__device__ inline void coord_stats(const StepParams& p, int64_t i, double& S, float& M2, float& a) {
+  if constexpr (J_T > 0) {
+    float x[J_T];
+#pragma unroll
+    for (int j = 0; j < J_T; ++j) x[j] = GT::ld(row_base<GT, TABLE>(p, j), i);
+    S = (double)x[0];
+#pragma unroll
+    for (int j = 1; j < J_T; ++j) S += (double)x[j];
+    const float mb = (float)(S * p.inv_J);
+    M2 = 0.f;
+    a = 0.f;
+#pragma unroll
+    for (int j = 0; j < J_T; ++j) {
+      const float r = x[j] - mb;
+      M2 = __builtin_fmaf(r, r, M2);
+      a = __builtin_fmaf(x[j], x[j], a);
+    }
+  } else {
+    coord_stats_generic<GT, TABLE>(p, i, S, M2, a);
+  }
+}
+
+template <class GT, int J_T, int MODE, int BLOCK, bool TABLE, bool GBAR>
 __device__ inline void guarded_tile(const StepParams& p, int64_t tile, int tile_coords, double (*red)[BLOCK / 64][NT_NV],
                                     int buf) {
   constexpr int VEC = GT::VEC;
@@ -330,7 +356,7 @@ __device__ inline void guarded_tile(const StepParams& p, int64_t tile, int tile_
       if (i < p.d) {
         double S;
         float M2, aa;
-        coord_stats_generic<GT, TABLE>(p, i, S, M2, aa);
+        coord_stats<GT, TABLE, J_T>(p, i, S, M2, aa);
         const float gb = (float)(S * p.inv_J);
         const float sf = (float)S;
         a[e] = aa;
@@ -591,7 +617,7 @@ __global__ __launch_bounds__(BLOCK, NT_WAVES_PER_EU) void k_step(StepParams p, i
       else
         fast_tile_multi<GT, MODE, BLOCK, ITERS, TABLE, GBAR>(p, tile, red, buf);
     } else {
-      guarded_tile<GT, MODE, BLOCK, TABLE, GBAR>(p, tile, TILE, red, buf);
+      guarded_tile<GT, J_T, MODE, BLOCK, TABLE, GBAR>(p, tile, TILE, red, buf);
     }
     buf ^= 1;
   }
@@ -818,9 +844,8 @@ __global__ __launch_bounds__(NT_FIN_THREADS) void k_finalize(const double* in, i
   *out = r;
 }
 
-// Sums over the coordinates [plo, phi) taken one by one, NT_LAYER_THREADS apart per thread.  J_T > 0: the row
-// count is known at compile time, so the J loads of a coordinate are issued together and kept in registers;
-// the arithmetic is coord_stats_generic's, operation for operation.  J_T = 0: any J.
+// Sums over the coordinates [plo, phi) taken one by one, NT_LAYER_THREADS apart per thread.  J_T > 0: row
+// count known at compile time; J_T = 0: any J.
 template <class GT, bool TABLE, int J_T>
 __device__ inline void piece_sums(const StepParams& p, int64_t plo, int64_t phi, double& a, double& b, double& c,
                                   int64_t& nfail) {
@@ -828,25 +853,7 @@ __device__ inline void piece_sums(const StepParams& p, int64_t plo, int64_t phi,
   for (int64_t i = plo + threadIdx.x; i < phi; i += NT_LAYER_THREADS) {
     double S;
     float M2, aa;
-    if constexpr (J_T > 0) {
-      float x[J_T];
-#pragma unroll
-      for (int j = 0; j < J_T; ++j) x[j] = GT::ld(row_base<GT, TABLE>(p, j), i);
-      S = (double)x[0];
-#pragma unroll
-      for (int j = 1; j < J_T; ++j) S += (double)x[j];
-      const float mb = (float)(S * p.inv_J);
-      M2 = 0.f;
-      aa = 0.f;
-#pragma unroll
-      for (int j = 0; j < J_T; ++j) {
-        const float r = x[j] - mb;
-        M2 = __builtin_fmaf(r, r, M2);
-        aa = __builtin_fmaf(x[j], x[j], aa);
-      }
-    } else {
-      coord_stats_generic<GT, TABLE>(p, i, S, M2, aa);
-    }
+    coord_stats<GT, TABLE, J_T>(p, i, S, M2, aa);
     const float gb = (float)(S * p.inv_J);
     const float sf = (float)S;
     a += (double)aa;
