@@ -73,6 +73,8 @@ def _bind(path: str):
     lib.nto_coord_test.restype = ctypes.c_int
     lib.nto_resplit.argtypes = [i64, i64, i64, i64, vp, vp, vp]
     lib.nto_resplit.restype = ctypes.c_int
+    lib.nto_test_due.argtypes = [i64, i64, i64, i64]
+    lib.nto_test_due.restype = ctypes.c_int
     lib.nto_clip_coef.argtypes = [dbl, dbl]
     lib.nto_clip_coef.restype = dbl
     return lib
@@ -177,6 +179,17 @@ def resplit(b: int, J: int, M_base: int, micro_max: int):
     if rc:
         raise ValueError("nto_resplit rejected its arguments")
     return int(out[0]), int(out[1]), int(out[2])
+
+
+def test_due(step: int, interval: int, b_k: int, b_max: int = 0) -> bool:
+    """Does step `step` (counted from 1) run the test, given the test interval and the batch-size maximum?"""
+    rc = _load().nto_test_due(step, interval, b_k, b_max)
+    if rc < 0:
+        raise ValueError("nto_test_due rejected its arguments")
+    return bool(rc)
+
+
+test_due.__test__ = False  # not a pytest test, whatever its name
 
 
 def clip_coef(gbar_sq: float, max_norm: float) -> float:

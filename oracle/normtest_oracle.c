@@ -191,6 +191,20 @@ int nto_resplit(int64_t b, int64_t J, int64_t M_base, int64_t micro_max, int64_t
 }
 
 /*
+ * Which steps run the test (Sec. 5, training specifications; "Test interval" in the hyper-parameter tables).
+ * Two rules are stated: the test is performed at a fixed interval of steps rather than at every step, and it
+ * is no longer performed once the global batch size has reached its maximum.  Reading taken where the text is
+ * silent: steps are counted from 1 and the first step tests, so step k tests when (k - 1) is a multiple of the
+ * interval; "reached" means b_k >= b_max (a test could not enlarge the batch any more), b_max = 0 meaning no
+ * maximum.  Returns 1 if step k runs the test, 0 if not, -1 for invalid arguments.
+ */
+int nto_test_due(int64_t step, int64_t interval, int64_t b_k, int64_t b_max) {
+  if (step < 1 || interval < 1 || b_k < 1 || b_max < 0) return -1;
+  if (b_max > 0 && b_k >= b_max) return 0;
+  return (step - 1) % interval == 0 ? 1 : 0;
+}
+
+/*
  * Coordinate-wise form of the test.  The analysis (Sec. 4, Prop. 1; App. B remark) asks the norm-test
  * condition of every coordinate i separately; with the same estimators as the aggregate test this reads
  *   Var_i / b_k <= eta^2 gbar_i^2,   Var_i = sum_j (g_j[i] - gbar_i)^2 / (J - ddof),

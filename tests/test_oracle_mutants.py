@@ -48,6 +48,11 @@ MUTANTS = [
     ("resplit_ignores_cap", "if (m < M_base) m = M_base;", "m = M_base;"),
     ("resplit_floor_micro", "mb = b / (J * m) + (b % (J * m) != 0);", "mb = b / (J * m);"),
     ("resplit_steps_from_total", "m = per_worker / micro_max + (per_worker % micro_max != 0);", "m = b / micro_max + (b % micro_max != 0);"),
+    ("due_counts_from_zero", "return (step - 1) % interval == 0 ? 1 : 0;", "return step % interval == 0 ? 1 : 0;"),
+    ("due_ignores_interval", "return (step - 1) % interval == 0 ? 1 : 0;", "return 1;"),
+    ("due_ignores_maximum", "if (b_max > 0 && b_k >= b_max) return 0;", ""),
+    ("due_strictly_above_maximum", "if (b_max > 0 && b_k >= b_max) return 0;", "if (b_max > 0 && b_k > b_max) return 0;"),
+    ("due_zero_maximum_stops", "if (b_max > 0 && b_k >= b_max) return 0;", "if (b_k >= b_max) return 0;"),
     ("clip_never", "return c < 1.0 ? c : 1.0;", "return 1.0;"),
     ("clip_always", "return c < 1.0 ? c : 1.0;", "return c;"),
     ("clip_uses_squared_norm", "c = max_norm / (sqrt(gbar_sq) + 1e-6);", "c = max_norm / (gbar_sq + 1e-6);"),
@@ -94,6 +99,7 @@ def battery():
         P.test_clipped_step_matches_library_clipping,
         lambda: P.test_coordinatewise_brute_force_and_invariants(3),
         P.test_resplit_reproduces_the_papers_table_values_and_invariants,
+        P.test_test_schedule_interval_and_maximum,
     ]
     return checks
 

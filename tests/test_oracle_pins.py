@@ -542,6 +542,27 @@ def test_resplit_reproduces_the_papers_table_values_and_invariants():
         oracle.resplit(0, 4, 16, 8)
 
 
+def test_test_schedule_interval_and_maximum():
+    """Sec. 5: fixed-interval testing, no test once the batch size is at its maximum.  The paper's runs use
+    interval 1: every step tests while b_k < b_max = 8192 and none after."""
+    assert all(oracle.test_due(k, 1, 256, 8192) for k in range(1, 200))
+    assert not any(oracle.test_due(k, 1, 8192, 8192) for k in range(1, 200))
+    assert not oracle.test_due(1, 1, 9000, 8192)
+    assert oracle.test_due(7, 1, 10 ** 9, 0)                       # no maximum: never switched off
+    # interval 5, counted from the first step: steps 1, 6, 11, ... test
+    due = [k for k in range(1, 23) if oracle.test_due(k, 5, 128, 8192)]
+    assert due == [1, 6, 11, 16, 21]
+    # over any window of n*interval consecutive steps exactly n tests run
+    for interval in (2, 3, 7, 16):
+        for start in (1, 4, 30):
+            assert sum(oracle.test_due(k, interval, 64, 0) for k in range(start, start + 4 * interval)) == 4
+    # one below the maximum still tests
+    assert oracle.test_due(1, 1, 8191, 8192)
+    for bad in ((0, 1, 32, 0), (1, 0, 32, 0), (1, 1, 0, 0), (1, 1, 32, -1)):
+        with pytest.raises(ValueError):
+            oracle.test_due(*bad)
+
+
 def test_argument_checks():
     with pytest.raises(ValueError):
         oracle.decide(1, 1, 1, 1, 0.1, 32, 0, 1, 1)      # J - ddof = 0
