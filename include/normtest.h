@@ -229,6 +229,17 @@ double normtest_clip_coef(double gbar_sq, double max_norm);
 int normtest_resplit(int64_t b, int64_t J, int64_t accum_base, int64_t micro_max,
                      int64_t* micro, int64_t* accum, int64_t* global_batch);
 
+/*
+ * Host helper: the flags for step `step` (k >= 1) under the two scheduling rules of Sec. 5 (training
+ * specifications; "Test interval" in the hyper-parameter tables): the test runs at a fixed interval of steps,
+ * and not at all once the global batch size has reached its maximum.  Returns `flags` unchanged when step k
+ * tests, i.e. when (k - 1) % test_interval == 0 and not (b_max > 0 and b_k >= b_max); otherwise `flags` without
+ * NT_DO_STATS, NT_PARTIAL and NT_COORD_TEST, so that normtest_step runs the mean + AdamW pass only (0 if nothing
+ * is left to do).  Invalid arguments (step < 1, test_interval < 1, b_k < 1, b_max < 0) return `flags` unchanged.
+ */
+uint32_t normtest_schedule_flags(int64_t step, int64_t test_interval, int64_t b_k, int64_t b_max,
+                                 uint32_t flags);
+
 /* Plain streaming copy of `bytes` bytes (device to device, 16-byte aligned, bytes % 16 == 0) with the
  * same load/store instructions as the step kernel: a yardstick for achievable HBM bandwidth and for
  * scaling hardware byte counters.  Enqueued on the stream. */

@@ -117,6 +117,8 @@ def lib(path: Optional[str] = None):
         L.normtest_clip_coef.restype = ctypes.c_double
         L.normtest_resplit.argtypes = [i64, i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64)]
         L.normtest_resplit.restype = ctypes.c_int
+        L.normtest_schedule_flags.argtypes = [i64, i64, i64, i64, ctypes.c_uint32]
+        L.normtest_schedule_flags.restype = ctypes.c_uint32
         L.normtest_calib_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.normtest_calib_copy.restype = ctypes.c_int
         L.normtest_strerror.argtypes = [ctypes.c_int]
@@ -368,6 +370,10 @@ def normtest_resplit(b: int, J: int, accum_base: int, micro_max: int):
     if rc != NT_OK:
         raise NormtestError(rc, "normtest_resplit")
     return micro.value, accum.value, glob.value
+
+
+def normtest_schedule_flags(step: int, test_interval: int, b_k: int, b_max: int, flags: int) -> int:
+    return int(lib().normtest_schedule_flags(step, test_interval, b_k, b_max, flags))
 
 
 def read_result(result: torch.Tensor) -> nt_result:

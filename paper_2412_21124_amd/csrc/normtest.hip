@@ -1369,6 +1369,14 @@ int normtest_resplit(int64_t b, int64_t J, int64_t accum_base, int64_t micro_max
   return NT_OK;
 }
 
+uint32_t normtest_schedule_flags(int64_t step, int64_t test_interval, int64_t b_k, int64_t b_max, uint32_t flags) {
+  if (step < 1 || test_interval < 1 || b_k < 1 || b_max < 0) return flags;
+  const bool at_maximum = b_max > 0 && b_k >= b_max;
+  const bool on_interval = (step - 1) % test_interval == 0;
+  if (on_interval && !at_maximum) return flags;
+  return flags & ~(uint32_t)(NT_DO_STATS | NT_PARTIAL | NT_COORD_TEST);
+}
+
 int normtest_combine(const nt_result* partials, int32_t n, int64_t J, const nt_hyper* hyper, nt_result* out) {
   if (!partials || !out || n < 1 || J < 2 || !hyper) return NT_ERR_BAD_ARG;
   if (!(hyper->eta > 0.0) || !std::isfinite(hyper->eta) || hyper->b_k < 1 || hyper->b_max < 0 ||

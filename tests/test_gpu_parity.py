@@ -379,6 +379,47 @@ def test_adamw_gbar_misaligned_matches_aligned():
         assert torch.equal(a, b)
 
 
+# ------------------------------------------------------------------ a short run: schedule, growth, bias corrections
+
+def test_short_run_with_test_interval_and_maximum():
+    """Ten consecutive steps as a training loop would issue them: flags from normtest_schedule_flags (interval 2,
+    maximum 512), step counter k = 1.., b_k fed back from next_b, fresh gradients each step.  Every step is compared with the oracle from the same pre-step state; the sequence of
+    batch sizes must be the oracle's."""
+    J, d, M = 4, 3 * 4096 + 100, 4
+    b_k, b_max, interval = 32, 512, 2
+    dev_state = None
+    sizes, tested = [], []
+    for k in range(1, 11):
+        # T = r^2 / (eta^2 (1 + r^2/J)) for noise-to-signal ratio r: about 100, 300, 700 on the steps that test
+        sigma = 1e-2 * {1: 0.52, 3: 0.96, 5: 1.76}.get(k, 1.0)
+        h = synth.Hyper(lr=3e-3, step=k, b_k=b_k, b_max=b_max, round_to=J * M, ddof=1, eta=0.05)
+        wl = synth.make("run", J, d, gdtype=torch.bfloat16, sigma=sigma, seed=100 + k, device=DEV, hyper=h)
+        if dev_state is None:
+            dev_state = (wl.w, wl.m, wl.v)
+        w, m, v = dev_state
+        w0, m0, v0 = w.clone(), m.clone(), v.clone()
+        flags = B.normtest_schedule_flags(k, interval, b_k, b_max, FULL)
+        due = oracle.test_due(k, interval, b_k, b_max)
+        assert bool(flags & B.NT_DO_STATS) == due
+        res = gpu_step(wl.grads, w, m, v, h, flags=flags)
+        H.oracle_adamw_check(wl.grads, d, w0, m0, v0, w, m, v, h)      # AdamW runs on every step, bias terms at k
+        if due:
+            ref = H.oracle_full(wl.grads, d, J, h)
+            H.assert_stats_close(res, ref)
+            assert not H.near_threshold(ref.dec.T, b_k), "choose another seed: T too close to b_k"
+            H.assert_decision_matches(res, ref, h)
+            assert res["next_b"] == ref.dec.next_b
+        else:
+            assert res["status"] == B.NT_STATUS_NO_STATS and res["next_b"] == b_k and res["pass"] == 1
+        tested.append(due)
+        sizes.append(res["next_b"])
+        b_k = res["next_b"]
+    assert tested[:2] == [True, False] and sizes[-1] == b_max            # grew to the maximum ...
+    first_max = sizes.index(b_max)
+    assert not any(tested[first_max + 1:])                                # ... after which no step tests
+    assert all(b >= a for a, b in zip(sizes, sizes[1:])) and all(s % (J * M) == 0 for s in sizes if s != 32)
+
+
 # ------------------------------------------------------------------ coordinate-wise form of the test
 
 @pytest.mark.parametrize("J,gdtype,d,sigma,b_k", [

@@ -25,7 +25,7 @@ def test_every_declared_symbol_is_exported():
     names = declared_functions()
     assert {"normtest_step", "normtest_combine", "normtest_workspace_bytes", "normtest_tile_coords",
             "normtest_strerror", "normtest_calib_copy", "normtest_step_clipped", "normtest_adamw_gbar",
-            "normtest_clip_coef", "normtest_step_rows", "normtest_resplit", "normtest_layer_stats"} <= set(names)
+            "normtest_clip_coef", "normtest_step_rows", "normtest_resplit", "normtest_layer_stats", "normtest_schedule_flags"} <= set(names)
     L = B.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -217,6 +217,26 @@ def test_resplit_matches_oracle():
     for bad in ((0, 4, 16, 8), (256, 0, 16, 8), (256, 4, 0, 8), (256, 4, 16, 0)):
         with pytest.raises(B.NormtestError):
             B.normtest_resplit(*bad)
+
+
+def test_schedule_flags_match_oracle():
+    """The library drops the statistics flags exactly on the steps on which the oracle says no test is due."""
+    stats_bits = B.NT_DO_STATS | B.NT_PARTIAL | B.NT_COORD_TEST
+    rng = np.random.default_rng(11)
+    for _ in range(3000):
+        step = int(rng.integers(1, 500))
+        interval = int(rng.choice([1, 1, 2, 3, 5, 16, 100]))
+        b_max = int(rng.choice([0, 256, 8192]))
+        b_k = int(rng.choice([1, 255, 256, 257, 4096, 8191, 8192, 8193]))
+        flags = int(rng.choice([FULL, B.NT_DO_STATS, FULL | B.NT_COORD_TEST, FULL | B.NT_PARTIAL | B.NT_WRITE_GBAR,
+                                B.NT_DO_ADAMW]))
+        got = B.normtest_schedule_flags(step, interval, b_k, b_max, flags)
+        want = flags if oracle.test_due(step, interval, b_k, b_max) else flags & ~stats_bits
+        assert got == want, (step, interval, b_k, b_max, flags)
+    assert B.normtest_schedule_flags(3, 2, 32, 0, B.NT_DO_STATS) == B.NT_DO_STATS      # (3 - 1) % 2 == 0: tests
+    assert B.normtest_schedule_flags(2, 2, 32, 0, B.NT_DO_STATS) == 0                   # nothing left to do
+    for bad in ((0, 1, 32, 0), (1, 0, 32, 0), (1, 1, 0, 0), (1, 1, 32, -1)):
+        assert B.normtest_schedule_flags(*bad, FULL) == FULL
 
 
 def test_clip_coef_matches_oracle():
