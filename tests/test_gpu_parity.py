@@ -667,6 +667,48 @@ def test_step_can_be_captured_in_a_hip_graph():
             _ = (torch.randn(1 << 16, device=DEV) * 2).sum().item()        # unrelated eager work between replays
 
 
+def test_clipped_step_and_layer_table_can_be_captured_together():
+    """Both phases of the clipped step and the per-layer table in one graph (five kernel launches, no memsets,
+    no allocation); replays must reproduce the eager results bit for bit."""
+    wl = synth.make("t", 8, 6 * 4096 + 55, gdtype=torch.bfloat16, seed=33, device=DEV, sigma=3e-2)
+    state0 = [t.clone() for t in (wl.w, wl.m, wl.v)]
+    hy = hyper_of(wl.hyper, FULL | B.NT_COORD_TEST)
+    ws = torch.empty(B.normtest_workspace_bytes(wl.J, wl.d), dtype=torch.uint8, device=DEV)
+    result = torch.zeros(B.RESULT_BYTES, dtype=torch.uint8, device=DEV)
+    gbar = torch.empty(wl.d, dtype=torch.float32, device=DEV)
+    off = torch.tensor([0, 5000, 5001, 20000, wl.d], dtype=torch.int64, device=DEV)
+    layers = torch.zeros(4 * B.LAYER_BYTES, dtype=torch.uint8, device=DEV)
+
+    def enqueue(stream):
+        B.normtest_step_clipped(wl.grads, wl.w, wl.m, wl.v, gbar, 0.05, hy, workspace=ws, result=result, stream=stream)
+        B.normtest_layer_stats(wl.grads, off, ws, layers=layers, stream=stream)
+
+    eager = []
+    for _ in range(2):
+        enqueue(torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        eager.append((B.read_result(result).as_dict(), layers.clone(), [t.clone() for t in (wl.w, wl.m, wl.v)]))
+    assert eager[0][0]["clip_coef"] < 1.0 and eager[0][0]["coord_fail"] > 0
+    for t, s in zip((wl.w, wl.m, wl.v), state0):
+        t.copy_(s)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        enqueue(torch.cuda.current_stream())
+    for rounds in range(2):
+        for t, s in zip((wl.w, wl.m, wl.v), state0):
+            t.copy_(s)
+        for k in range(2):
+            result.zero_()
+            layers.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert B.read_result(result).as_dict() == eager[k][0]
+            assert torch.equal(layers, eager[k][1])
+            for a, b in zip((wl.w, wl.m, wl.v), eager[k][2]):
+                assert torch.equal(a, b)
+            _ = (torch.randn(1 << 16, device=DEV) * 2).sum().item()
+
+
 def test_calib_copy():
     src = torch.randn(1 << 20, device=DEV)
     dst = torch.zeros_like(src)
