@@ -79,6 +79,12 @@ def cpu_baseline(wl, sample_coords: int):
     A, Bv, C = oracle.combine_chunks(parts)
     oracle.decide(A, Bv, C, wl.J, h.eta, h.b_k, h.b_max, h.round_to, h.ddof)
     dt = time.perf_counter() - t0
+    # the same on one core, over a sixteenth of the sample
+    n1 = max(1, n // 16)
+    t1 = time.perf_counter()
+    for r in [(lo, min(n1, lo + chunk)) for lo in range(0, n1, chunk)]:
+        work(r)
+    dt1 = time.perf_counter() - t1
     bytes_per_param = wl.J * wl.grad_bytes + 24
     return {
         "value": n * bytes_per_param / dt / 1e9,
@@ -87,6 +93,7 @@ def cpu_baseline(wl, sample_coords: int):
         "cores": min(threads, len(ranges)),
         "kind": "oracle",
         "seconds": dt,
+        "one_core_params_per_s": n1 / dt1,
         "sample": "first %d coordinates of the same workload (J=%d), statistics + decision + AdamW in fp64" % (n, wl.J),
     }
 
@@ -224,6 +231,7 @@ def main():
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "launch_ms_avg": ev_avg,
+            "launch_ms_median": sorted(ev_ms)[len(ev_ms) // 2],
             "launch_ms_min": min(ev_ms),
             "algorithmic_bytes": alg_bytes,
             "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if (args.scale == 1.0 and args.mode == "full") else None,
