@@ -3,7 +3,9 @@
 // One streaming kernel (k_step) reads the J gradient rows and w, m, v once, writes w, m, v once and
 // leaves four fp64 partial sums per fixed-size tile of coordinates (A, B, C and the count of
 // coordinates failing the coordinate-wise form of the test); k_reduce_groups / k_finalize then add the
-// tile partials in double-double arithmetic and take Alg. 1's decision on the device.  The path is
+// tile partials in double-double arithmetic and take Alg. 1's decision on the device.  The partials stay
+// in the caller's workspace behind a small record of the step, from which k_layer_stats can regroup them
+// into a per-layer table.  k_adamw_gbar is the second phase of the gradient-clipped variant.  The path is
 // bound by HBM bandwidth (about two lane-operations per byte), so there is no MFMA here: the work is
 // fully coalesced 8- and 16-byte accesses, fp32 per-coordinate arithmetic, fp64 accumulation and wave64
 // shuffle reductions.  Launch shapes (block size, sweeps per tile) differ per class of call and were
