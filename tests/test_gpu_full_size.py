@@ -127,6 +127,49 @@ def test_fsdp_shard_full():
     assert math.isnan(res["T"])
 
 
+def test_fsdp_all_eight_shards_combine_full():
+    """The whole 7e9-parameter vector as eight sequential 875e6-coordinate shard calls (fresh seed per shard, J=16
+    micro-batch gradients, partial sums + AdamW on the shard); the host combine of the eight partial results
+    against the oracle over the concatenation, and AdamW on a sampled range of every shard."""
+    import oracle
+    parts, accs = [], []
+    hyper = None
+    t0 = time.time()
+    for sid in range(8):
+        wl = synth.fsdp_shard(sid, device=DEV)
+        hyper, d = wl.hyper, wl.d
+        lo = (sid * 104_729_111) % (d - (1 << 22))                     # a 4M-coordinate window, different per shard
+        window = [(lo, lo + (1 << 22))]
+        before = [t[lo:lo + (1 << 22)].clone() for t in (wl.w, wl.m, wl.v)]
+        shard = B.nt_shard_info(sid, 8, wl.meta["shard_offset"], wl.meta["d_global"])
+        hy = B.make_hyper(lr=hyper.lr, beta1=hyper.beta1, beta2=hyper.beta2, eps=hyper.eps,
+                          weight_decay=hyper.weight_decay, eta=hyper.eta, step=hyper.step, b_k=hyper.b_k,
+                          b_max=hyper.b_max, round_to=hyper.round_to, ddof=hyper.ddof, flags=FULL | B.NT_PARTIAL)
+        res = B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hy, shard=shard)
+        torch.cuda.synchronize()
+        r = B.read_result(res)
+        assert r.status == B.NT_STATUS_PARTIAL_ONLY
+        A, Bs, C = H.oracle_stats(wl.grads, d)
+        H.assert_stats_close(r.as_dict(), H.OracleOut(A, Bs, C, None), partial=True)
+        # AdamW on the window: rebuild full-length views of the pre-step state for the helper
+        w0 = wl.w.clone(); m0 = wl.m.clone(); v0 = wl.v.clone()
+        for full, part in zip((w0, m0, v0), before):
+            full[lo:lo + (1 << 22)] = part
+        H.oracle_adamw_check(wl.grads, d, w0, m0, v0, wl.w, wl.m, wl.v, hyper, ranges=window)
+        parts.append(r)
+        accs.append((A, Bs, C))
+        print("shard %d: A=%.6g C=%.6g  (%.0f s so far)" % (sid, r.A, r.C, time.time() - t0), flush=True)
+        del wl, w0, m0, v0
+        torch.cuda.empty_cache()
+    hy = B.make_hyper(eta=hyper.eta, b_k=hyper.b_k, b_max=hyper.b_max, round_to=hyper.round_to, ddof=hyper.ddof)
+    comb = B.normtest_combine(parts, 16, hy).as_dict()
+    A, Bs, C = oracle.combine_chunks(accs)
+    ref = H.OracleOut(A, Bs, C, H.oracle_decide(A, Bs, C, 16, hyper))
+    H.assert_stats_close(comb, ref)
+    H.assert_decision_matches(comb, ref, hyper)
+    print("7e9 parameters in 8 shards: T=%.6g (oracle %.6g) next_b=%d" % (comb["T"], ref.dec.T, comb["next_b"]), flush=True)
+
+
 def test_per_sample_full():
     """b = 512 per-example gradients of a 2^24 vector with Student-t(3) noise: the row-walking kernel."""
     wl = synth.per_sample(device=DEV)
