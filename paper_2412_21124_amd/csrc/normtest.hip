@@ -105,6 +105,9 @@
 #define NT_WS_HEADER 16        // doubles in front of the tile partials: a record of the step that wrote them
 #define NT_WS_MAGIC 0x4e54574f524b5350ll
 #define NT_LAYER_THREADS 1024  // per-layer kernel: one block per layer
+#ifndef NT_TWO_PHASE_J
+#define NT_TWO_PHASE_J 96      // from this many rows on, the full step runs as statistics + gbar, then AdamW from gbar
+#endif
 
 namespace {
 
@@ -1111,13 +1114,26 @@ extern "C" {
 
 int64_t normtest_tile_coords(int64_t J) { return J >= 2 ? NT_TILE_MAX : 0; }
 
-size_t normtest_workspace_bytes(int64_t J, int64_t d) {
-  if (J < 2 || d < 0) return 0;
+// Bytes of the record, the tile partials and the group partials: what every call needs.
+static size_t partials_bytes(int64_t J, int64_t d) {
   const int64_t tc = min_tile_coords(J);
   const int64_t ntiles = (d + tc - 1) / tc;
   const int64_t n = ntiles > 0 ? ntiles : 1;
   const int64_t ngroups = ntiles > NT_DIRECT_TILES ? (ntiles + NT_GROUP_TILES - 1) / NT_GROUP_TILES : 0;
   return (size_t)(NT_WS_HEADER + n * NT_NV + ngroups * 2 * NT_NV) * sizeof(double);
+}
+
+// With many rows the few bytes written per coordinate disturb the read stream far more than their share
+// (sparse writes cost the memory system about ten times their volume), and the step is faster as two
+// passes: statistics that store only gbar, then AdamW from gbar.  The fp32 gbar buffer for that lives
+// behind the partials (plus slack to align it to 16 bytes) unless the caller asked for gbar anyway.
+static inline bool two_phase(int64_t J) { return J >= NT_TWO_PHASE_J; }
+
+size_t normtest_workspace_bytes(int64_t J, int64_t d) {
+  if (J < 2 || d < 0) return 0;
+  size_t need = partials_bytes(J, d);
+  if (two_phase(J)) need += (((size_t)d * sizeof(float) + 15u) & ~(size_t)15u) + 16;
+  return need;
 }
 
 // AdamW constants in fp64 on the host, rounded once to fp32.
@@ -1263,6 +1279,26 @@ static int enqueue_adamw_gbar(const float* gbar, int64_t d, float* w, float* m, 
   return hip_code(hipGetLastError());
 }
 
+// The step as the caller's flags describe it: one fused pass, or for many rows (two_phase) the statistics
+// pass that stores gbar followed by AdamW from gbar, which leaves the same bits in w, m, v and the result.
+static int enqueue_step_routed(const void* grads, bool table, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld,
+                               float* w, float* m, float* v, float* gbar_out, const nt_hyper* hyper, void* workspace,
+                               nt_result* result_dev, hipStream_t st) {
+  const uint32_t flags = hyper->flags;
+  const uint32_t both = NT_DO_STATS | NT_DO_ADAMW;
+  if ((flags & both) != both || !two_phase(J))
+    return enqueue_step(grads, table, gdtype, J, d, ld, w, m, v, gbar_out, flags, hyper, 0.0, workspace, result_dev, st);
+  float* gbar = gbar_out;
+  if (!(flags & NT_WRITE_GBAR)) {
+    const uintptr_t behind = (uintptr_t)workspace + partials_bytes(J, d);
+    gbar = (float*)((behind + 15u) & ~(uintptr_t)15u);
+  }
+  const int rc = enqueue_step(grads, table, gdtype, J, d, ld, nullptr, nullptr, nullptr, gbar,
+                              (flags & ~(uint32_t)NT_DO_ADAMW) | NT_WRITE_GBAR, hyper, 0.0, workspace, result_dev, st);
+  if (rc != NT_OK) return rc;
+  return enqueue_adamw_gbar(gbar, d, w, m, v, hyper, 1.0, nullptr, st);
+}
+
 int normtest_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld, float* w, float* m,
                   float* v, float* gbar_out, const nt_hyper* hyper, const nt_shard_info* shard, void* workspace,
                   size_t workspace_bytes, nt_result* result_dev, void* hip_stream) {
@@ -1270,8 +1306,8 @@ int normtest_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int6
   const int rc = check_step_args(grads, gdtype, J, d, ld, w, m, v, gbar_out, hyper->flags, hyper, shard, workspace,
                                  workspace_bytes, result_dev);
   if (rc != NT_OK) return rc;
-  return enqueue_step(grads, false, gdtype, J, d, ld, w, m, v, gbar_out, hyper->flags, hyper, 0.0, workspace,
-                      result_dev, (hipStream_t)hip_stream);
+  return enqueue_step_routed(grads, false, gdtype, J, d, ld, w, m, v, gbar_out, hyper, workspace, result_dev,
+                             (hipStream_t)hip_stream);
 }
 
 int normtest_step_rows(const void* const* grad_rows_dev, nt_dtype gdtype, int64_t J, int64_t d, float* w, float* m,
@@ -1282,8 +1318,8 @@ int normtest_step_rows(const void* const* grad_rows_dev, nt_dtype gdtype, int64_
   const int rc = check_step_args(grad_rows_dev, gdtype, J, d, d, w, m, v, gbar_out, hyper->flags, hyper, shard,
                                  workspace, workspace_bytes, result_dev);
   if (rc != NT_OK) return rc;
-  return enqueue_step(grad_rows_dev, true, gdtype, J, d, d, w, m, v, gbar_out, hyper->flags, hyper, 0.0, workspace,
-                      result_dev, (hipStream_t)hip_stream);
+  return enqueue_step_routed(grad_rows_dev, true, gdtype, J, d, d, w, m, v, gbar_out, hyper, workspace, result_dev,
+                             (hipStream_t)hip_stream);
 }
 
 int normtest_step_clipped(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld, float* w, float* m,

@@ -600,6 +600,48 @@ def test_canaries_around_every_buffer_survive(J, gdtype, flags):
         assert r.status in (0, B.NT_STATUS_NO_STATS)
 
 
+@pytest.mark.parametrize("J,gdtype", [(96, torch.bfloat16), (100, torch.float32), (257, torch.bfloat16)])
+def test_many_rows_take_two_passes_inside_the_workspace(J, gdtype):
+    """From 96 rows on the full step runs as statistics + stored gbar, then AdamW from gbar, with the gbar
+    buffer carved out of the workspace: results match the oracle, equal the explicit two-phase call bit for
+    bit, and nothing outside the declared workspace size is touched, whatever the workspace's alignment."""
+    d = 3 * 2048 + 777
+    guard = 64
+    for shift in (0, 8):                                   # workspace base 16-byte aligned, or only 8-byte aligned
+        wl = synth.make("t", J, d, gdtype=gdtype, sigma=1e-2, seed=40 + J, device=DEV,
+                        hyper=synth.Hyper(b_k=64, round_to=1, step=5))
+        w0, m0, v0 = wl.w.clone(), wl.m.clone(), wl.v.clone()
+        need = B.normtest_workspace_bytes(J, d)
+        assert need >= 4 * d                                # room for gbar
+        raw = torch.full((guard * 8 + shift + need + guard * 8,), 0x5A, dtype=torch.uint8, device=DEV)
+        lo = guard * 8 + shift
+        assert (raw.data_ptr() + lo) % 16 == shift
+        res = B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hyper_of(wl.hyper, FULL | B.NT_COORD_TEST),
+                              workspace=raw[lo:lo + need])
+        torch.cuda.synchronize()
+        assert bool((raw[:lo] == 0x5A).all()) and bool((raw[lo + need:] == 0x5A).all())
+        got = B.read_result(res).as_dict()
+        ref = H.oracle_full(wl.grads, d, J, wl.hyper)
+        H.assert_stats_close(got, ref)
+        H.assert_decision_matches(got, ref, wl.hyper)
+        H.oracle_adamw_check(wl.grads, d, w0, m0, v0, wl.w, wl.m, wl.v, wl.hyper)
+        H.assert_coord_count(got["coord_fail"], H.oracle_coord_counts(wl.grads, d, wl.hyper))
+        # the explicit two-phase entry point without a bound leaves the same bits
+        w2, m2, v2 = w0.clone(), m0.clone(), v0.clone()
+        gbar = torch.empty(d, dtype=torch.float32, device=DEV)
+        res2 = B.normtest_step_clipped(wl.grads, w2, m2, v2, gbar, 0.0, hyper_of(wl.hyper, FULL | B.NT_COORD_TEST))
+        torch.cuda.synchronize()
+        assert B.read_result(res2).as_dict() == got
+        for a, b in zip((wl.w, wl.m, wl.v), (w2, m2, v2)):
+            assert torch.equal(a, b)
+        # and the per-layer table still finds its partials in front of the gbar buffer
+        off = torch.tensor([0, 1000, d], dtype=torch.int64, device=DEV)
+        lay = B.normtest_layer_stats(wl.grads, off, raw[lo:lo + need])
+        torch.cuda.synchronize()
+        layers = B.read_layers(lay)
+        assert layers[0].status == 0 and layers[0].A + layers[1].A == pytest.approx(got["A"], rel=1e-7)
+
+
 def test_result_in_pinned_host_memory_and_two_streams():
     """The result struct may live in pinned host memory, and calls on different streams with their own
     buffers do not interfere (the library keeps no state)."""

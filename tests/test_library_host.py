@@ -84,12 +84,14 @@ def test_workspace_and_tiles():
         prev = 0
         for d in (0, 1, tc, tc + 1, 5000 * tc, 1_500_000_000):
             need = B.normtest_workspace_bytes(J, d)
+            if J >= 96:          # many rows: room for an fp32 gbar behind the partials (two-pass route)
+                need -= (4 * d + 15) // 16 * 16 + 16
             # a 128-byte record, four doubles per tile (tiles are at most tc and at least 1024 coordinates), and
             # a small second level
             lo = 128 + 32 * max(1, -(-d // tc))
             hi = 128 + 32 * max(1, -(-d // 1024))
             assert lo <= need <= hi + hi // 256 + 64
-            assert need >= prev and need % 8 == 0
+            assert need >= prev and need % 8 == 0 and B.normtest_workspace_bytes(J, d) % 8 == 0
             prev = need
     assert B.normtest_tile_coords(1) == 0
     assert B.normtest_workspace_bytes(1, 10) == 0 and B.normtest_workspace_bytes(4, -1) == 0
