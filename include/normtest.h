@@ -116,9 +116,9 @@ typedef struct {
 int64_t normtest_tile_coords(int64_t J);
 
 /* Bytes of device workspace normtest_step needs for J rows of d coordinates (0 if J or d is invalid): a few
- * doubles per tile, and from 96 rows on also 4 d bytes, because the full step then runs as two passes
- * (statistics that store gbar, then AdamW from gbar: faster there, same bits) and keeps gbar in the workspace
- * unless NT_WRITE_GBAR names a buffer for it. */
+ * doubles per tile, and from 48 rows on also 4 d bytes, because with 192 or more gradient bytes per coordinate
+ * (96 bf16 or 48 fp32 rows) the full step runs as two passes (statistics that store gbar, then AdamW from
+ * gbar: faster there, same bits) and keeps gbar in the workspace unless NT_WRITE_GBAR names a buffer for it. */
 size_t normtest_workspace_bytes(int64_t J, int64_t d);
 
 /*

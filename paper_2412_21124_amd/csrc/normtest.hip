@@ -105,9 +105,9 @@
 #define NT_WS_HEADER 16        // doubles in front of the tile partials: a record of the step that wrote them
 #define NT_WS_MAGIC 0x4e54574f524b5350ll
 #define NT_LAYER_THREADS 1024  // per-layer kernel: one block per layer
-#ifndef NT_TWO_PHASE_J
-#define NT_TWO_PHASE_J 96      // from this many rows on, the full step runs as statistics + gbar, then AdamW from gbar
-#endif
+#ifndef NT_TWO_PHASE_ROW_BYTES
+#define NT_TWO_PHASE_ROW_BYTES 192  // from this many gradient bytes per coordinate on (96 bf16 or 48 fp32 rows) the
+#endif                              // full step runs as statistics + gbar, then AdamW from gbar
 
 namespace {
 
@@ -1127,12 +1127,12 @@ static size_t partials_bytes(int64_t J, int64_t d) {
 // (sparse writes cost the memory system about ten times their volume), and the step is faster as two
 // passes: statistics that store only gbar, then AdamW from gbar.  The fp32 gbar buffer for that lives
 // behind the partials (plus slack to align it to 16 bytes) unless the caller asked for gbar anyway.
-static inline bool two_phase(int64_t J) { return J >= NT_TWO_PHASE_J; }
+static inline bool two_phase(int64_t J, int esize) { return J * esize >= NT_TWO_PHASE_ROW_BYTES; }
 
 size_t normtest_workspace_bytes(int64_t J, int64_t d) {
   if (J < 2 || d < 0) return 0;
   size_t need = partials_bytes(J, d);
-  if (two_phase(J)) need += (((size_t)d * sizeof(float) + 15u) & ~(size_t)15u) + 16;
+  if (two_phase(J, 4)) need += (((size_t)d * sizeof(float) + 15u) & ~(size_t)15u) + 16;  // dtype unknown here
   return need;
 }
 
@@ -1286,7 +1286,7 @@ static int enqueue_step_routed(const void* grads, bool table, nt_dtype gdtype, i
                                nt_result* result_dev, hipStream_t st) {
   const uint32_t flags = hyper->flags;
   const uint32_t both = NT_DO_STATS | NT_DO_ADAMW;
-  if ((flags & both) != both || !two_phase(J))
+  if ((flags & both) != both || !two_phase(J, gdtype == NT_F32 ? 4 : 2))
     return enqueue_step(grads, table, gdtype, J, d, ld, w, m, v, gbar_out, flags, hyper, 0.0, workspace, result_dev, st);
   float* gbar = gbar_out;
   if (!(flags & NT_WRITE_GBAR)) {

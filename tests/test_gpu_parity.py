@@ -600,9 +600,10 @@ def test_canaries_around_every_buffer_survive(J, gdtype, flags):
         assert r.status in (0, B.NT_STATUS_NO_STATS)
 
 
-@pytest.mark.parametrize("J,gdtype", [(96, torch.bfloat16), (100, torch.float32), (257, torch.bfloat16)])
+@pytest.mark.parametrize("J,gdtype", [(96, torch.bfloat16), (48, torch.float32), (100, torch.float32),
+                                      (257, torch.bfloat16)])
 def test_many_rows_take_two_passes_inside_the_workspace(J, gdtype):
-    """From 96 rows on the full step runs as statistics + stored gbar, then AdamW from gbar, with the gbar
+    """From 96 bf16 or 48 fp32 rows on the full step runs as statistics + stored gbar, then AdamW from gbar, with the gbar
     buffer carved out of the workspace: results match the oracle, equal the explicit two-phase call bit for
     bit, and nothing outside the declared workspace size is touched, whatever the workspace's alignment."""
     d = 3 * 2048 + 777

@@ -78,13 +78,13 @@ def test_plain_c_client_sees_the_layout_the_binding_assumes(tmp_path):
 
 
 def test_workspace_and_tiles():
-    for J in (2, 8, 16, 17, 512):
+    for J in (2, 8, 16, 17, 47, 48, 512):
         tc = B.normtest_tile_coords(J)
         assert tc == 16384
         prev = 0
         for d in (0, 1, tc, tc + 1, 5000 * tc, 1_500_000_000):
             need = B.normtest_workspace_bytes(J, d)
-            if J >= 96:          # many rows: room for an fp32 gbar behind the partials (two-pass route)
+            if J >= 48:          # many rows: room for an fp32 gbar behind the partials (two-pass route)
                 need -= (4 * d + 15) // 16 * 16 + 16
             # a 128-byte record, four doubles per tile (tiles are at most tc and at least 1024 coordinates), and
             # a small second level
