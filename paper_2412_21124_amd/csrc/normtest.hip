@@ -248,22 +248,22 @@ __device__ inline void tile_reduce(double a, double b, double c, double n, doubl
 __device__ inline int coord_fails(float thr, float c, float gb) { return (thr >= 0.f && c > thr * (gb * gb)) ? 1 : 0; }
 
 // Per-chunk bookkeeping of the J > 16 walk, shared by the fast and the guarded path so that both
-// perform the same operations.  For one coordinate and a chunk of nb rows shifted by K (the running
-// mean before the chunk, or the first row for the first chunk), sr = sum (x - K) in fp64 and
-// q = sum (x - K)^2 in fp32 have been accumulated.  Then
+// perform the same operations.  For one coordinate and a chunk of nb rows with shift K (the running
+// mean before the chunk, or the first row for the first chunk) two sums have been accumulated:
+// sb = sum x in fp64 (exact for all practical purposes, so the mean handed to AdamW is correctly rounded
+// even when the rows cancel) and q = sum (x - K)^2 in fp32.  With sr = sb - nb K, the sum of the shifted values,
 //   chunk centred sum   M2_b = q - sr^2/nb
 //   chunk sum of squares  a_b = q + K (2 sr + nb K)
-//   chunk sum             s_b = nb K + sr
-// and the chunk is merged into the running (S, M2) with  M2 += M2_b + delta^2 na nb/(na + nb),
+// and the chunk is merged into the running (S, M2) with  S += sb,  M2 += M2_b + delta^2 na nb/(na + nb),
 // delta = mean_b - mean_a.  Returns the shift for the next chunk.
-__device__ inline float chunk_merge(bool first, int na, int nb, float K, double sr, float q, double& S, float& M2,
+__device__ inline float chunk_merge(bool first, int na, int nb, float K, double sb, float q, double& S, float& M2,
                                     float& a) {
+  const double sr = __builtin_fma(-(double)K, (double)nb, sb);
   const float srf = (float)sr;
   const float nbf = (float)nb;
   const double inv_nb = 1.0 / (double)nb;
   const float M2b = __builtin_fmaf(-(srf * (float)inv_nb), srf, q);
   a += __builtin_fmaf(K, __builtin_fmaf(nbf, K, 2.0f * srf), q);
-  const double sb = __builtin_fma((double)K, (double)nb, sr);
   if (first) {
     S = sb;
     M2 = M2b;
@@ -306,14 +306,15 @@ __device__ inline void coord_stats_generic(const StepParams& p, int64_t i, doubl
   int na = 0;
   for (int j0 = 0; j0 < J; j0 += NT_MCHUNK) {
     const int nb = (J - j0 < NT_MCHUNK) ? (J - j0) : NT_MCHUNK;
-    double sr = 0.0;
+    double sb = 0.0;
     float q = 0.f;
     for (int j = 0; j < nb; ++j) {
-      const float r = GT::ld(row_base<GT, TABLE>(p, j0 + j), i) - K;
-      sr += (double)r;
+      const float x = GT::ld(row_base<GT, TABLE>(p, j0 + j), i);
+      const float r = x - K;
+      sb += (double)x;
       q = __builtin_fmaf(r, r, q);
     }
-    K = chunk_merge(na == 0, na, nb, K, sr, q, S, M2, a);
+    K = chunk_merge(na == 0, na, nb, K, sb, q, S, M2, a);
     na += nb;
   }
 }
@@ -496,16 +497,16 @@ __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fast tile, J > 16: rows are walked NT_MCHUNK at a time.  Inside a chunk every value is shifted by
-// K, the running mean of the rows before it, so one pass over the chunk gives both its sum and its
-// centred sum of squares without cancellation; see chunk_merge for the bookkeeping.
+// Fast tile, J > 16: rows are walked NT_MCHUNK at a time.  One pass over a chunk gives its plain sum
+// (fp64) and the sum of squares of the values shifted by K, the running mean of the rows before it, hence
+// its centred sum of squares without cancellation; see chunk_merge for the bookkeeping.
 // ---------------------------------------------------------------------------------------------
 template <class GT, bool RT>
-__device__ inline void chunk_accumulate(const typename GT::raw_t* raw, int nb, const float* K, double* sr, float* q) {
+__device__ inline void chunk_accumulate(const typename GT::raw_t* raw, int nb, const float* K, double* sb, float* q) {
   constexpr int VEC = GT::VEC;
 #pragma unroll
   for (int e = 0; e < VEC; ++e) {
-    sr[e] = 0.0;
+    sb[e] = 0.0;
     q[e] = 0.f;
   }
 #pragma unroll
@@ -513,8 +514,9 @@ __device__ inline void chunk_accumulate(const typename GT::raw_t* raw, int nb, c
     if (!RT || j < nb) {
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
-        const float r = GT::val(raw[j], e) - K[e];
-        sr[e] += (double)r;
+        const float x = GT::val(raw[j], e);
+        const float r = x - K[e];
+        sb[e] += (double)x;
         q[e] = __builtin_fmaf(r, r, q[e]);
       }
     }
@@ -531,7 +533,7 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
   for (int it = 0; it < ITERS; ++it) {
     const int64_t i0 = tile * TILE + ((int64_t)it * BLOCK + threadIdx.x) * VEC;
     const int64_t goff = i0 * GT::ESIZE;
-    double S[VEC], sr[VEC];
+    double S[VEC], sb[VEC];
     float M2[VEC], a[VEC], K[VEC], q[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) a[e] = 0.f;
@@ -541,26 +543,26 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
     for (int j = 0; j < NT_MCHUNK; ++j) raw[j] = GT::ldraw(row_base<GT, TABLE>(p, j) + goff);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) K[e] = GT::val(raw[0], e);
-    chunk_accumulate<GT, false>(raw, NT_MCHUNK, K, sr, q);
+    chunk_accumulate<GT, false>(raw, NT_MCHUNK, K, sb, q);
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) K[e] = chunk_merge(true, 0, NT_MCHUNK, K[e], sr[e], q[e], S[e], M2[e], a[e]);
+    for (int e = 0; e < VEC; ++e) K[e] = chunk_merge(true, 0, NT_MCHUNK, K[e], sb[e], q[e], S[e], M2[e], a[e]);
     int j0 = NT_MCHUNK;
 #pragma unroll 1
     for (; j0 + NT_MCHUNK <= J; j0 += NT_MCHUNK) {
 #pragma unroll
       for (int j = 0; j < NT_MCHUNK; ++j) raw[j] = GT::ldraw(row_base<GT, TABLE>(p, j0 + j) + goff);
-      chunk_accumulate<GT, false>(raw, NT_MCHUNK, K, sr, q);
+      chunk_accumulate<GT, false>(raw, NT_MCHUNK, K, sb, q);
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) K[e] = chunk_merge(false, j0, NT_MCHUNK, K[e], sr[e], q[e], S[e], M2[e], a[e]);
+      for (int e = 0; e < VEC; ++e) K[e] = chunk_merge(false, j0, NT_MCHUNK, K[e], sb[e], q[e], S[e], M2[e], a[e]);
     }
     if (j0 < J) {
       const int nb = J - j0;
 #pragma unroll
       for (int j = 0; j < NT_MCHUNK; ++j)
         if (j < nb) raw[j] = GT::ldraw(row_base<GT, TABLE>(p, j0 + j) + goff);
-      chunk_accumulate<GT, true>(raw, nb, K, sr, q);
+      chunk_accumulate<GT, true>(raw, nb, K, sb, q);
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) K[e] = chunk_merge(false, j0, nb, K[e], sr[e], q[e], S[e], M2[e], a[e]);
+      for (int e = 0; e < VEC; ++e) K[e] = chunk_merge(false, j0, nb, K[e], sb[e], q[e], S[e], M2[e], a[e]);
     }
     float gb[VEC];
 #pragma unroll

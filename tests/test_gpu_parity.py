@@ -567,6 +567,34 @@ def test_random_configurations_against_oracle():
         assert bool((big[:, :off] == 3.0).all()) and bool((big[:, off + d:] == 3.0).all()), ctx
 
 
+def test_noisy_gradients_and_tiny_second_moments_stay_within_the_adamw_bound():
+    """Noise far above the state's scale with a small epsilon makes w sensitive to the relative error of gbar
+    wherever gbar and v are both small.  300 seeded draws over every row-count path; the row sums must be
+    exact enough (fp64 sums of the unshifted values, also for more than 16 rows) for all of them."""
+    rng = np.random.default_rng(7)
+    for case in range(300):
+        J = int(rng.choice([2, 3, 4, 7, 8, 16, 17, 20, 24, 31, 32, 33, 40, 64, 70, 95, 96, 128, 200]))
+        d = int(rng.choice([20000, 40001, 100000]))
+        gdtype = torch.bfloat16 if rng.random() < 0.6 else torch.float32
+        h = synth.Hyper(lr=float(rng.choice([1e-3, 4e-4, 1e-2])), beta1=float(rng.choice([0.9, 0.0, 0.5])),
+                        beta2=float(rng.choice([0.95, 0.999])), eps=float(rng.choice([1e-8, 1e-12])),
+                        weight_decay=float(rng.choice([0.1, 0.0])), eta=0.1, step=int(rng.choice([1, 2, 10, 1000])),
+                        b_k=32, b_max=0, round_to=1, ddof=1)
+        sigma = float(rng.choice([1e-3, 1e-2, 1e-1, 1.0]))
+        mu = str(rng.choice(["normal", "sign"]))
+        if sigma < 0.1 and case % 4:          # keep the run short: the quiet draws are covered elsewhere
+            continue
+        wl = synth.make("r", J, d, gdtype=gdtype, sigma=sigma, mu=mu, seed=5000 + case, device=DEV, hyper=h)
+        w0, m0, v0 = wl.w.clone(), wl.m.clone(), wl.v.clone()
+        res = gpu_step(wl.grads, wl.w, wl.m, wl.v, h)
+        try:
+            H.assert_stats_close(res, H.oracle_full(wl.grads, d, J, h))
+            H.oracle_adamw_check(wl.grads, d, w0, m0, v0, wl.w, wl.m, wl.v, h)
+        except AssertionError as e:
+            raise AssertionError("case %d: J=%d %s sigma=%g mu=%s lr=%g step=%d eps=%g: %s" % (
+                case, J, gdtype, sigma, mu, h.lr, h.step, h.eps, e))
+
+
 # ------------------------------------------------------------------ memory safety and graph capture
 
 @pytest.mark.parametrize("J,gdtype,flags", [(8, torch.bfloat16, FULL), (4, torch.float32, FULL),
