@@ -13,6 +13,11 @@
  *     pass = !(T > b_k), next_b by Alg. 1's rounding chain     (Alg. 1, If-branch)
  *     AdamW on gbar, in place on w, m, v                       (Alg. 1, last five update lines)
  *
+ * Dynamic range: squares are formed in fp32, so |g| beyond ~1.8e19 overflows (reported as NT_STATUS_NONFINITE)
+ * and sums of squares lose precision for |g| below ~1e-19; where (1 - beta2) gbar^2 falls below fp32's normal
+ * range (|gbar| below ~1e-18) the stored second moment keeps few or no significant bits, as in any AdamW with
+ * fp32 state.  Between those limits results are scale-invariant to the stated tolerances.
+ *
  * All pointers named "device" must be dereferenceable by the GPU (device memory; result may also be
  * pinned host memory).  The library allocates nothing, keeps no state between calls, never
  * synchronises the device and never touches host copies of the data: it validates, enqueues kernels

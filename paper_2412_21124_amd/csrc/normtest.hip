@@ -188,11 +188,15 @@ __device__ inline void st16(void* p, f32x4 x) {
 
 // AdamW on one coordinate (Alg. 1): moments, bias corrections folded into step_size and
 // inv_sqrt_bc2, decoupled decay.  sqrt and reciprocal are the 1-ulp hardware forms: the term they
-// feed is scaled by lr before it meets w.
+// feed is scaled by lr before it meets w.  The hardware square root flushes subnormal arguments to
+// zero, so a second moment below 2^-96 is scaled by 2^64 first (same bits for every normal v).
 __device__ inline void adamw_coord(const StepParams& p, float g, float& w, float& m, float& v) {
   m = __builtin_fmaf(p.beta1, m, p.omb1 * g);
   v = __builtin_fmaf(p.beta2, v, (p.omb2 * g) * g);
-  float denom = __builtin_fmaf(__builtin_amdgcn_sqrtf(v), p.inv_sqrt_bc2, p.eps);
+  const bool tiny = v < 0x1p-96f;
+  float root = __builtin_amdgcn_sqrtf(tiny ? v * 0x1p+64f : v);
+  root = tiny ? root * 0x1p-32f : root;
+  float denom = __builtin_fmaf(root, p.inv_sqrt_bc2, p.eps);
   float upd = (p.step_size * m) * __builtin_amdgcn_rcpf(denom);
   w = __builtin_fmaf(p.decay, w, -upd);
 }

@@ -595,6 +595,30 @@ def test_noisy_gradients_and_tiny_second_moments_stay_within_the_adamw_bound():
                 case, J, gdtype, sigma, mu, h.lr, h.step, h.eps, e))
 
 
+@pytest.mark.parametrize("J", [8, 33])
+def test_subnormal_second_moment_keeps_the_sign_step(J):
+    """Gradients around 1e-19 put (1 - beta2) gbar^2 into fp32's subnormal range.  From zero moments at k = 1 the
+    update is lr * gbar / (|gbar| + eps), a sign step for eps far below |gbar| (closed form).  The stored v has
+    few significant bits there, so only 1e-3 of the step is asked for; a square root that flushes subnormals
+    would instead divide by eps alone and throw w off by many orders of magnitude."""
+    d = 20000
+    h = synth.Hyper(lr=1e-2, beta1=0.9, beta2=0.95, eps=1e-30, weight_decay=0.0, step=1, b_k=32)
+    wl = synth.make("t", J, d, gdtype=torch.float32, sigma=1e-3, mu="sign", seed=77, device=DEV, hyper=h)
+    g = wl.grads * 3e-17                                  # |gbar| about 3e-19: gbar^2 * 0.05 about 5e-39
+    wl.m.zero_()
+    wl.v.zero_()
+    w0 = wl.w.clone()
+    res = gpu_step(g, wl.w, wl.m, wl.v, h)
+    assert res["status"] == 0
+    gbar = g.double().mean(dim=0)
+    v_expect = 0.05 * gbar * gbar
+    assert float(v_expect.max()) < 1.2e-38 and float(v_expect.min()) > 1e-42      # all subnormal, none flushed
+    expect = w0.double() - h.lr * torch.sign(gbar)
+    assert bool(torch.isfinite(wl.w).all())
+    assert float((wl.w.double() - expect).abs().max()) <= 1e-3 * h.lr
+    assert float((wl.v.double() - v_expect).abs().max()) <= 1.5e-45              # within one subnormal step
+
+
 # ------------------------------------------------------------------ memory safety and graph capture
 
 @pytest.mark.parametrize("J,gdtype,flags", [(8, torch.bfloat16, FULL), (4, torch.float32, FULL),
