@@ -25,7 +25,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # copy-kernel calibration; None until measured for that workload.
 MEASURED_TRAFFIC_BYTES = {
     # profiles/k_step_flat_1p5b.md: FETCH_SIZE x 2.0000 + WRITE_SIZE x 1.0000 per k_step launch
-    "flat_1p5b": 6.0010e10,
+    ("flat_1p5b", "full"): 6.0010e10,
+    # profiles/k_step_other_workloads.md, clipped mode: k_step (statistics + gbar) + k_adamw_gbar
+    ("flat_1p5b", "clipped"): 7.201e10,
 }
 
 
@@ -238,7 +240,7 @@ def main():
             "launch_ms_median": sorted(ev_ms)[len(ev_ms) // 2],
             "launch_ms_min": min(ev_ms),
             "algorithmic_bytes": alg_bytes,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if (args.scale == 1.0 and args.mode == "full") else None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, args.mode)) if (args.scale == 1.0 and not args.layers) else None,
         },
     }
     if not args.no_cpu_baseline and args.mode == "full":
