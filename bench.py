@@ -112,6 +112,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0,
                     help="also produce the per-layer table each step: -1 = the workload's own parameter blocks, "
                          "N > 0 = N layers of uneven, unaligned sizes")
+    ap.add_argument("--one-pass", action="store_true",
+                    help="keep the fused single pass where the library would take its two-pass route (many rows)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 29)
     ap.add_argument("--calib-copy-gib", type=int, default=0,
@@ -133,6 +135,8 @@ def main():
              "clipped": B.NT_DO_STATS | B.NT_DO_ADAMW}[args.mode]
     if args.workload == "fsdp_shard" and args.mode in ("full", "stats"):
         flags |= B.NT_PARTIAL
+    if args.one_pass:
+        flags |= B.NT_ONE_PASS
     # bytes per coordinate: J gradient reads; + read/write of w, m, v; the clipped variant also writes and re-reads gbar
     bytes_per_param = wl.J * wl.grad_bytes + {"full": 24, "stats": 0, "adamw": 24, "clipped": 32}[args.mode]
     gbar_buf = torch.empty(wl.d, dtype=torch.float32, device=dev) if args.mode == "clipped" else None
@@ -194,7 +198,8 @@ def main():
     res = B.read_result(result).as_dict()
 
     # from 96 rows on the library runs the full step as two passes and asks for room for gbar in the workspace
-    two_pass = args.mode == "full" and B.normtest_workspace_bytes(wl.J, wl.d) >= 4 * wl.d > 0
+    two_pass = (args.mode == "full" and not args.one_pass and wl.J * wl.grad_bytes >= 192
+                and B.normtest_workspace_bytes(wl.J, wl.d) >= 4 * wl.d > 0)
     alg_bytes = wl.d * bytes_per_param
     ms_per_step = wall * 1e3 / args.steps
     ev_avg = sum(ev_ms) / len(ev_ms)

@@ -15,7 +15,7 @@ import torch
 from . import build as _build
 
 NT_F32, NT_BF16 = 0, 1
-NT_DO_STATS, NT_DO_ADAMW, NT_PARTIAL, NT_WRITE_GBAR, NT_COORD_TEST = 1, 2, 4, 8, 16
+NT_DO_STATS, NT_DO_ADAMW, NT_PARTIAL, NT_WRITE_GBAR, NT_COORD_TEST, NT_ONE_PASS = 1, 2, 4, 8, 16, 32
 NT_STATUS_NONFINITE = 1
 NT_STATUS_ZERO_GRAD_NORM = 2
 NT_STATUS_CLAMPED = 4

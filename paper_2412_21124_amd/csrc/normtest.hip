@@ -1052,7 +1052,7 @@ inline int64_t min_tile_coords(int64_t J) {
 
 bool hyper_ok(const nt_hyper* h, int64_t J) {
   if (!h) return false;
-  const uint32_t known = NT_DO_STATS | NT_DO_ADAMW | NT_PARTIAL | NT_WRITE_GBAR | NT_COORD_TEST;
+  const uint32_t known = NT_DO_STATS | NT_DO_ADAMW | NT_PARTIAL | NT_WRITE_GBAR | NT_COORD_TEST | NT_ONE_PASS;
   if (h->flags & ~known) return false;
   if (!(h->flags & (NT_DO_STATS | NT_DO_ADAMW))) return false;
   if ((h->flags & (NT_PARTIAL | NT_COORD_TEST)) && !(h->flags & NT_DO_STATS)) return false;
@@ -1292,7 +1292,7 @@ static int enqueue_step_routed(const void* grads, bool table, nt_dtype gdtype, i
                                nt_result* result_dev, hipStream_t st) {
   const uint32_t flags = hyper->flags;
   const uint32_t both = NT_DO_STATS | NT_DO_ADAMW;
-  if ((flags & both) != both || !two_phase(J, gdtype == NT_F32 ? 4 : 2))
+  if ((flags & both) != both || (flags & NT_ONE_PASS) || !two_phase(J, gdtype == NT_F32 ? 4 : 2))
     return enqueue_step(grads, table, gdtype, J, d, ld, w, m, v, gbar_out, flags, hyper, 0.0, workspace, result_dev, st);
   float* gbar = gbar_out;
   if (!(flags & NT_WRITE_GBAR)) {

@@ -27,8 +27,9 @@ int main(void) {
   FIELD(nt_layer_stats, var_l1); FIELD(nt_layer_stats, T); FIELD(nt_layer_stats, n);
   FIELD(nt_layer_stats, coord_fail); FIELD(nt_layer_stats, pass); FIELD(nt_layer_stats, status);
   printf("enum NT_F32 %d\nenum NT_BF16 %d\n", (int)NT_F32, (int)NT_BF16);
-  printf("enum NT_DO_STATS %u\nenum NT_DO_ADAMW %u\nenum NT_PARTIAL %u\nenum NT_WRITE_GBAR %u\nenum NT_COORD_TEST %u\n",
-         NT_DO_STATS, NT_DO_ADAMW, NT_PARTIAL, NT_WRITE_GBAR, NT_COORD_TEST);
+  printf("enum NT_DO_STATS %u\nenum NT_DO_ADAMW %u\nenum NT_PARTIAL %u\nenum NT_WRITE_GBAR %u\nenum NT_COORD_TEST %u\n"
+         "enum NT_ONE_PASS %u\n",
+         NT_DO_STATS, NT_DO_ADAMW, NT_PARTIAL, NT_WRITE_GBAR, NT_COORD_TEST, NT_ONE_PASS);
   printf("enum NT_STATUS_NONFINITE %u\nenum NT_STATUS_ZERO_GRAD_NORM %u\nenum NT_STATUS_CLAMPED %u\n"
          "enum NT_STATUS_PARTIAL_ONLY %u\nenum NT_STATUS_T_SATURATED %u\nenum NT_STATUS_NO_STATS %u\n"
          "enum NT_STATUS_BAD_RANGE %u\n",

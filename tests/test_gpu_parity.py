@@ -679,6 +679,13 @@ def test_many_rows_take_two_passes_inside_the_workspace(J, gdtype):
         H.assert_decision_matches(got, ref, wl.hyper)
         H.oracle_adamw_check(wl.grads, d, w0, m0, v0, wl.w, wl.m, wl.v, wl.hyper)
         H.assert_coord_count(got["coord_fail"], H.oracle_coord_counts(wl.grads, d, wl.hyper))
+        # the fused single pass, forced, leaves the same bits in the state and the same result
+        w1, m1, v1 = w0.clone(), m0.clone(), v0.clone()
+        res1 = B.normtest_step(wl.grads, w1, m1, v1, hyper_of(wl.hyper, FULL | B.NT_COORD_TEST | B.NT_ONE_PASS))
+        torch.cuda.synchronize()
+        assert B.read_result(res1).as_dict() == got
+        for a, b in zip((wl.w, wl.m, wl.v), (w1, m1, v1)):
+            assert torch.equal(a, b)
         # the explicit two-phase entry point without a bound leaves the same bits
         w2, m2, v2 = w0.clone(), m0.clone(), v0.clone()
         gbar = torch.empty(d, dtype=torch.float32, device=DEV)

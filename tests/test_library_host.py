@@ -68,7 +68,7 @@ def test_plain_c_client_sees_the_layout_the_binding_assumes(tmp_path):
             n_enum += 1
     for k, cls in mirrors.items():
         assert seen[k] == len(cls._fields_), k          # every field of the mirror exists in the header and back
-    assert n_enum == 19
+    assert n_enum == 20
     lines = {l.split()[0]: l.split()[1:] for l in out if l.split()[0] in ("combine", "resplit", "clip", "workspace", "tile", "strerror")}
     A, Bv, C, T, passed, next_b = lines["combine"]
     assert (float(A), float(Bv), float(C), float(T), int(passed), int(next_b)) == (50.0, 80.0, 10.0, 2.0, 0, 2)
