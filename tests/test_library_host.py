@@ -347,3 +347,45 @@ def test_combine_rejects_bad_input():
     with pytest.raises(B.NormtestError):
         B.normtest_combine([_part(1, 1, 1)], 4, B.make_hyper(eta=0.0, b_k=32))
     assert B.lib().normtest_combine(None, 1, 4, ctypes.byref(hy), ctypes.byref(B.nt_result())) == B.NT_ERR_BAD_ARG
+
+
+def _decide_both(A, Bv, C, J, eta, b_k, b_max, round_to, ddof):
+    """(T, pass, next_b, status) from the oracle and from the library's host-side decision."""
+    o = oracle.decide(A, Bv, C, J, eta, b_k, b_max, round_to, ddof)
+    hy = B.make_hyper(eta=eta, b_k=b_k, b_max=b_max, round_to=round_to, ddof=ddof)
+    g = B.normtest_combine([_part(A, Bv, C)], J, hy)
+    return (o.T, o.passed, o.next_b, o.status), (g.T, bool(g.pass_), g.next_b, g.status)
+
+
+def test_decision_invariants_hold_for_arbitrary_sums():
+    """Alg. 1's If-branch as properties, for the oracle and for the library, over arbitrary positive sums:
+    never shrink; grow exactly when T > b_k; the new size is the least multiple of round_to at or above ceil(T)
+    (then cut to the cap, then raised back to b_k); scaling all gradients by a power of two changes nothing."""
+    from hypothesis import given, settings, strategies as st
+
+    pos = st.floats(min_value=1e-30, max_value=1e30, allow_nan=False, allow_infinity=False)
+
+    @settings(max_examples=600, deadline=None)
+    @given(Bv=pos, C=pos, J=st.integers(2, 5000), eta=st.floats(min_value=1e-3, max_value=10.0),
+           b_k=st.integers(1, 1 << 20), b_max=st.sampled_from([0, 1, 512, 8192, 1 << 30]),
+           round_to=st.sampled_from([1, 2, 3, 64, 128, 1000]), ddof=st.integers(0, 1), shift=st.integers(-20, 20))
+    def check(Bv, C, J, eta, b_k, b_max, round_to, ddof, shift):
+        A = C + Bv / J
+        for T, passed, next_b, status in _decide_both(A, Bv, C, J, eta, b_k, b_max, round_to, ddof):
+            assert next_b >= b_k
+            assert passed == (not T > b_k)
+            if passed:
+                assert next_b == b_k and not status & B.NT_STATUS_CLAMPED
+            elif status & B.NT_STATUS_T_SATURATED:
+                assert next_b == max(b_k, b_max)
+            else:
+                want = -(-math.ceil(T) // round_to) * round_to
+                if b_max > 0 and want > b_max:
+                    assert status & B.NT_STATUS_CLAMPED and next_b == max(b_max, b_k)
+                else:
+                    assert not status & B.NT_STATUS_CLAMPED and next_b == max(want, b_k)
+        c = 2.0 ** (2 * shift)                     # gradients scaled by 2^shift: every sum by 4^shift, exactly
+        a, b_ = _decide_both(A, Bv, C, J, eta, b_k, b_max, round_to, ddof), _decide_both(A * c, Bv * c, C * c, J, eta, b_k, b_max, round_to, ddof)
+        assert a == b_
+
+    check()
