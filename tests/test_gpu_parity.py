@@ -619,6 +619,26 @@ def test_subnormal_second_moment_keeps_the_sign_step(J):
     assert float((wl.v.double() - v_expect).abs().max()) <= 1.5e-45              # within one subnormal step
 
 
+def test_maximum_row_count():
+    """J = 2^20 rows (the largest the entry points accept) of a 9-coordinate vector: 65536 chunks per coordinate."""
+    J, d = 1 << 20, 9
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(5)
+    mu = torch.randn(d, device=DEV, generator=gen) * 1e-2
+    grads = (mu + 1e-2 * torch.randn(J, d, device=DEV, generator=gen)).to(torch.bfloat16)
+    h = synth.Hyper(b_k=64, round_to=1, step=2)
+    w = torch.randn(d, device=DEV, generator=gen) * 0.02
+    m = torch.randn(d, device=DEV, generator=gen) * 0.02
+    v = (torch.randn(d, device=DEV, generator=gen) * 0.02) ** 2
+    w0, m0, v0 = w.clone(), m.clone(), v.clone()
+    res = gpu_step(grads, w, m, v, h, flags=FULL | B.NT_COORD_TEST)
+    ref = H.oracle_full(grads, d, J, h)
+    H.assert_stats_close(res, ref)
+    H.assert_decision_matches(res, ref, h)
+    H.oracle_adamw_check(grads, d, w0, m0, v0, w, m, v, h)
+    H.assert_coord_count(res["coord_fail"], H.oracle_coord_counts(grads, d, h))
+
+
 # ------------------------------------------------------------------ memory safety and graph capture
 
 @pytest.mark.parametrize("J,gdtype,flags", [(8, torch.bfloat16, FULL), (4, torch.float32, FULL),

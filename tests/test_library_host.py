@@ -109,6 +109,7 @@ def _call(J=4, d=64, ld=None, gdtype=B.NT_F32, grads=0x1000, w=0x2000, m=0x3000,
 def test_bad_arguments_are_rejected_before_any_launch():
     bad = B.NT_ERR_BAD_ARG
     assert _call(J=1) == bad
+    assert _call(J=(1 << 20) + 1) == bad                     # more rows than the entry points accept
     assert _call(d=-1) == bad
     assert _call(d=64, ld=63) == bad
     assert _call(grads=None) == bad
