@@ -193,3 +193,35 @@ def test_more_than_2_to_31_coordinates():
     wl = synth.make("beyond_int32", 2, d, gdtype=torch.bfloat16, sigma=1e-2, seed=7, device=DEV,
                     hyper=synth.Hyper(b_k=64, round_to=2, step=3))
     run_and_check(wl)
+
+
+def test_more_tiles_than_the_grid_holds():
+    """Beyond 2^20 tiles (d > 4.29e9 at 4096 coordinates per tile) the blocks of k_step take several tiles each.
+    J = 2 bf16 rows keep the footprint at 70 GB; all sums, and AdamW on windows at the start, around the
+    coordinate where the second round of tiles begins, and at the ragged end."""
+    wrap = 4096 * (1 << 20)
+    d = wrap + 4096 * 3000 + 77
+    wl = synth.make("beyond_grid", 2, d, gdtype=torch.bfloat16, sigma=1e-2, seed=9, device=DEV,
+                    hyper=synth.Hyper(b_k=64, round_to=2, step=3))
+    h = wl.hyper
+    win = 1 << 21
+    windows = [(0, 2 * win), (wrap - win, wrap + win), (d - 2 * win, d)]
+    keep = {lo: [t[lo:hi].clone() for t in (wl.w, wl.m, wl.v)] for lo, hi in windows}
+    hy = B.make_hyper(lr=h.lr, beta1=h.beta1, beta2=h.beta2, eps=h.eps, weight_decay=h.weight_decay, eta=h.eta,
+                      step=h.step, b_k=h.b_k, b_max=h.b_max, round_to=h.round_to, ddof=h.ddof,
+                      flags=FULL | B.NT_COORD_TEST)
+    res = B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hy)
+    torch.cuda.synchronize()
+    res = B.read_result(res).as_dict()
+    ref = H.oracle_full(wl.grads, d, 2, h)
+    H.assert_stats_close(res, ref)
+    H.assert_decision_matches(res, ref, h)
+    H.assert_coord_count(res["coord_fail"], H.oracle_coord_counts(wl.grads, d, h))
+    import oracle
+    for lo, hi in windows:
+        G = synth.grads_as_numpy(wl.grads, lo, hi)
+        w0, m0, v0 = (t.cpu().numpy() for t in keep[lo])
+        out = oracle.adamw(G, w0, m0, v0, h.lr, h.beta1, h.beta2, h.eps, h.weight_decay, h.step)
+        for name, got, want in zip("wmv", (wl.w, wl.m, wl.v), out):
+            H.assert_state_close("%s[%d:%d]" % (name, lo, hi), got[lo:hi].cpu().numpy(), want)
+    print("beyond the grid: d=%d T=%.6g (oracle %.6g)" % (d, res["T"], ref.dec.T), flush=True)
