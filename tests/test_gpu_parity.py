@@ -619,6 +619,95 @@ def test_subnormal_second_moment_keeps_the_sign_step(J):
     assert float((wl.v.double() - v_expect).abs().max()) <= 1.5e-45              # within one subnormal step
 
 
+def test_structural_sweep_over_entry_points_flags_and_alignment():
+    """250 seeded draws of row count (2 .. 3000, every path and both routes), length, dtype, misalignment of rows
+    and of state, row padding, entry point (strided, pointer table, clipped), mode, and the optional flags; all
+    outputs against the oracle, and guard words around every buffer the library may write."""
+    rng = np.random.default_rng(21)
+    guard = 16
+    for case in range(250):
+        J = int(rng.choice([2, 3, 5, 8, 13, 16, 17, 31, 47, 48, 64, 95, 96, 97, 300, 1000, 3000]))
+        d = int(rng.choice([1, 3, 4, 100, 2047, 2048, 2049, 4095, 4097, 8192, 16383, 16385, 30000]))
+        if J * d > 20_000_000:
+            d = 2049
+        gdtype = torch.bfloat16 if rng.random() < 0.5 else torch.float32
+        off = int(rng.choice([0, 0, 1, 2, 3, 4, 8]))
+        pad = int(rng.choice([0, 0, 1, 3, 8, 64]))
+        soff = int(rng.choice([0, 0, 1, 2, 4]))
+        entry = str(rng.choice(["step", "rows", "clipped"]))
+        mode = str(rng.choice(["full", "full", "stats", "adamw"])) if entry != "clipped" else "full"
+        flags = {"full": FULL, "stats": B.NT_DO_STATS, "adamw": B.NT_DO_ADAMW}[mode]
+        coord = mode != "adamw" and rng.random() < 0.5
+        want_gbar = entry != "clipped" and rng.random() < 0.3
+        partial = mode != "adamw" and entry != "clipped" and rng.random() < 0.2
+        one_pass = rng.random() < 0.2
+        h = synth.Hyper(eta=float(rng.choice([0.05, 0.2])), step=int(rng.choice([1, 7])), b_k=int(rng.choice([1, 32, 256])),
+                        b_max=int(rng.choice([0, 512])), round_to=int(rng.choice([1, 16])), ddof=int(rng.integers(0, 2)))
+        sigma = float(rng.choice([1e-3, 1e-2, 1e-1]))
+        max_norm = float(rng.choice([0.0, 0.01, 100.0]))
+        src = synth.make("r", J, d, gdtype=gdtype, sigma=sigma, seed=20000 + case, device=DEV, hyper=h)
+        if d == 1:
+            continue                      # a one-element vector has no rms to measure AdamW errors against
+        big = torch.full((J, off + d + pad), 3.0, dtype=gdtype, device=DEV)
+        grads = big[:, off:off + d]
+        grads.copy_(src.grads)
+        st = []
+        for s0 in (src.w, src.m, src.v):
+            t = torch.full((guard + soff + d + guard,), 9.0, device=DEV)
+            t[guard + soff:guard + soff + d] = s0
+            st.append(t)
+        view = lambda t: t[guard + soff:guard + soff + d]
+        before = [view(t).clone() for t in st]
+        gb = torch.full((guard + soff + d + guard,), 7.0, device=DEV)
+        fl = (flags | (B.NT_COORD_TEST if coord else 0) | (B.NT_WRITE_GBAR if want_gbar else 0)
+              | (B.NT_PARTIAL if partial else 0) | (B.NT_ONE_PASS if one_pass else 0))
+        need = B.normtest_workspace_bytes(J, d)
+        wsraw = torch.full((64 + need + 64,), 0x5A, dtype=torch.uint8, device=DEV)
+        ws = wsraw[64:64 + need]
+        ctx = "case %d J=%d d=%d %s off=%d pad=%d soff=%d entry=%s mode=%s coord=%s gbar=%s partial=%s one_pass=%s" % (
+            case, J, d, gdtype, off, pad, soff, entry, mode, coord, want_gbar, partial, one_pass)
+        try:
+            a = [view(t) if mode != "stats" else None for t in st]
+            if entry == "step":
+                res = B.normtest_step(grads, a[0], a[1], a[2], hyper_of(h, fl), d=d,
+                                      gbar_out=view(gb) if want_gbar else None, workspace=ws)
+            elif entry == "rows":
+                res = B.normtest_step_rows([big[j, off:off + d] for j in range(J)], a[0], a[1], a[2], hyper_of(h, fl),
+                                           d=d, gbar_out=view(gb) if want_gbar else None, workspace=ws)
+            else:
+                res = B.normtest_step_clipped(grads, a[0], a[1], a[2], view(gb), max_norm, hyper_of(h, fl), d=d,
+                                              workspace=ws)
+            torch.cuda.synchronize()
+            r = B.read_result(res).as_dict()
+            ref = H.oracle_full(grads, d, J, h)
+            if mode != "adamw":
+                H.assert_stats_close(r, ref, partial=partial)
+                if not partial:
+                    H.assert_decision_matches(r, ref, h)
+                if coord:
+                    H.assert_coord_count(r["coord_fail"], H.oracle_coord_counts(grads, d, h))
+                else:
+                    assert r["coord_fail"] == -1
+            else:
+                assert r["status"] == B.NT_STATUS_NO_STATS
+            if mode != "stats":
+                coef = oracle.clip_coef(ref.dec.gbar_sq, max_norm) if entry == "clipped" else 1.0
+                H.oracle_adamw_check(grads, d, before[0], before[1], before[2], view(st[0]), view(st[1]), view(st[2]), h,
+                                     gbar=view(gb) if want_gbar else None, grad_scale=coef)
+            else:
+                for t, b0 in zip(st, before):
+                    assert torch.equal(view(t), b0)
+            for t in st:
+                assert bool((t[:guard + soff] == 9.0).all()) and bool((t[guard + soff + d:] == 9.0).all()), "state guard"
+            assert bool((gb[:guard + soff] == 7.0).all()) and bool((gb[guard + soff + d:] == 7.0).all()), "gbar guard"
+            if not (want_gbar or entry == "clipped"):
+                assert bool((gb == 7.0).all()), "gbar touched"
+            assert bool((big[:, :off] == 3.0).all()) and bool((big[:, off + d:] == 3.0).all()), "gradients written"
+            assert bool((wsraw[:64] == 0x5A).all()) and bool((wsraw[64 + need:] == 0x5A).all()), "workspace guard"
+        except AssertionError as e:
+            raise AssertionError(ctx + ": " + str(e))
+
+
 def test_maximum_row_count():
     """J = 2^20 rows (the largest the entry points accept) of a 9-coordinate vector: 65536 chunks per coordinate."""
     J, d = 1 << 20, 9
