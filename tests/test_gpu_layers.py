@@ -222,3 +222,28 @@ def test_partial_step_layers_add_over_shards():
     for t, w_ in zip(tot, want):
         for k in "ABC":
             assert t[k] == pytest.approx(w_[k], rel=RTOL)
+
+
+def test_layer_table_sweep():
+    """200 seeded draws of row count, length, dtype, kind of step, number and position of cuts (layers that start
+    after 0 or end before d included): every layer against the oracle."""
+    rng = np.random.default_rng(31)
+    for case in range(200):
+        J = int(rng.choice([2, 3, 8, 16, 17, 40, 96, 130]))
+        d = int(rng.choice([1, 5, 4096, 4097, 20000, 70001, 200000]))
+        gdtype = torch.bfloat16 if rng.random() < 0.5 else torch.float32
+        mode = str(rng.choice(["full", "stats", "clipped", "rows"]))
+        coord = bool(rng.random() < 0.5)
+        wl = synth.make("layers", J, d, gdtype=gdtype, sigma=float(rng.choice([1e-3, 2e-2])), seed=300 + case, device=DEV,
+                        hyper=synth.Hyper(b_k=int(rng.choice([8, 64])), round_to=1, step=4, ddof=int(rng.integers(0, 2))))
+        cuts = sorted(int(x) for x in rng.integers(0, d + 1, size=int(rng.choice([0, 1, 5, 40]))))
+        lo = 0 if rng.random() < 0.7 else int(rng.integers(0, d + 1))
+        hi = d if rng.random() < 0.7 else int(rng.integers(lo, d + 1))
+        offsets = sorted([lo] + [c for c in cuts if lo <= c <= hi] + [hi])
+        flags = B.NT_DO_STATS if mode == "stats" else FULL
+        try:
+            res, layers = run_layers(wl, flags, offsets, rows=mode == "rows", clipped=mode == "clipped", coord=coord)
+            check_layers(wl, res, layers, offsets, coord=coord)
+        except AssertionError as e:
+            raise AssertionError("case %d J=%d d=%d %s mode=%s coord=%s offsets=%s: %s" % (
+                case, J, d, gdtype, mode, coord, offsets[:8], e))
