@@ -112,6 +112,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0,
                     help="also produce the per-layer table each step: -1 = the workload's own parameter blocks, "
                          "N > 0 = N layers of uneven, unaligned sizes")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step in a HIP graph and time replays (removes launch gaps; matters for small d)")
     ap.add_argument("--one-pass", action="store_true",
                     help="keep the fused single pass where the library would take its two-pass route (many rows)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -181,6 +183,20 @@ def main():
         B.normtest_calib_copy(dst, src, stream=stream)
         torch.cuda.synchronize()
         del src, dst
+    if args.graph:
+        # capture on a side stream (the library only enqueues kernels, so the step can be captured as it is)
+        eager_step = step
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            stream = side
+            eager_step()                       # warm-up outside the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            eager_step()
+        stream = torch.cuda.current_stream()
+        step = graph.replay
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -232,6 +248,7 @@ def main():
             "J": wl.J, "d": wl.d, "grad_dtype": "bf16" if wl.grad_bytes == 2 else "f32",
             "bytes_per_param": bytes_per_param, "flags": flags,
             "layers": 0 if layer_off is None else layer_off.numel() - 1,
+            "graph_replay": bool(args.graph),
         },
         "result": {k: res[k] for k in ("T", "pass", "next_b", "status")},
         "roofline": {
