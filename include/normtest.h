@@ -50,10 +50,11 @@ enum {
 /* nt_result.status bits */
 enum {
   NT_STATUS_NONFINITE = 1u,      /* a sum is NaN/Inf (NaN/Inf gradient, or |g| beyond ~1.8e19): batch size kept  */
-  NT_STATUS_ZERO_GRAD_NORM = 2u, /* ||gbar||^2 == 0: T is NaN (C == 0, passes) or +inf (fails, goes to the cap)  */
+  NT_STATUS_ZERO_GRAD_NORM = 2u, /* ||gbar||^2 == 0: T is NaN (C == 0, passes) or +inf (fails; next_b = b_max, or  */
+                                 /* b_k when b_max is 0 or below b_k: an infinite T names no finite batch size)   */
   NT_STATUS_CLAMPED = 4u,        /* the rounded batch size exceeded b_max and was cut to it                      */
   NT_STATUS_PARTIAL_ONLY = 8u,   /* NT_PARTIAL: only A, B, C (and their low parts) are meaningful                */
-  NT_STATUS_T_SATURATED = 16u,   /* T >= 2^62: treated as infinite                                               */
+  NT_STATUS_T_SATURATED = 16u,   /* T >= 2^62: treated as infinite (same next_b rule as for +inf)                */
   NT_STATUS_NO_STATS = 32u,      /* NT_DO_STATS was clear: sums are NaN, pass = 1, next_b = b_k                  */
   NT_STATUS_BAD_RANGE = 64u      /* nt_layer_stats only: the layer's offsets were descending or outside [0, d]   */
 };
@@ -78,7 +79,7 @@ typedef struct {
   int64_t b_k;                                /* current global batch size, >= 1                               */
   int64_t b_max;                              /* cap on next_b, 0 = none; never pulls next_b below b_k         */
   int64_t round_to;                           /* J*M (workers x accumulation steps): next_b is a multiple;     */
-                                              /* 1 = the plain ceiling rule of Sec. 3.1                        */
+                                              /* 1 = the plain ceiling rule of Sec. 3.1; 1 <= round_to <= 2^31 */
   int32_t ddof;                               /* 0: variance / J (Alg. 1);  1: / (J-1) (sample variance)       */
   uint32_t flags;                             /* NT_DO_* | NT_PARTIAL | NT_WRITE_GBAR | NT_COORD_TEST | NT_ONE_PASS */
 } nt_hyper;

@@ -121,8 +121,8 @@ int nto_decide(double A, double B, double C, int64_t J, double eta, int64_t b_k,
   double Jd = (double)J, T;
   int64_t cap;
   if (!out || J < 1 || J - ddof < 1 || !(eta > 0.0) || b_k < 1 || b_max < 0 || round_to < 1 ||
-      (ddof != 0 && ddof != 1))
-    return -1;
+      round_to > ((int64_t)1 << 31) || (ddof != 0 && ddof != 1))
+    return -1; /* the bound on round_to keeps q * round_to below 2^63 for every t < 2^62 */
   cap = (b_max > 0 && b_max > b_k) ? b_max : b_k; /* value taken when T is infinite */
   out->status = 0;
   out->gbar_sq = B / (Jd * Jd);

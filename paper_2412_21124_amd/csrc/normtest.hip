@@ -97,6 +97,7 @@
 #ifndef NT_MCHUNK
 #define NT_MCHUNK 16          // beyond that, rows are walked this many at a time (2 .. NT_JCHUNK + 1; 16 measured best)
 #endif
+#define NT_ROUND_TO_MAX (1ll << 31)  // bound on nt_hyper.round_to that keeps the rounding chain inside int64
 #define NT_FIN_THREADS 1024
 #define NT_NV 4                // values per tile partial: A, B, C and the count of failing coordinates
 #define NT_GROUP_THREADS 256   // first-stage reduction: threads per block
@@ -715,8 +716,9 @@ __host__ __device__ inline void decide(const DecideParams& q, nt_result* r) {
       r->next_b = cap;
       return;
     }
+    // t < 2^62 and round_to <= 2^31 (validated), so the next multiple fits an int64
     const int64_t t = (int64_t)ceil(T);
-    int64_t nb = ((t + q.round_to - 1) / q.round_to) * q.round_to;
+    int64_t nb = (t / q.round_to + (t % q.round_to != 0)) * q.round_to;
     if (q.b_max > 0 && nb > q.b_max) {
       nb = q.b_max;
       r->status |= NT_STATUS_CLAMPED;
@@ -1057,7 +1059,7 @@ bool hyper_ok(const nt_hyper* h, int64_t J) {
   if (!(h->flags & (NT_DO_STATS | NT_DO_ADAMW))) return false;
   if ((h->flags & (NT_PARTIAL | NT_COORD_TEST)) && !(h->flags & NT_DO_STATS)) return false;
   if (!(h->eta > 0.0) || !std::isfinite(h->eta)) return false;
-  if (h->b_k < 1 || h->b_max < 0 || h->round_to < 1) return false;
+  if (h->b_k < 1 || h->b_max < 0 || h->round_to < 1 || h->round_to > NT_ROUND_TO_MAX) return false;
   if (h->ddof != 0 && h->ddof != 1) return false;
   if (J - h->ddof < 1) return false;
   if (h->flags & NT_DO_ADAMW) {
@@ -1424,7 +1426,7 @@ uint32_t normtest_schedule_flags(int64_t step, int64_t test_interval, int64_t b_
 int normtest_combine(const nt_result* partials, int32_t n, int64_t J, const nt_hyper* hyper, nt_result* out) {
   if (!partials || !out || n < 1 || J < 2 || !hyper) return NT_ERR_BAD_ARG;
   if (!(hyper->eta > 0.0) || !std::isfinite(hyper->eta) || hyper->b_k < 1 || hyper->b_max < 0 ||
-      hyper->round_to < 1 || (hyper->ddof != 0 && hyper->ddof != 1) || J - hyper->ddof < 1)
+      hyper->round_to < 1 || hyper->round_to > NT_ROUND_TO_MAX || (hyper->ddof != 0 && hyper->ddof != 1) || J - hyper->ddof < 1)
     return NT_ERR_BAD_ARG;
   dd tot[3] = {{0.0, 0.0}, {0.0, 0.0}, {0.0, 0.0}};
   uint32_t status = 0;

@@ -164,7 +164,7 @@ def test_fsdp_all_eight_shards_combine_full():
     hy = B.make_hyper(eta=hyper.eta, b_k=hyper.b_k, b_max=hyper.b_max, round_to=hyper.round_to, ddof=hyper.ddof)
     comb = B.normtest_combine(parts, 16, hy).as_dict()
     A, Bs, C = oracle.combine_chunks(accs)
-    ref = H.OracleOut(A, Bs, C, H.oracle_decide(A, Bs, C, 16, hyper))
+    ref = H.OracleOut(A, Bs, C, H.oracle_decide(A, Bs, C, 16, hyper), 16)
     H.assert_stats_close(comb, ref)
     H.assert_decision_matches(comb, ref, hyper)
     print("7e9 parameters in 8 shards: T=%.6g (oracle %.6g) next_b=%d" % (comb["T"], ref.dec.T, comb["next_b"]), flush=True)

@@ -90,7 +90,7 @@ def test_fsdp_shard_scaled_and_combine():
         accs.append((ref.A, ref.B, ref.C))
     comb = B.normtest_combine(parts, J, hyper_of(hyper)).as_dict()
     A, Bs, C = oracle.combine_chunks(accs)
-    ref = H.OracleOut(A, Bs, C, H.oracle_decide(A, Bs, C, J, hyper))
+    ref = H.OracleOut(A, Bs, C, H.oracle_decide(A, Bs, C, J, hyper), J)
     H.assert_stats_close(comb, ref)
     H.assert_decision_matches(comb, ref, hyper)
 

@@ -50,7 +50,7 @@ class Case:
     def compare(self):
         h = self.h
         A, Bs, C = oracle.stats(self.G)
-        ref = H.OracleOut(A, Bs, C, oracle.decide(A, Bs, C, self.J, h.eta, h.b_k, h.b_max, h.round_to, h.ddof))
+        ref = H.OracleOut(A, Bs, C, oracle.decide(A, Bs, C, self.J, h.eta, h.b_k, h.b_max, h.round_to, h.ddof), self.J)
         H.assert_stats_close(self.res, ref)
         H.assert_decision_matches(self.res, ref, h)
         if self.exact:      # every step is exact in binary arithmetic: no threshold tolerance applies

@@ -123,7 +123,7 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert _call(gdtype=7) == B.NT_ERR_UNSUPPORTED
     assert _call(ws_bytes=24) == B.NT_ERR_WORKSPACE_TOO_SMALL
     for kw in (dict(eta=0.0), dict(eta=-1.0), dict(eta=math.nan), dict(step=0), dict(b_k=0), dict(b_max=-1),
-               dict(round_to=0), dict(ddof=2), dict(beta1=1.0), dict(beta2=-0.1), dict(lr=-1.0),
+               dict(round_to=0), dict(round_to=(1 << 31) + 1), dict(ddof=2), dict(beta1=1.0), dict(beta2=-0.1), dict(lr=-1.0),
                dict(eps=-1e-8), dict(weight_decay=math.inf), dict(flags=0), dict(flags=64 | FULL),
                dict(flags=B.NT_COORD_TEST | B.NT_DO_ADAMW),
                dict(flags=B.NT_PARTIAL | B.NT_DO_ADAMW)):
@@ -309,6 +309,53 @@ def test_combine_special_cases_agree_with_oracle():
             want = oracle.decide(A, Bv, C, 4, 0.1, 32, b_max, 4, 1)
             assert (got.next_b, bool(got.pass_), got.status) == (want.next_b, want.passed, want.status), (A, Bv, C)
             assert (math.isnan(got.T) and math.isnan(want.T)) or got.T == want.T
+
+
+def _golden_decision_cases():
+    import test_oracle_pins as P
+    return [c for c in P.GOLDEN_CASES if "expect_T" in c and "expect_A" in c]
+
+
+@pytest.mark.parametrize("case", _golden_decision_cases(), ids=lambda c: c["name"])
+def test_host_decision_on_hand_worked_cases(case):
+    """The library's own decision (host side of normtest_combine) against the hand-worked values under
+    tests/golden/, edge conventions included: no oracle in the loop, so a convention the two share by
+    mistake would still have to match the written value."""
+    J = len(case["g"])
+    hy = B.make_hyper(eta=float(case["eta"]), b_k=int(case["b_k"]), b_max=int(case["b_max"]),
+                      round_to=int(case["round_to"]), ddof=int(case["ddof"]))
+    got = B.normtest_combine([_part(float(case["expect_A"]), float(case["expect_B"]), float(case["expect_C"]))], J, hy)
+    want_T = float(case["expect_T"])
+    if math.isnan(want_T):
+        assert math.isnan(got.T)
+    elif math.isinf(want_T):
+        assert got.T == want_T
+    else:
+        assert got.T == pytest.approx(want_T, rel=1e-14)
+    assert got.gbar_sq == pytest.approx(float(case["expect_gbar_sq"]), rel=1e-15)
+    assert got.var_l1 == pytest.approx(float(case["expect_var_l1"]), rel=1e-15)
+    assert (got.pass_, got.next_b) == (int(case["expect_pass"]), int(case["expect_next_b"]))
+    if "expect_status" in case:
+        assert got.status == int(case["expect_status"])
+
+
+def test_rounding_chain_cannot_overflow():
+    """Largest accepted granularity with the largest statistic that is not treated as infinite: the next multiple
+    of round_to still fits an int64 (both in the library and in the oracle), and a larger round_to is refused."""
+    J, eta, b_k, rt = 2, 1.0, 1, 1 << 31
+    T = float((1 << 62) - (1 << 10))               # largest double below 2^62 is 2^62 - 2^9; this one is exact too
+    Bv = 4.0                                       # gbar_sq = 1
+    C = T                                          # ddof 1: var_l1 = C
+    hy = B.make_hyper(eta=eta, b_k=b_k, b_max=0, round_to=rt, ddof=1)
+    got = B.normtest_combine([_part(C + Bv / J, Bv, C)], J, hy)
+    want = oracle.decide(C + Bv / J, Bv, C, J, eta, b_k, 0, rt, 1)
+    assert got.T == want.T == T
+    expect = -(-int(T) // rt) * rt
+    assert expect == 1 << 62 and got.next_b == want.next_b == expect and got.status == want.status == 0
+    with pytest.raises(B.NormtestError):
+        B.normtest_combine([_part(1, 1, 1)], J, B.make_hyper(eta=eta, b_k=b_k, round_to=rt + 1))
+    with pytest.raises(ValueError):
+        oracle.decide(1.0, 1.0, 1.0, J, eta, b_k, 0, rt + 1, 1)
 
 
 def test_combine_adds_shards_in_double_double():
