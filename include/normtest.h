@@ -256,6 +256,22 @@ uint32_t normtest_schedule_flags(int64_t step, int64_t test_interval, int64_t b_
  * scaling hardware byte counters.  Enqueued on the stream. */
 int normtest_calib_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
+/*
+ * Yardstick for mixes of streams.  Walks, in step, `row_reads` read streams of 2 bytes per coordinate (8 bytes
+ * per lane, like the bfloat16 gradient rows), `reads` read streams and `writes` written streams of 4 bytes per
+ * coordinate (16 bytes per lane, like w, m, v; rmw != 0: each written stream is read first, as an in-place
+ * update does), over `coords` coordinates (a multiple of 4) with the step kernel's load/store instructions and
+ * block shape and no arithmetic.  Time it to see what HBM gives for a given mix, e.g. 8 row reads + 3 in-place
+ * streams (the fused step at J = 8), or R reads x W writes.  buf: device scratch, 16-byte aligned, of at least
+ * row_reads * r2 + (reads + writes) * r4 + 16 bytes, r2 = coords * 2 and r4 = coords * 4 each rounded up to a
+ * multiple of 256; contents are irrelevant and are overwritten.  Supported mixes (else NT_ERR_UNSUPPORTED):
+ * row_reads = 0 with reads in {0, 1, 2, 4, 8, 11} and writes in {0..3} (not both 0), rmw = 0; 1 or 3 in-place
+ * streams alone; row_reads in {4, 8, 16} alone or with 3 in-place streams; 8 row reads + 1 write; 8 row reads +
+ * 3 reads + 3 writes.  Enqueued on the stream.
+ */
+int normtest_calib_streams(void* buf, size_t buf_bytes, int64_t coords, int row_reads, int reads, int writes,
+                           int rmw, void* hip_stream);
+
 /* Static, human-readable text for a return code. */
 const char* normtest_strerror(int code);
 

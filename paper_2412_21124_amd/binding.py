@@ -121,6 +121,9 @@ def lib(path: Optional[str] = None):
         L.normtest_schedule_flags.restype = ctypes.c_uint32
         L.normtest_calib_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.normtest_calib_copy.restype = ctypes.c_int
+        L.normtest_calib_streams.argtypes = [vp, ctypes.c_size_t, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                             ctypes.c_int, vp]
+        L.normtest_calib_streams.restype = ctypes.c_int
         L.normtest_strerror.argtypes = [ctypes.c_int]
         L.normtest_strerror.restype = ctypes.c_char_p
         _lib = L
@@ -401,3 +404,21 @@ def normtest_calib_copy(dst: torch.Tensor, src: torch.Tensor, stream: Optional[t
         rc = lib().normtest_calib_copy(_ptr(dst), _ptr(src), nbytes, ctypes.c_void_p(stream.cuda_stream))
     if rc != NT_OK:
         raise NormtestError(rc, "normtest_calib_copy")
+
+
+def calib_streams_bytes(coords: int, row_reads: int, reads: int, writes: int) -> int:
+    """Scratch bytes normtest_calib_streams needs (the rule stated in the header)."""
+    r2 = (coords * 2 + 255) // 256 * 256
+    r4 = (coords * 4 + 255) // 256 * 256
+    return row_reads * r2 + (reads + writes) * r4 + 16
+
+
+def normtest_calib_streams(buf: torch.Tensor, coords: int, row_reads: int, reads: int, writes: int, rmw: bool = False,
+                           stream: Optional[torch.cuda.Stream] = None) -> None:
+    if stream is None:
+        stream = torch.cuda.current_stream(buf.device)
+    with torch.cuda.device(buf.device):
+        rc = lib().normtest_calib_streams(_ptr(buf), buf.numel() * buf.element_size(), coords, row_reads, reads, writes,
+                                          1 if rmw else 0, ctypes.c_void_p(stream.cuda_stream))
+    if rc != NT_OK:
+        raise NormtestError(rc, "normtest_calib_streams")

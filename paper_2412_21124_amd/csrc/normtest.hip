@@ -1010,6 +1010,55 @@ __global__ __launch_bounds__(NT_AUX_BLOCK) void k_copy16(f32x4* dst, const u32x4
   }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Yardstick: R8 row-like read streams (8 bytes per lane, like four bfloat16 values of a gradient row), R16 read
+// streams and W written streams (16 bytes per lane, like four fp32 values of w, m or v; RMW: read first, as an
+// in-place update does), all walked in step by one block per 4096 coordinates with the step kernel's load and
+// store instructions and no arithmetic beyond an exclusive-or that keeps every load alive.  It shows what
+// the memory system gives for a mix of streams, independent of the step's arithmetic.
+// ---------------------------------------------------------------------------------------------
+#define NT_CALIB_MAX_R8 16
+#define NT_CALIB_MAX_R16 12
+#define NT_CALIB_MAX_W 4
+struct CalibStreams {
+  const char* r8[NT_CALIB_MAX_R8];
+  const char* r16[NT_CALIB_MAX_R16];
+  char* w[NT_CALIB_MAX_W];
+  uint32_t* sink;   // spare word behind the streams; read-only mixes store to it when a load hits one magic value
+};
+
+template <int R8, int R16, int W, bool RMW>
+__global__ __launch_bounds__(NT_AUX_BLOCK) void k_calib_streams(CalibStreams s, int64_t ngroups) {
+  for (int64_t i = (int64_t)blockIdx.x * NT_AUX_BLOCK + threadIdx.x; i < ngroups; i += (int64_t)gridDim.x * NT_AUX_BLOCK) {
+    u32x2 a[R8 > 0 ? R8 : 1];
+    u32x4 b[R16 > 0 ? R16 : 1];
+    u32x4 c[W > 0 ? W : 1];
+#pragma unroll
+    for (int k = 0; k < R8; ++k) a[k] = ld_vec<true, u32x2>(s.r8[k] + 8 * i);
+#pragma unroll
+    for (int k = 0; k < R16; ++k) b[k] = ld16(s.r16[k] + 16 * i);
+    if constexpr (RMW) {
+#pragma unroll
+      for (int k = 0; k < W; ++k) c[k] = ld16(s.w[k] + 16 * i);
+    }
+    uint32_t acc = 0;
+#pragma unroll
+    for (int k = 0; k < R8; ++k) acc ^= a[k][0] ^ a[k][1];
+#pragma unroll
+    for (int k = 0; k < R16; ++k) acc ^= b[k][0] ^ b[k][1] ^ b[k][2] ^ b[k][3];
+#pragma unroll
+    for (int k = 0; k < W; ++k) {
+      u32x4 o = {acc, acc + 1u, acc + 2u, acc + 3u};
+      if constexpr (RMW) o ^= c[k];
+      st16(s.w[k] + 16 * i, __builtin_bit_cast(f32x4, o));
+    }
+    if constexpr (W == 0) {
+      if (acc == 0x9e3779b9u) *s.sink = acc;   // data-dependent, so the loads cannot be dropped
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------------------------
@@ -1481,6 +1530,52 @@ int normtest_calib_copy(void* dst, const void* src, size_t bytes, void* hip_stre
   const int grid = (int)(want < max_grid ? want : max_grid);
   hipLaunchKernelGGL(k_copy16, dim3(grid), dim3(NT_AUX_BLOCK), 0, (hipStream_t)hip_stream, (f32x4*)dst,
                      (const u32x4*)src, n16);
+  return hip_code(hipGetLastError());
+}
+
+int normtest_calib_streams(void* buf, size_t buf_bytes, int64_t coords, int row_reads, int reads, int writes, int rmw,
+                           void* hip_stream) {
+  if (!buf || !aligned16(buf) || coords < 0 || (coords & 3) || row_reads < 0 || reads < 0 || writes < 0)
+    return NT_ERR_BAD_ARG;
+  if (row_reads > NT_CALIB_MAX_R8 || reads > NT_CALIB_MAX_R16 || writes > NT_CALIB_MAX_W || row_reads + reads + writes == 0)
+    return NT_ERR_UNSUPPORTED;
+  // streams sit one after the other: row-like ones of 2 bytes per coordinate first, then those of 4
+  const size_t row_bytes = (((size_t)coords * 2 + 255u) & ~(size_t)255u), vec_bytes = (((size_t)coords * 4 + 255u) & ~(size_t)255u);
+  const size_t need = row_bytes * (size_t)row_reads + vec_bytes * (size_t)(reads + writes) + 16;
+  if (buf_bytes < need) return NT_ERR_WORKSPACE_TOO_SMALL;
+  if (coords == 0) return NT_OK;
+  CalibStreams s;
+  std::memset(&s, 0, sizeof(s));
+  char* at = (char*)buf;
+  for (int k = 0; k < row_reads; ++k, at += row_bytes) s.r8[k] = at;
+  for (int k = 0; k < reads; ++k, at += vec_bytes) s.r16[k] = at;
+  for (int k = 0; k < writes; ++k, at += vec_bytes) s.w[k] = at;
+  s.sink = (uint32_t*)at;
+  const int64_t ngroups = coords / 4;
+  const int64_t want = (ngroups + NT_AUX_BLOCK - 1) / NT_AUX_BLOCK;
+  const int64_t max_grid = (int64_t)cu_count() * NT_BLOCKS_PER_CU;
+  const int grid = (int)(want < max_grid ? want : max_grid);
+  hipStream_t st = (hipStream_t)hip_stream;
+  bool found = false;
+#define NT_CALIB(R8, R16, W, RMW)                                                                                  \
+  if (!found && row_reads == R8 && reads == R16 && writes == W && (rmw != 0) == RMW) {                              \
+    hipLaunchKernelGGL((k_calib_streams<R8, R16, W, RMW>), dim3(grid), dim3(NT_AUX_BLOCK), 0, st, s, ngroups);     \
+    found = true;                                                                                                  \
+  }
+#define NT_CALIB_ROW(R16) NT_CALIB(0, R16, 0, false) NT_CALIB(0, R16, 1, false) NT_CALIB(0, R16, 2, false) NT_CALIB(0, R16, 3, false)
+  // the matrix of read streams x written streams ...
+  NT_CALIB(0, 0, 1, false) NT_CALIB(0, 0, 2, false) NT_CALIB(0, 0, 3, false)
+  NT_CALIB_ROW(1) NT_CALIB_ROW(2) NT_CALIB_ROW(4) NT_CALIB_ROW(8) NT_CALIB_ROW(11)
+  // ... in-place updates alone ...
+  NT_CALIB(0, 0, 1, true) NT_CALIB(0, 0, 3, true)
+  // ... and the traffic of the step itself: J row reads with three in-place fp32 arrays, rows alone, and the same
+  // bytes with the results going to separate arrays
+  NT_CALIB(4, 0, 3, true) NT_CALIB(8, 0, 3, true) NT_CALIB(16, 0, 3, true)
+  NT_CALIB(4, 0, 0, false) NT_CALIB(8, 0, 0, false) NT_CALIB(16, 0, 0, false)
+  NT_CALIB(8, 0, 1, false) NT_CALIB(8, 3, 3, false)
+#undef NT_CALIB_ROW
+#undef NT_CALIB
+  if (!found) return NT_ERR_UNSUPPORTED;
   return hip_code(hipGetLastError());
 }
 
