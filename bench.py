@@ -100,6 +100,49 @@ def cpu_baseline(wl, sample_coords: int):
     }
 
 
+STREAM_MATRIX = ([(0, r, w, False) for r in (0, 1, 2, 4, 8, 11) for w in (0, 1, 2, 3) if r + w > 0]
+                 + [(0, 0, 1, True), (0, 0, 3, True)]
+                 + [(4, 0, 0, False), (8, 0, 0, False), (16, 0, 0, False), (8, 0, 1, False), (8, 3, 3, False),
+                    (4, 0, 3, True), (8, 0, 3, True), (16, 0, 3, True)])
+
+
+def run_streams(args):
+    """The library's stream-mix yardstick (normtest_calib_streams): what HBM gives for R read and W written
+    streams walked in step with the step kernel's access widths and no arithmetic.  One JSON line."""
+    import torch
+    from paper_2412_21124_amd import binding as B
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU: the library has no CPU path")
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    coords = args.coords // 4 * 4
+    mixes = STREAM_MATRIX if args.matrix else [(args.row_reads, args.reads, args.writes, args.rmw)]
+    buf = torch.empty(max(B.calib_streams_bytes(coords, a, r, w) for a, r, w, _ in mixes), dtype=torch.uint8, device=dev)
+    buf.zero_()
+    stream = torch.cuda.current_stream()
+    rows = []
+    for a, r, w, rmw in mixes:
+        nbytes = coords * (2 * a + 4 * r + (8 if rmw else 4) * w)
+        for _ in range(args.warmup):
+            B.normtest_calib_streams(buf, coords, a, r, w, rmw, stream=stream)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        for e0, e1 in ev:
+            e0.record(stream)
+            B.normtest_calib_streams(buf, coords, a, r, w, rmw, stream=stream)
+            e1.record(stream)
+        torch.cuda.synchronize()
+        ms = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+        med = ms[len(ms) // 2]
+        rows.append({"row_reads": a, "reads": r, "writes": w, "rmw": bool(rmw), "bytes": nbytes, "ms_median": med,
+                     "ms_min": ms[0], "GBps": nbytes / (med * 1e-3) / 1e9, "frac": nbytes / (med * 1e-3) / 1e9 / HBM_PEAK_GBS})
+        print("# row_reads %2d reads %2d writes %d rmw %d: %8.3f ms  %6.0f GB/s" % (a, r, w, rmw, med, rows[-1]["GBps"]),
+              file=sys.stderr, flush=True)
+    print(json.dumps({"metric": "stream-mix yardstick (no arithmetic): HBM GB/s", "unit": "GB/s", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "coords_per_stream": coords, "peak": HBM_PEAK_GBS,
+                      "mixes": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -107,8 +150,16 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="flat_1p5b")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink d (debugging only; the result is then not the headline)")
-    ap.add_argument("--mode", default="full", choices=["full", "stats", "adamw", "clipped"],
-                    help="full: the fused step (headline); stats / adamw: one half only; clipped: two-phase variant")
+    ap.add_argument("--mode", default="full", choices=["full", "stats", "adamw", "clipped", "streams"],
+                    help="full: the fused step (headline); stats / adamw: one half only; clipped: two-phase variant; "
+                         "streams: the stream-mix yardstick (see --row-reads, --reads, --writes, --rmw, --matrix)")
+    ap.add_argument("--row-reads", type=int, default=8, help="streams mode: read streams of 2 bytes per coordinate")
+    ap.add_argument("--reads", type=int, default=0, help="streams mode: read streams of 4 bytes per coordinate")
+    ap.add_argument("--writes", type=int, default=3, help="streams mode: written streams of 4 bytes per coordinate")
+    ap.add_argument("--rmw", action="store_true", help="streams mode: written streams are read first (in-place update)")
+    ap.add_argument("--matrix", action="store_true", help="streams mode: every supported mix in one run")
+    ap.add_argument("--coords", type=int, default=402_653_184,
+                    help="streams mode: coordinates per stream (default 1.5 GiB per fp32 stream)")
     ap.add_argument("--layers", type=int, default=0,
                     help="also produce the per-layer table each step: -1 = the workload's own parameter blocks, "
                          "N > 0 = N layers of uneven, unaligned sizes")
@@ -123,6 +174,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+    if args.mode == "streams":
+        return run_streams(args)
 
     import torch
     from paper_2412_21124_amd import binding as B
