@@ -65,6 +65,7 @@ enum {
   NT_ERR_BAD_ARG = -1,
   NT_ERR_UNSUPPORTED = -2,
   NT_ERR_WORKSPACE_TOO_SMALL = -3,
+  NT_ERR_TOO_LARGE = -4,
   NT_ERR_HIP_BASE = -1000
 };
 
@@ -164,6 +165,28 @@ int normtest_step_rows(const void* const* grad_rows_dev, nt_dtype gdtype, int64_
                        const nt_hyper* hyper, const nt_shard_info* shard,
                        void* workspace, size_t workspace_bytes,
                        nt_result* result_dev, void* hip_stream);
+
+/*
+ * normtest_step for callers that cannot allocate or hand over a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results (bit for bit) as
+ * normtest_step, without `workspace`: the tile partial sums and the record of the step go to a 16 MiB array that
+ * the library holds in each GPU's memory (a static __device__ array; no hipMalloc, hipFree or other allocating
+ * call is made here, on any path).  Limits: d <= normtest_static_max_coords(J) (about 2.1e9 coordinates up to
+ * 16 rows, 1.0e9 beyond), else NT_ERR_TOO_LARGE and nothing is enqueued.  With many rows (96 bf16 / 48 fp32 or
+ * more) normtest_step's two-pass route needs 4 d bytes for gbar: here it is taken only when NT_WRITE_GBAR names a
+ * gbar_out buffer, otherwise the single fused pass runs (same bits).  The array keeps the last call's contents;
+ * nothing in it has to be cleared between calls.  All calls on one GPU share it: two calls that overlap in time
+ * on the same GPU (different streams, or graphs replayed concurrently) race and give wrong statistics; calls on
+ * one stream, or ordered by events, are fine.  normtest_layer_stats cannot follow this call (it needs the
+ * caller's workspace).
+ */
+int normtest_step_static(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld,
+                         float* w, float* m, float* v, float* gbar_out,
+                         const nt_hyper* hyper, const nt_shard_info* shard,
+                         nt_result* result_dev, void* hip_stream);
+
+/* Largest d that normtest_step_static accepts for J rows (0 if J is invalid). */
+int64_t normtest_static_max_coords(int64_t J);
 
 /*
  * Host-side combination of n per-shard partial results (all host memory), Sec. 3.3 / Appendix A:

@@ -23,7 +23,7 @@ NT_STATUS_PARTIAL_ONLY = 8
 NT_STATUS_T_SATURATED = 16
 NT_STATUS_NO_STATS = 32
 NT_STATUS_BAD_RANGE = 64
-NT_OK, NT_ERR_BAD_ARG, NT_ERR_UNSUPPORTED, NT_ERR_WORKSPACE_TOO_SMALL, NT_ERR_HIP_BASE = 0, -1, -2, -3, -1000
+NT_OK, NT_ERR_BAD_ARG, NT_ERR_UNSUPPORTED, NT_ERR_WORKSPACE_TOO_SMALL, NT_ERR_TOO_LARGE, NT_ERR_HIP_BASE = 0, -1, -2, -3, -4, -1000
 
 
 class nt_hyper(ctypes.Structure):
@@ -98,6 +98,11 @@ def lib(path: Optional[str] = None):
                                     ctypes.POINTER(nt_hyper), ctypes.POINTER(nt_shard_info),
                                     vp, ctypes.c_size_t, vp, vp]
         L.normtest_step.restype = ctypes.c_int
+        L.normtest_step_static.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp,
+                                           ctypes.POINTER(nt_hyper), ctypes.POINTER(nt_shard_info), vp, vp]
+        L.normtest_step_static.restype = ctypes.c_int
+        L.normtest_static_max_coords.argtypes = [i64]
+        L.normtest_static_max_coords.restype = i64
         L.normtest_step_rows.argtypes = [vp, ctypes.c_int, i64, i64, vp, vp, vp, vp,
                                          ctypes.POINTER(nt_hyper), ctypes.POINTER(nt_shard_info),
                                          vp, ctypes.c_size_t, vp, vp]
@@ -200,6 +205,42 @@ def normtest_step(grads: torch.Tensor, w: Optional[torch.Tensor], m: Optional[to
         raise NormtestError(rc, "normtest_step")
     if own_workspace:
         workspace.record_stream(stream)   # keep the scratch alive until the stream has consumed it
+    return result
+
+
+def normtest_static_max_coords(J: int) -> int:
+    return int(lib().normtest_static_max_coords(J))
+
+
+def normtest_step_static(grads: torch.Tensor, w: Optional[torch.Tensor], m: Optional[torch.Tensor],
+                         v: Optional[torch.Tensor], hyper: nt_hyper, result: torch.Tensor, *, d: Optional[int] = None,
+                         shard: Optional[nt_shard_info] = None, gbar_out: Optional[torch.Tensor] = None,
+                         stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """normtest_step without a workspace (the library's built-in scratch) and without any allocation here:
+    the caller passes the device tensor for the nt_result."""
+    if grads.dim() != 2 or (grads.shape[1] > 1 and grads.stride(1) != 1):
+        raise ValueError("grads must be (J, ld) with a contiguous last axis")
+    J = grads.shape[0]
+    ld = grads.stride(0) if J > 1 else grads.shape[1]
+    d = grads.shape[1] if d is None else d
+    dev = grads.device
+    if dev.type != "cuda":
+        raise ValueError("normtest_step_static needs device tensors; there is no CPU path")
+    for name, t in (("w", w), ("m", m), ("v", v), ("gbar_out", gbar_out)):
+        if t is not None:
+            if t.dtype != torch.float32 or t.device != dev or not t.is_contiguous() or t.numel() < d:
+                raise ValueError("%s must be a contiguous float32 tensor of >= d elements on %s" % (name, dev))
+    if result is None or result.device != dev or result.numel() * result.element_size() < RESULT_BYTES:
+        raise ValueError("result must be a device tensor of at least RESULT_BYTES bytes")
+    if stream is None:
+        stream = torch.cuda.current_stream(dev)
+    with torch.cuda.device(dev):
+        rc = lib().normtest_step_static(_ptr(grads), _gdtype(grads), J, d, ld, _ptr(w), _ptr(m), _ptr(v),
+                                        _ptr(gbar_out), ctypes.byref(hyper),
+                                        ctypes.byref(shard) if shard is not None else None,
+                                        _ptr(result), ctypes.c_void_p(stream.cuda_stream))
+    if rc != NT_OK:
+        raise NormtestError(rc, "normtest_step_static")
     return result
 
 

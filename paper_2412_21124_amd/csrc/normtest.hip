@@ -110,6 +110,11 @@
 #define NT_TWO_PHASE_ROW_BYTES 192  // from this many gradient bytes per coordinate on (96 bf16 or 48 fp32 rows) the
 #endif                              // full step runs as statistics + gbar, then AdamW from gbar
 
+// Scratch of normtest_step_static: the per-tile partial sums and the record of the step, for callers that
+// cannot hand over (or allocate) a workspace.  One copy per GPU, held until the process ends.
+#define NT_SCRATCH_BYTES (16u << 20)
+static __device__ __align__(256) unsigned char scratch[NT_SCRATCH_BYTES];
+
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -1379,6 +1384,55 @@ int normtest_step_rows(const void* const* grad_rows_dev, nt_dtype gdtype, int64_
                              (hipStream_t)hip_stream);
 }
 
+// Address of this device's copy of `scratch`, looked up once per device (the array's name is only a host-side
+// handle of the symbol; kernels, copies and fills take this pointer).
+static int scratch_address(void** out) {
+  static void* cached[64] = {nullptr};
+  int dev = 0;
+  const hipError_t e0 = hipGetDevice(&dev);
+  if (e0 != hipSuccess) return hip_code(e0);
+  if (dev < 0 || dev >= 64) return NT_ERR_UNSUPPORTED;
+  void* ptr = __atomic_load_n(&cached[dev], __ATOMIC_ACQUIRE);
+  if (!ptr) {
+    const hipError_t e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_code(e);
+    if (!ptr) return NT_ERR_UNSUPPORTED;
+    __atomic_store_n(&cached[dev], ptr, __ATOMIC_RELEASE);
+  }
+  *out = ptr;
+  return NT_OK;
+}
+
+int64_t normtest_static_max_coords(int64_t J) {
+  if (J < 2 || J > (1 << 20)) return 0;
+  // largest d whose record, tile partials and group partials fit: partials_bytes is monotone in d
+  int64_t lo = 0, hi = (int64_t)1 << 40;
+  while (lo < hi) {
+    const int64_t mid = lo + (hi - lo + 1) / 2;
+    if (partials_bytes(J, mid) <= NT_SCRATCH_BYTES) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
+int normtest_step_static(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld, float* w, float* m,
+                         float* v, float* gbar_out, const nt_hyper* hyper, const nt_shard_info* shard,
+                         nt_result* result_dev, void* hip_stream) {
+  if (!hyper) return NT_ERR_BAD_ARG;
+  if (J >= 2 && J <= (1 << 20) && d > normtest_static_max_coords(J)) return NT_ERR_TOO_LARGE;
+  // many rows: the two-pass route needs room for gbar, which only the caller can give (NT_WRITE_GBAR)
+  nt_hyper hy = *hyper;
+  if (!(hy.flags & NT_WRITE_GBAR)) hy.flags |= NT_ONE_PASS;
+  // validate with a stand-in for the workspace (any non-null, aligned address: nothing is enqueued here)
+  const int rc = check_step_args(grads, gdtype, J, d, ld, w, m, v, gbar_out, hy.flags, &hy, shard, (const void*)256,
+                                 (size_t)-1, result_dev);
+  if (rc != NT_OK) return rc;
+  void* ws = nullptr;
+  const int rs = scratch_address(&ws);
+  if (rs != NT_OK) return rs;
+  return enqueue_step_routed(grads, false, gdtype, J, d, ld, w, m, v, gbar_out, &hy, ws, result_dev,
+                             (hipStream_t)hip_stream);
+}
+
 int normtest_step_clipped(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld, float* w, float* m,
                           float* v, float* gbar_buf, double max_norm, const nt_hyper* hyper,
                           const nt_shard_info* shard, void* workspace, size_t workspace_bytes, nt_result* result_dev,
@@ -1585,6 +1639,7 @@ const char* normtest_strerror(int code) {
     case NT_ERR_BAD_ARG: return "bad argument (null or misaligned pointer, J < 2, d < 0, ld < d, or invalid hyper-parameters)";
     case NT_ERR_UNSUPPORTED: return "unsupported gradient dtype";
     case NT_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than normtest_workspace_bytes(J, d)";
+    case NT_ERR_TOO_LARGE: return "d beyond normtest_static_max_coords(J): the built-in scratch cannot hold the partial sums";
     default: break;
   }
   if (code <= NT_ERR_HIP_BASE) return hipGetErrorString((hipError_t)(NT_ERR_HIP_BASE - code));

@@ -168,6 +168,30 @@ def test_clipped_entry_points_validate_before_launch():
     assert f(0x7000, 0, None, None, None, ctypes.byref(hy), 1.0, None, None) == B.NT_OK               # d = 0: nothing to do
 
 
+def test_static_entry_point_validates_before_launch():
+    """normtest_step_static: the size limit and the argument checks come before any HIP call."""
+    hy = B.make_hyper(step=1, b_k=32, flags=FULL)
+    L = B.lib()
+
+    def call(J=8, d=64, ld=None, w=0x2000, hyper=hy, result=0x6000):
+        return L.normtest_step_static(0x1000, B.NT_BF16, J, d, d if ld is None else ld, w, 0x3000, 0x4000, None,
+                                      ctypes.byref(hyper), None, result, None)
+
+    for J in (2, 8, 16, 17, 512):
+        top = B.normtest_static_max_coords(J)
+        assert top > 10 ** 9
+        assert call(J=J, d=top + 1) == B.NT_ERR_TOO_LARGE
+        assert B.normtest_workspace_bytes(J, top) - (4 * top + 32 if J >= 48 else 0) <= 16 << 20
+    assert B.normtest_static_max_coords(1) == 0
+    assert call(J=1) == B.NT_ERR_BAD_ARG
+    assert call(d=-1) == B.NT_ERR_BAD_ARG
+    assert call(ld=63) == B.NT_ERR_BAD_ARG
+    assert call(w=None) == B.NT_ERR_BAD_ARG
+    assert call(result=None) == B.NT_ERR_BAD_ARG
+    assert call(hyper=B.make_hyper(step=1, b_k=0, flags=FULL)) == B.NT_ERR_BAD_ARG
+    assert "scratch" in B.normtest_strerror(B.NT_ERR_TOO_LARGE)
+
+
 def test_rows_entry_point_validates_before_launch():
     L = B.lib()
     hy = B.make_hyper(step=1, b_k=32, flags=FULL)
