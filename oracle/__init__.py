@@ -71,6 +71,8 @@ def _bind(path: str):
     lib.nto_adamw.restype = ctypes.c_int
     lib.nto_coord_test.argtypes = [vp, ctypes.c_int, i64, i64, i64, dbl, i64, ctypes.c_int32, dbl, vp]
     lib.nto_coord_test.restype = ctypes.c_int
+    lib.nto_coord_max_ratio.argtypes = [vp, ctypes.c_int, i64, i64, i64, dbl, i64, ctypes.c_int32, vp]
+    lib.nto_coord_max_ratio.restype = ctypes.c_int
     lib.nto_resplit.argtypes = [i64, i64, i64, i64, vp, vp, vp]
     lib.nto_resplit.restype = ctypes.c_int
     lib.nto_test_due.argtypes = [i64, i64, i64, i64]
@@ -170,6 +172,20 @@ def coord_test(G: np.ndarray, eta: float, b_k: int, ddof: int = 1, band: float =
         if J - ddof < 1 or not eta > 0 or b_k < 1:
             raise ValueError("nto_coord_test rejected its arguments")
     return int(out[0]), int(out[1]), int(out[2])
+
+
+def coord_max_ratio(G: np.ndarray, eta: float, b_k: int, ddof: int = 1, start: float = 0.0) -> float:
+    """Largest Var_i / (eta^2 b_k gbar_i^2) over the columns of G (0 where a column has no spread, +inf where it
+    has spread around a zero mean); `start` carries the maximum of earlier ranges of coordinates."""
+    ptr, dtype, J, ld, n = _grad_args(G)
+    out = np.array([start], dtype=np.float64)
+    if n:
+        rc = _load().nto_coord_max_ratio(ptr, dtype, J, ld, n, eta, b_k, ddof, out.ctypes.data)
+        if rc:
+            raise ValueError("nto_coord_max_ratio rejected its arguments")
+    elif J - ddof < 1 or not eta > 0 or b_k < 1:
+        raise ValueError("nto_coord_max_ratio rejected its arguments")
+    return float(out[0])
 
 
 def resplit(b: int, J: int, M_base: int, micro_max: int):

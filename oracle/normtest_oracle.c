@@ -241,6 +241,41 @@ int nto_coord_test(const void *grads, int dtype, int64_t J, int64_t ld, int64_t 
 }
 
 /*
+ * Largest violation of the coordinate-wise condition (Sec. 4, Prop. 1, with the estimators of the aggregate
+ * test): the maximum over coordinates i of
+ *   rho_i = Var_i / (eta^2 b_k gbar_i^2),   Var_i = sum_j (g_j[i] - gbar_i)^2 / (J - ddof),
+ * so that coordinate i fails exactly when rho_i > 1, and max_i rho_i <= 1 means every coordinate passes.
+ * Conventions where the quotient is not defined: a coordinate with no spread (Var_i = 0) has rho_i = 0
+ * whatever its mean (0 > 0 is false: it passes); a coordinate with spread and a zero mean has rho_i = +inf.
+ * *out is a running maximum: the caller sets it to 0 before the first range of coordinates and may call again
+ * with further ranges (the maximum over shards is the maximum of the shards' values).
+ */
+int nto_coord_max_ratio(const void *grads, int dtype, int64_t J, int64_t ld, int64_t n, double eta, int64_t b_k,
+                        int32_t ddof, double *out) {
+  if (!grads || !out || J < 1 || J - ddof < 1 || n < 0 || ld < n || !(eta > 0.0) || b_k < 1 ||
+      (dtype != NTO_F32 && dtype != NTO_BF16) || (ddof != 0 && ddof != 1))
+    return -1;
+  for (int64_t i = 0; i < n; ++i) {
+    double total = 0.0, spread = 0.0, mean, variance, rho;
+    for (int64_t j = 0; j < J; ++j) total += widen(grads, dtype, j * ld + i);
+    mean = total / (double)J;
+    for (int64_t j = 0; j < J; ++j) {
+      double dev = widen(grads, dtype, j * ld + i) - mean;
+      spread += dev * dev;
+    }
+    variance = spread / (double)(J - ddof);
+    if (variance == 0.0)
+      rho = 0.0;
+    else if (mean == 0.0)
+      rho = INFINITY;
+    else
+      rho = variance / (eta * eta * (double)b_k * mean * mean);
+    if (rho > *out) *out = rho;
+  }
+  return 0;
+}
+
+/*
  * Global-norm gradient clipping, used in the paper's runs (Sec. 5, training specifications; the
  * hyper-parameter tables list "gradient clipping 1.0") but not part of Alg. 1.  The paper gives no
  * formula; this is the usual convention: the whole gradient is scaled by

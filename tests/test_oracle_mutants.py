@@ -45,6 +45,17 @@ MUTANTS = [
     ("coord_ddof_ignored", "var = c / (double)(J - ddof);", "var = c / (double)J;"),
     ("coord_equality_fails", "if (var > rhs * (1.0 + band))", "if (var >= rhs * (1.0 + band))"),
     ("coord_inequality_flipped", "if (var > rhs * (1.0 + band))", "if (var < rhs * (1.0 + band))"),
+    ("ratio_without_batch", "rho = variance / (eta * eta * (double)b_k * mean * mean);", "rho = variance / (eta * eta * mean * mean);"),
+    ("ratio_eta_not_squared", "rho = variance / (eta * eta * (double)b_k * mean * mean);", "rho = variance / (eta * (double)b_k * mean * mean);"),
+    ("ratio_mean_not_squared", "rho = variance / (eta * eta * (double)b_k * mean * mean);", "rho = variance / (eta * eta * (double)b_k * mean);"),
+    ("ratio_inverted", "rho = variance / (eta * eta * (double)b_k * mean * mean);", "rho = (eta * eta * (double)b_k * mean * mean) / variance;"),
+    ("ratio_ddof_ignored", "variance = spread / (double)(J - ddof);", "variance = spread / (double)J;"),
+    ("ratio_minimum", "if (rho > *out) *out = rho;", "if (rho < *out) *out = rho;"),
+    ("ratio_last_not_largest", "if (rho > *out) *out = rho;", "*out = rho;"),
+    ("ratio_zero_mean_ignored", "else if (mean == 0.0)\n      rho = INFINITY;", "else if (mean == 0.0)\n      rho = 0.0;"),
+    ("ratio_no_spread_is_nan", "if (variance == 0.0)\n      rho = 0.0;\n    else if", "if (0)\n      rho = 0.0;\n    else if"),
+    ("ratio_mean_not_divided", "mean = total / (double)J;", "mean = total;"),
+    ("ratio_deviation_not_squared", "spread += dev * dev;", "spread += dev;"),
     ("resplit_ignores_cap", "if (m < M_base) m = M_base;", "m = M_base;"),
     ("resplit_floor_micro", "mb = b / (J * m) + (b % (J * m) != 0);", "mb = b / (J * m);"),
     ("resplit_steps_from_total", "m = per_worker / micro_max + (per_worker % micro_max != 0);", "m = b / micro_max + (b % micro_max != 0);"),

@@ -127,6 +127,15 @@ def test_golden_coordinatewise(case, as_bf16):
         assert (fail, near) == (int(val), 0) and fail + ok == G.shape[1], key
         n_checked += 1
     assert n_checked >= 2
+    n_ratio = 0
+    for key, val in case.items():
+        if not key.startswith("maxratio_"):
+            continue
+        _, dd, bk = key.split("_")
+        got = oracle.coord_max_ratio(Gin, float(case["eta"]), int(bk[2:]), int(dd[4:]))
+        assert approx_or_special(got, val, 1e-15), key
+        n_ratio += 1
+    assert n_ratio >= 2
 
 
 @pytest.mark.parametrize("as_bf16", [False, True])
@@ -201,6 +210,35 @@ def test_coordinatewise_brute_force_and_invariants(J):
             assert oracle.coord_test(G * np.float32(8.0), float(eta), b_k, ddof) == (fail, near, ok)
             # a larger batch can only make coordinates pass
             assert oracle.coord_test(G, float(eta), b_k * 4, ddof)[0] <= fail
+            # largest ratio: exact rationals, with the two conventions (no spread: 0; spread around zero mean: inf)
+            exact_max, any_inf = Fraction(0), False
+            for i in range(d):
+                col = [Fraction(float(x)) for x in G[:, i]]
+                mean = sum(col) / J
+                var = sum((x - mean) ** 2 for x in col) / (J - ddof)
+                if var == 0:
+                    continue
+                if mean == 0:
+                    any_inf = True
+                else:
+                    exact_max = max(exact_max, var / (eta * eta * b_k * mean * mean))
+            got = oracle.coord_max_ratio(G, float(eta), b_k, ddof)
+            if any_inf:
+                assert got == math.inf
+                finite = np.ascontiguousarray(G[:, [i for i in range(d) if G[:, i].sum(dtype=np.float64) != 0 or not G[:, i].any()]])
+                got = oracle.coord_max_ratio(finite, float(eta), b_k, ddof)
+            assert got == pytest.approx(float(exact_max), rel=1e-14)
+            # somebody fails exactly when the largest ratio exceeds one (up to the rounding of an exact tie)
+            assert (fail > 0) == (oracle.coord_max_ratio(G, float(eta), b_k, ddof) > 1.0) or exact_eq > 0
+            # scale-free, monotone in b_k (ratio ~ 1/b_k), and the maximum over shards is the maximum of the shards
+            whole_r = oracle.coord_max_ratio(G, float(eta), b_k, ddof)
+            assert oracle.coord_max_ratio(G * np.float32(8.0), float(eta), b_k, ddof) == whole_r
+            if math.isfinite(whole_r):
+                assert oracle.coord_max_ratio(G, float(eta), 4 * b_k, ddof) == pytest.approx(whole_r / 4, rel=1e-15)
+            run = 0.0
+            for lo, hi in ((0, 33), (33, 150), (150, d)):
+                run = oracle.coord_max_ratio(np.ascontiguousarray(G[:, lo:hi]), float(eta), b_k, ddof, start=run)
+            assert run == whole_r
     # if every coordinate passes, so does the aggregate test (sum the inequalities)
     Gp = np.tile(np.array([[1.0], [1.25]], dtype=np.float32), (1, 50))
     assert oracle.coord_test(Gp, 0.5, 4, 1)[0] == 0
