@@ -3,13 +3,15 @@
 
 A "step" is one pass of the whole hot path (statistics, decision, fused AdamW: `normtest_step`) over
 the headline workload: J=8 bfloat16 gradient rows of a flat d=1.5e9 vector with fp32 w, m, v, all
-resident in HBM before the timed region.  Prints one JSON line.
+resident in HBM before the timed region.  Prints one JSON line; its `configs` array carries the other
+workloads of the benchmark set (gpt2_small, fsdp_shard, per_sample, tiny), timed in the same run.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload flat_1p5b|gpt2_small|fsdp_shard|per_sample|tiny|paper_300m|paper_1.1b|paper_3.4b]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--mode full|stats|adamw|clipped|streams]
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -20,15 +22,31 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+HEADLINE = "flat_1p5b"
+METRIC = "norm-test+AdamW step: achieved HBM GB/s (% of peak), params/s at d=1.5B J=8"
+OTHER_CONFIGS = ("gpt2_small", "fsdp_shard", "per_sample", "tiny")
+KERNEL_SOURCE = os.path.join(ROOT, "paper_2412_21124_amd", "csrc", "normtest.hip")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
 
-# HBM bytes per step from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/), scaled by the
-# copy-kernel calibration; None until measured for that workload.
-MEASURED_TRAFFIC_BYTES = {
-    # profiles/k_step_flat_1p5b.md: FETCH_SIZE x 2.0000 + WRITE_SIZE x 1.0000 per k_step launch
-    ("flat_1p5b", "full"): 6.0010e10,
-    # profiles/k_step_other_workloads.md, clipped mode: k_step (statistics + gbar) + k_adamw_gbar
-    ("flat_1p5b", "clipped"): 7.201e10,
-}
+
+def kernel_source_sha256(path: str = KERNEL_SOURCE) -> str:
+    with open(path, "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()
+
+
+def traffic_from_profile(workload: str, mode: str, traffic_file: str = TRAFFIC_FILE, source: str = KERNEL_SOURCE):
+    """HBM bytes per step that the tracked counter runs measured for this workload and mode (rocprofv3 --pmc
+    FETCH_SIZE and WRITE_SIZE, scaled by the copy-kernel calibration; profiles/traffic.json records the runs), or
+    None when there is no such run or when it was made with another version of the kernel source."""
+    try:
+        with open(traffic_file) as f:
+            prof = json.load(f)
+    except (OSError, ValueError):
+        return None
+    if prof.get("kernel_source_sha256") != kernel_source_sha256(source):
+        return None
+    entry = prof.get("entries", {}).get("%s/%s" % (workload, mode))
+    return None if entry is None else float(entry["hbm_bytes_per_step"])
 
 
 def make_workload(name: str, device: str, scale: float):
@@ -46,6 +64,12 @@ def make_workload(name: str, device: str, scale: float):
         return synth.per_sample(d=max(64, int((1 << 24) * scale) // 64 * 64), device=device)
     if name == "tiny":
         return synth.tiny(1e-2, device=device)
+    if name.startswith("rows:"):
+        # rows:J:d -- J bf16 rows of a flat d-coordinate vector with the headline's distribution (row-count sweeps)
+        _, J, d = name.split(":")
+        wl = synth.flat_1p5b(d=int(int(d) * scale), J=int(J), device=device)
+        wl.name = "rows_J%s" % J
+        return wl
     if name in ("paper_300m", "paper_1.1b", "paper_3.4b"):
         which = name.split("_")[1]
         wl = synth.paper_model(which, device=device)
@@ -55,13 +79,13 @@ def make_workload(name: str, device: str, scale: float):
 
 def cpu_baseline(wl, sample_coords: int):
     """The oracle, as it stands, on the host cores over the first `sample_coords` coordinates."""
-    import numpy as np
     import oracle
     from concurrent.futures import ThreadPoolExecutor
     from paper_2412_21124_amd import synth
 
     n = min(wl.d, sample_coords)
-    threads = max(1, min(16, os.cpu_count() or 1))
+    cores = os.cpu_count() or 1
+    threads = max(1, min(16, cores))     # the box's CPU share for one GPU
     chunk = 1 << 22
     h = wl.hyper
     G = synth.grads_as_numpy(wl.grads, 0, n)
@@ -88,16 +112,151 @@ def cpu_baseline(wl, sample_coords: int):
         work(r)
     dt1 = time.perf_counter() - t1
     bytes_per_param = wl.J * wl.grad_bytes + 24
+    used = min(threads, len(ranges))
     return {
         "value": n * bytes_per_param / dt / 1e9,
         "unit": "GB/s",
         "params_per_s": n / dt,
-        "cores": min(threads, len(ranges)),
+        "cores": used,
+        "host_cores": cores,
         "kind": "oracle",
         "seconds": dt,
         "one_core_params_per_s": n1 / dt1,
-        "sample": "first %d coordinates of the same workload (J=%d), statistics + decision + AdamW in fp64" % (n, wl.J),
+        "sample": "first %d coordinates of the same workload (J=%d), statistics + decision + AdamW in fp64 "
+                  "(the C oracle called from %d Python threads; the host reports %d cores)" % (n, wl.J, used, cores),
     }
+
+
+MODE_TEXT = {
+    "full": "stats+decision+fused AdamW in one pass",
+    "full_two_pass": "statistics + decision, then AdamW from the stored mean (the library's two-pass route for many rows)",
+    "stats": "statistics and decision only",
+    "adamw": "mean + AdamW only (test skipped)",
+    "clipped": "two-phase gradient-clipped step (stats+gbar, then AdamW)",
+}
+
+
+def time_steps(wl, mode: str, steps: int, warmup: int, *, one_pass=False, layers=0, graph=False, calib_copy_gib=0):
+    """Run `warmup` + `steps` steps of one workload and mode; HIP events on the launch stream bracket every step."""
+    import torch
+    from paper_2412_21124_amd import binding as B
+
+    dev = wl.grads.device
+    h = wl.hyper
+    flags = {"full": B.NT_DO_STATS | B.NT_DO_ADAMW, "stats": B.NT_DO_STATS, "adamw": B.NT_DO_ADAMW,
+             "clipped": B.NT_DO_STATS | B.NT_DO_ADAMW}[mode]
+    if wl.name == "fsdp_shard" and mode in ("full", "stats"):
+        flags |= B.NT_PARTIAL
+    if one_pass:
+        flags |= B.NT_ONE_PASS
+    # bytes per coordinate: J gradient reads; + read/write of w, m, v; the clipped variant also writes and re-reads gbar
+    bytes_per_param = wl.J * wl.grad_bytes + {"full": 24, "stats": 0, "adamw": 24, "clipped": 32}[mode]
+    gbar_buf = torch.empty(wl.d, dtype=torch.float32, device=dev) if mode == "clipped" else None
+    hy = B.make_hyper(lr=h.lr, beta1=h.beta1, beta2=h.beta2, eps=h.eps, weight_decay=h.weight_decay, eta=h.eta,
+                      step=h.step, b_k=h.b_k, b_max=h.b_max, round_to=h.round_to, ddof=h.ddof, flags=flags)
+    gdtype = B.NT_BF16 if wl.grad_bytes == 2 else B.NT_F32
+    ws_flags = flags | (B.NT_WRITE_GBAR if mode == "clipped" else 0)
+    ws_bytes = B.normtest_workspace_bytes_for(gdtype, wl.J, wl.d, ws_flags)
+    workspace = torch.empty(max(ws_bytes, 8), dtype=torch.uint8, device=dev)
+    result = torch.empty(B.RESULT_BYTES, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+    layer_off = layer_out = None
+    if layers and mode == "adamw":
+        raise SystemExit("--layers needs a mode that computes the statistics")
+    if layers:
+        if layers < 0:
+            if not wl.meta.get("block_sizes"):
+                raise SystemExit("--layers -1 needs a workload with parameter blocks (gpt2_small, per_sample)")
+            sizes = wl.meta["block_sizes"]
+        else:
+            # sizes proportional to 1, 2, ..., N with odd remainders so that no boundary is aligned
+            tot = layers * (layers + 1) // 2
+            sizes = [max(1, (wl.d * (i + 1) // tot) | 1) for i in range(layers)]
+            sizes[-1] = wl.d - sum(sizes[:-1])
+            if sizes[-1] < 1:
+                raise SystemExit("--layers: too many layers for this d")
+        offs = [0]
+        for sz in sizes:
+            offs.append(offs[-1] + sz)
+        layer_off = torch.tensor(offs, dtype=torch.int64, device=dev)
+        layer_out = torch.empty(len(sizes) * B.LAYER_BYTES, dtype=torch.uint8, device=dev)
+
+    def step():
+        if mode == "clipped":
+            B.normtest_step_clipped(wl.grads, wl.w, wl.m, wl.v, gbar_buf, 1.0, hy, workspace=workspace,
+                                    result=result, stream=stream)
+        else:
+            B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hy, workspace=workspace, result=result, stream=stream)
+        if layer_off is not None:
+            B.normtest_layer_stats(wl.grads, layer_off, workspace, layers=layer_out, stream=stream)
+
+    if calib_copy_gib > 0:
+        src = torch.zeros(calib_copy_gib << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        B.normtest_calib_copy(dst, src, stream=stream)
+        torch.cuda.synchronize()
+        del src, dst
+    if graph:
+        # capture on a side stream (the library only enqueues kernels, so the step can be captured as it is)
+        eager_step = step
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            stream = side
+            eager_step()                       # warm-up outside the capture
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            eager_step()
+        stream = torch.cuda.current_stream()
+        step = g.replay
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        starts[i].record(stream)
+        step()
+        stops[i].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev_ms = sorted(s.elapsed_time(e) for s, e in zip(starts, stops))
+    res = B.read_result(result).as_dict()
+    # from 192 gradient bytes per coordinate on the library runs the full step as two passes
+    two_pass = mode == "full" and not one_pass and wl.J * wl.grad_bytes >= 192
+    alg_bytes = wl.d * bytes_per_param
+    ev_avg = sum(ev_ms) / len(ev_ms)
+    return {
+        "flags": flags, "bytes_per_param": bytes_per_param, "alg_bytes": alg_bytes, "two_pass": two_pass,
+        "wall_ms_per_step": wall * 1e3 / steps, "ev_avg": ev_avg, "ev_median": ev_ms[len(ev_ms) // 2],
+        "ev_min": ev_ms[0], "ev_max": ev_ms[-1], "result": res, "workspace_bytes": ws_bytes,
+        "layers": 0 if layer_off is None else layer_off.numel() - 1,
+        "route": MODE_TEXT["full_two_pass" if two_pass else mode],
+    }
+
+
+def config_entry(name: str, device: str, steps: int, warmup: int):
+    """One of the other workloads of the benchmark set, timed like the headline (full step, inputs resident)."""
+    import torch
+    wl = make_workload(name, device, 1.0)
+    t = time_steps(wl, "full", steps, warmup)
+    gbs = lambda ms: t["alg_bytes"] / (ms * 1e-3) / 1e9
+    entry = {
+        "workload": name, "J": wl.J, "d": wl.d, "grad_dtype": "bf16" if wl.grad_bytes == 2 else "f32",
+        "bytes_per_param": t["bytes_per_param"], "steps": steps, "warmup": warmup, "route": t["route"],
+        "ms_per_step": t["wall_ms_per_step"], "GBps": gbs(t["wall_ms_per_step"]),
+        "frac": gbs(t["wall_ms_per_step"]) / HBM_PEAK_GBS,
+        "params_per_s": wl.d / (t["wall_ms_per_step"] * 1e-3),
+        "event_ms": {"avg": t["ev_avg"], "median": t["ev_median"], "min": t["ev_min"], "max": t["ev_max"]},
+        "GBps_event_range": [gbs(t["ev_max"]), gbs(t["ev_min"])],
+        "result": {k: t["result"][k] for k in ("T", "pass", "next_b", "status")},
+    }
+    del wl
+    torch.cuda.empty_cache()
+    return entry
 
 
 STREAM_MATRIX = ([(0, r, w, False) for r in (0, 1, 2, 4, 8, 11) for w in (0, 1, 2, 3) if r + w > 0]
@@ -148,7 +307,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="flat_1p5b")
+    ap.add_argument("--workload", default=HEADLINE)
     ap.add_argument("--scale", type=float, default=1.0, help="shrink d (debugging only; the result is then not the headline)")
     ap.add_argument("--mode", default="full", choices=["full", "stats", "adamw", "clipped", "streams"],
                     help="full: the fused step (headline); stats / adamw: one half only; clipped: two-phase variant; "
@@ -168,6 +327,8 @@ def main():
     ap.add_argument("--one-pass", action="store_true",
                     help="keep the fused single pass where the library would take its two-pass route (many rows)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the other workloads of the benchmark set (they run after the headline by default)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 29)
     ap.add_argument("--calib-copy-gib", type=int, default=0,
                     help="also run the library's plain copy kernel once on this many GiB (known traffic for scaling byte counters)")
@@ -178,108 +339,27 @@ def main():
         return run_streams(args)
 
     import torch
-    from paper_2412_21124_amd import binding as B
 
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU: the library has no CPU path")
     dev = "cuda:0"
     torch.cuda.set_device(0)
     wl = make_workload(args.workload, dev, args.scale)
-    h = wl.hyper
-    flags = {"full": B.NT_DO_STATS | B.NT_DO_ADAMW, "stats": B.NT_DO_STATS, "adamw": B.NT_DO_ADAMW,
-             "clipped": B.NT_DO_STATS | B.NT_DO_ADAMW}[args.mode]
-    if args.workload == "fsdp_shard" and args.mode in ("full", "stats"):
-        flags |= B.NT_PARTIAL
-    if args.one_pass:
-        flags |= B.NT_ONE_PASS
-    # bytes per coordinate: J gradient reads; + read/write of w, m, v; the clipped variant also writes and re-reads gbar
-    bytes_per_param = wl.J * wl.grad_bytes + {"full": 24, "stats": 0, "adamw": 24, "clipped": 32}[args.mode]
-    gbar_buf = torch.empty(wl.d, dtype=torch.float32, device=dev) if args.mode == "clipped" else None
-    hy = B.make_hyper(lr=h.lr, beta1=h.beta1, beta2=h.beta2, eps=h.eps, weight_decay=h.weight_decay, eta=h.eta,
-                      step=h.step, b_k=h.b_k, b_max=h.b_max, round_to=h.round_to, ddof=h.ddof, flags=flags)
-    workspace = torch.empty(B.normtest_workspace_bytes(wl.J, wl.d), dtype=torch.uint8, device=dev)
-    result = torch.empty(B.RESULT_BYTES, dtype=torch.uint8, device=dev)
-    stream = torch.cuda.current_stream()
-    layer_off = layer_out = None
-    if args.layers and args.mode == "adamw":
-        raise SystemExit("--layers needs a mode that computes the statistics")
-    if args.layers:
-        if args.layers < 0:
-            if not wl.meta.get("block_sizes"):
-                raise SystemExit("--layers -1 needs a workload with parameter blocks (gpt2_small, per_sample)")
-            sizes = wl.meta["block_sizes"]
-        else:
-            # sizes proportional to 1, 2, ..., N with odd remainders so that no boundary is aligned
-            tot = args.layers * (args.layers + 1) // 2
-            sizes = [max(1, (wl.d * (i + 1) // tot) | 1) for i in range(args.layers)]
-            sizes[-1] = wl.d - sum(sizes[:-1])
-            if sizes[-1] < 1:
-                raise SystemExit("--layers: too many layers for this d")
-        offs = [0]
-        for sz in sizes:
-            offs.append(offs[-1] + sz)
-        layer_off = torch.tensor(offs, dtype=torch.int64, device=dev)
-        layer_out = torch.empty(len(sizes) * B.LAYER_BYTES, dtype=torch.uint8, device=dev)
-
-    def step():
-        if args.mode == "clipped":
-            B.normtest_step_clipped(wl.grads, wl.w, wl.m, wl.v, gbar_buf, 1.0, hy, workspace=workspace,
-                                    result=result, stream=stream)
-        else:
-            B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hy, workspace=workspace, result=result, stream=stream)
-        if layer_off is not None:
-            B.normtest_layer_stats(wl.grads, layer_off, workspace, layers=layer_out, stream=stream)
-
-    if args.calib_copy_gib > 0:
-        src = torch.zeros(args.calib_copy_gib << 28, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        B.normtest_calib_copy(dst, src, stream=stream)
-        torch.cuda.synchronize()
-        del src, dst
-    if args.graph:
-        # capture on a side stream (the library only enqueues kernels, so the step can be captured as it is)
-        eager_step = step
-        side = torch.cuda.Stream()
-        side.wait_stream(stream)
-        with torch.cuda.stream(side):
-            stream = side
-            eager_step()                       # warm-up outside the capture
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=side):
-            eager_step()
-        stream = torch.cuda.current_stream()
-        step = graph.replay
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-    stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        starts[i].record(stream)
-        step()
-        stops[i].record(stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ev_ms = [s.elapsed_time(e) for s, e in zip(starts, stops)]
-    res = B.read_result(result).as_dict()
-
-    # from 96 rows on the library runs the full step as two passes and asks for room for gbar in the workspace
-    two_pass = (args.mode == "full" and not args.one_pass and wl.J * wl.grad_bytes >= 192
-                and B.normtest_workspace_bytes(wl.J, wl.d) >= 4 * wl.d > 0)
-    alg_bytes = wl.d * bytes_per_param
-    ms_per_step = wall * 1e3 / args.steps
-    ev_avg = sum(ev_ms) / len(ev_ms)
-    value = alg_bytes / (wall / args.steps) / 1e9
-    achieved = alg_bytes / (ev_avg * 1e-3) / 1e9
+    t = time_steps(wl, args.mode, args.steps, args.warmup, one_pass=args.one_pass, layers=args.layers,
+                   graph=args.graph, calib_copy_gib=args.calib_copy_gib)
+    headline = (args.workload == HEADLINE and args.mode == "full" and args.scale == 1.0 and not args.layers
+                and not args.graph and not args.one_pass)
+    ms_per_step = t["wall_ms_per_step"]
+    value = t["alg_bytes"] / (ms_per_step * 1e-3) / 1e9
+    achieved = t["alg_bytes"] / (t["ev_avg"] * 1e-3) / 1e9
+    grad_dtype = "bf16" if wl.grad_bytes == 2 else "f32"
     out = {
-        "metric": "norm-test+AdamW step: achieved HBM GB/s (% of peak), params/s at d=1.5B J=8",
+        "metric": METRIC if headline else METRIC + " [this run: %s, mode %s%s]" % (
+            wl.name, args.mode, "" if args.scale == 1.0 else ", d scaled by %g" % args.scale),
         "value": value,
         "unit": "GB/s",
         "pct_of_peak": 100.0 * value / HBM_PEAK_GBS,
-        "params_per_s": wl.d / (wall / args.steps),
+        "params_per_s": wl.d / (ms_per_step * 1e-3),
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
@@ -288,38 +368,41 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
+        "dtype_note": "arithmetic type: fp32 per coordinate, fp64 accumulation; gradients are stored as %s, w/m/v as fp32" % grad_dtype,
         "data": "synthetic",
         "config": {
             "workload": "%s: J=%d %s gradient rows, d=%d, fp32 w/m/v, %s" % (
-                wl.name, wl.J, "bf16" if wl.grad_bytes == 2 else "fp32", wl.d,
-                {"full": ("statistics + decision, then AdamW from the stored mean (the library's two-pass route for many rows)"
-                          if two_pass else "stats+decision+fused AdamW in one pass"),
-                 "stats": "statistics and decision only",
-                 "adamw": "mean + AdamW only (test skipped)",
-                 "clipped": "two-phase gradient-clipped step (stats+gbar, then AdamW)"}[args.mode]),
+                wl.name, wl.J, "bf16" if wl.grad_bytes == 2 else "fp32", wl.d, t["route"]),
             "mode": args.mode,
-            "J": wl.J, "d": wl.d, "grad_dtype": "bf16" if wl.grad_bytes == 2 else "f32",
-            "bytes_per_param": bytes_per_param, "flags": flags,
-            "layers": 0 if layer_off is None else layer_off.numel() - 1,
+            "J": wl.J, "d": wl.d, "grad_dtype": grad_dtype,
+            "bytes_per_param": t["bytes_per_param"], "flags": t["flags"],
+            "layers": t["layers"],
             "graph_replay": bool(args.graph),
         },
-        "result": {k: res[k] for k in ("T", "pass", "next_b", "status")},
+        "result": {k: t["result"][k] for k in ("T", "pass", "next_b", "status")},
         "roofline": {
             "bound": "hbm",
-            "kernel": "k_step (the fused streaming kernel; the HIP events bracket the whole step, i.e. also the two reduction kernels, about 15 us)",
+            "kernel": "k_step (the fused streaming kernel; the HIP events bracket the whole step, i.e. also the finalize kernel, a few us)",
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "launch_ms_avg": ev_avg,
-            "launch_ms_median": sorted(ev_ms)[len(ev_ms) // 2],
-            "launch_ms_min": min(ev_ms),
-            "algorithmic_bytes": alg_bytes,
-            "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, args.mode)) if (args.scale == 1.0 and not args.layers) else None,
+            "launch_ms_avg": t["ev_avg"],
+            "launch_ms_median": t["ev_median"],
+            "launch_ms_min": t["ev_min"],
+            "algorithmic_bytes": t["alg_bytes"],
+            # counter-measured HBM bytes per step, quoted from the tracked profile of this kernel source (null if the
+            # source has changed since that run, or if this is not a profiled configuration)
+            "traffic": (traffic_from_profile(wl.name, args.mode)
+                        if (args.scale == 1.0 and not args.layers and not args.one_pass) else None),
         },
     }
     if not args.no_cpu_baseline and args.mode == "full":
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample)
+    if headline and not args.no_configs:
+        del wl
+        torch.cuda.empty_cache()
+        out["configs"] = [config_entry(name, dev, 200 if name == "tiny" else 20, 5) for name in OTHER_CONFIGS]
     print(json.dumps(out))
 
 

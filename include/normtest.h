@@ -42,7 +42,7 @@ enum {
   NT_DO_ADAMW = 2u,   /* update w, m, v in place with AdamW on gbar                              */
   NT_PARTIAL = 4u,    /* FSDP shard: stop at the additive sums A, B, C; decide in normtest_combine */
   NT_WRITE_GBAR = 8u, /* also store gbar (fp32[d]) to gbar_out                                   */
-  NT_COORD_TEST = 16u, /* also count the coordinates that fail the coordinate-wise form of the test */
+  NT_COORD_TEST = 16u, /* also the coordinate-wise form of the test: count of failing coordinates, largest ratio */
   NT_ONE_PASS = 32u   /* keep the full step in one fused pass even for many rows (see normtest_workspace_bytes): */
                       /* same bits, 8 bytes per coordinate less traffic, measured slower from 96 bf16 / 48 fp32 rows */
 };
@@ -105,6 +105,10 @@ typedef struct {
                            /* test, decided per coordinate in fp32; additive over shards; -1 if not requested        */
   int32_t pass;            /* 1 iff not (T > b_k)                                                                 */
   uint32_t status;         /* NT_STATUS_* bits                                                                    */
+  double coord_max_ratio;  /* NT_COORD_TEST: largest Var_i / (eta^2 b_k gbar_i^2) over the coordinates (a coordinate */
+                           /* fails iff its ratio exceeds 1), formed per coordinate in fp32; 0 for a coordinate       */
+                           /* without spread, +inf for spread around a zero mean (the rows cancel exactly); the       */
+                           /* largest over shards is the largest of the shards' values; -1 if not requested           */
 } nt_result;
 
 /* One layer (a block of consecutive coordinates) of normtest_layer_stats. */
@@ -117,6 +121,7 @@ typedef struct {
   int64_t coord_fail;    /* failing coordinates in the layer if the step ran with NT_COORD_TEST, else -1         */
   int32_t pass;          /* 1 iff not (T > b_k)                                                                  */
   uint32_t status;       /* NT_STATUS_NONFINITE | ZERO_GRAD_NORM | T_SATURATED | NO_STATS | BAD_RANGE            */
+  double coord_max_ratio; /* largest coordinate-wise ratio in the layer (see nt_result), else -1                 */
 } nt_layer_stats;
 
 /* Alignment, in coordinates, of the partial-sum tiles for J rows (every tile size divides it).  Results are
@@ -125,17 +130,23 @@ typedef struct {
 int64_t normtest_tile_coords(int64_t J);
 
 /* Bytes of device workspace normtest_step needs for J rows of d coordinates (0 if J or d is invalid): a few
- * doubles per tile, and from 48 rows on also 4 d bytes, because with 192 or more gradient bytes per coordinate
+ * doubles per tile (and a 256-byte record), and from 48 rows on also 4 d bytes, because with 192 or more gradient bytes per coordinate
  * (96 bf16 or 48 fp32 rows) the full step runs as two passes (statistics that store gbar, then AdamW from
  * gbar: faster there, same bits) and keeps gbar in the workspace unless NT_WRITE_GBAR names a buffer for it. */
 size_t normtest_workspace_bytes(int64_t J, int64_t d);
+
+/* The same for a known gradient dtype and nt_hyper.flags: what normtest_step (and the other step entry points)
+ * check for exactly that call.  Never more than normtest_workspace_bytes(J, d), which covers every dtype and
+ * flag: the 4 d bytes for gbar are needed only by a full step (NT_DO_STATS | NT_DO_ADAMW) of at least 192
+ * gradient bytes per coordinate without NT_ONE_PASS and without NT_WRITE_GBAR.  0 if an argument is invalid. */
+size_t normtest_workspace_bytes_for(nt_dtype gdtype, int64_t J, int64_t d, uint32_t flags);
 
 /*
  * One step.  Row j of the gradients starts at element j*ld of `grads` (device; ld >= d; elements of
  * type gdtype).  w, m, v: device fp32[d], updated in place when NT_DO_ADAMW (may be NULL otherwise).
  * gbar_out: device fp32[d], written when NT_WRITE_GBAR, else ignored.  hyper, shard: host pointers,
  * read before returning (shard may be NULL).  workspace: device scratch of at least
- * normtest_workspace_bytes(J, d) bytes, 8-byte aligned; contents irrelevant before; afterwards it holds the
+ * normtest_workspace_bytes_for(gdtype, J, d, hyper->flags) bytes, 8-byte aligned; contents irrelevant before; afterwards it holds the
  * call's per-tile partial sums in a private format, which only normtest_layer_stats reads.
  * result_dev: device or pinned-host nt_result, 8-byte aligned, written by the last kernel.
  * hip_stream: a hipStream_t (NULL = the default stream).
@@ -171,8 +182,8 @@ int normtest_step_rows(const void* const* grad_rows_dev, nt_dtype gdtype, int64_
  * serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results (bit for bit) as
  * normtest_step, without `workspace`: the tile partial sums and the record of the step go to a 16 MiB array that
  * the library holds in each GPU's memory (a static __device__ array; no hipMalloc, hipFree or other allocating
- * call is made here, on any path).  Limits: d <= normtest_static_max_coords(J) (about 2.1e9 coordinates up to
- * 16 rows, 1.0e9 beyond), else NT_ERR_TOO_LARGE and nothing is enqueued.  With many rows (96 bf16 / 48 fp32 or
+ * call is made here, on any path).  Limits: d <= normtest_static_max_coords(J) (about 1.7e9 coordinates up to
+ * 16 rows, 0.86e9 beyond), else NT_ERR_TOO_LARGE and nothing is enqueued.  With many rows (96 bf16 / 48 fp32 or
  * more) normtest_step's two-pass route needs 4 d bytes for gbar: here it is taken only when NT_WRITE_GBAR names a
  * gbar_out buffer, otherwise the single fused pass runs (same bits).  The array keeps the last call's contents;
  * nothing in it has to be cleared between calls.  All calls on one GPU share it: two calls that overlap in time
@@ -193,7 +204,8 @@ int64_t normtest_static_max_coords(int64_t J);
  * gradients of the shards are concatenated, so A, B, C add.  Sums (with their low parts) are added in
  * shard order in double-double arithmetic, then the same decision as in normtest_step is taken in
  * fp64 with `hyper` (eta, b_k, b_max, round_to, ddof; flags ignored).  Status bits of the parts are
- * OR-ed (minus PARTIAL_ONLY).  Returns NT_OK or NT_ERR_BAD_ARG.
+ * OR-ed (minus PARTIAL_ONLY); coord_fail adds up and coord_max_ratio is the largest of the parts (both -1 if a part
+ * lacks them).  Returns NT_OK or NT_ERR_BAD_ARG.
  */
 int normtest_combine(const nt_result* partials, int32_t n, int64_t J, const nt_hyper* hyper,
                      nt_result* out);

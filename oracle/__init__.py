@@ -246,5 +246,6 @@ def layer_stats(G: np.ndarray, offsets, eta: float, b_k: int, ddof: int = 1, ban
         row = dict(A=A, B=B, C=C, n=hi - lo, dec=decide(A, B, C, J, eta, b_k, 0, 1, ddof))
         if band is not None:
             row["coord"] = coord_test(G[:, lo:hi], eta, b_k, ddof, band)
+            row["coord_max_ratio"] = coord_max_ratio(G[:, lo:hi], eta, b_k, ddof)
         out.append(row)
     return out

@@ -47,7 +47,8 @@ class nt_result(ctypes.Structure):
         ("A", ctypes.c_double), ("B", ctypes.c_double), ("C", ctypes.c_double),
         ("A_lo", ctypes.c_double), ("B_lo", ctypes.c_double), ("C_lo", ctypes.c_double),
         ("gbar_sq", ctypes.c_double), ("var_l1", ctypes.c_double), ("T", ctypes.c_double),
-        ("clip_coef", ctypes.c_double), ("next_b", ctypes.c_int64), ("coord_fail", ctypes.c_int64), ("pass_", ctypes.c_int32), ("status", ctypes.c_uint32),
+        ("clip_coef", ctypes.c_double), ("next_b", ctypes.c_int64), ("coord_fail", ctypes.c_int64),
+        ("pass_", ctypes.c_int32), ("status", ctypes.c_uint32), ("coord_max_ratio", ctypes.c_double),
     ]
 
     def as_dict(self) -> dict:
@@ -64,6 +65,7 @@ class nt_layer_stats(ctypes.Structure):
         ("A", ctypes.c_double), ("B", ctypes.c_double), ("C", ctypes.c_double),
         ("gbar_sq", ctypes.c_double), ("var_l1", ctypes.c_double), ("T", ctypes.c_double),
         ("n", ctypes.c_int64), ("coord_fail", ctypes.c_int64), ("pass_", ctypes.c_int32), ("status", ctypes.c_uint32),
+        ("coord_max_ratio", ctypes.c_double),
     ]
 
     def as_dict(self) -> dict:
@@ -94,6 +96,8 @@ def lib(path: Optional[str] = None):
         L.normtest_tile_coords.restype = i64
         L.normtest_workspace_bytes.argtypes = [i64, i64]
         L.normtest_workspace_bytes.restype = ctypes.c_size_t
+        L.normtest_workspace_bytes_for.argtypes = [ctypes.c_int, i64, i64, ctypes.c_uint32]
+        L.normtest_workspace_bytes_for.restype = ctypes.c_size_t
         L.normtest_step.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp,
                                     ctypes.POINTER(nt_hyper), ctypes.POINTER(nt_shard_info),
                                     vp, ctypes.c_size_t, vp, vp]
@@ -147,6 +151,10 @@ def normtest_workspace_bytes(J: int, d: int) -> int:
     return int(lib().normtest_workspace_bytes(J, d))
 
 
+def normtest_workspace_bytes_for(gdtype: int, J: int, d: int, flags: int) -> int:
+    return int(lib().normtest_workspace_bytes_for(gdtype, J, d, flags))
+
+
 def make_hyper(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, eta=0.1, step=1, b_k=1,
                b_max=0, round_to=1, ddof=1, flags=NT_DO_STATS | NT_DO_ADAMW) -> nt_hyper:
     return nt_hyper(lr, beta1, beta2, eps, weight_decay, eta, step, b_k, b_max, round_to, ddof, flags)
@@ -164,6 +172,31 @@ def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
+def _matrix_layout(grads: torch.Tensor, d: Optional[int], where: str):
+    """(J, d, ld, device) of a (J, ld) gradient tensor whose rows are the gradient vectors."""
+    if grads.dim() != 2 or (grads.shape[1] > 1 and grads.stride(1) != 1):
+        raise ValueError("grads must be (J, ld) with a contiguous last axis")
+    J = grads.shape[0]
+    ld = grads.stride(0) if J > 1 else grads.shape[1]
+    d = grads.shape[1] if d is None else d
+    if grads.device.type != "cuda":
+        raise ValueError("%s needs device tensors; there is no CPU path" % where)
+    return J, d, ld, grads.device
+
+
+def _check_vectors(dev, d: int, required: bool = False, **tensors):
+    """w, m, v, gbar: contiguous float32 vectors of at least d elements on the gradients' device."""
+    for name, t in tensors.items():
+        if t is None and not required:
+            continue
+        if t is None or t.dtype != torch.float32 or t.device != dev or not t.is_contiguous() or t.numel() < d:
+            raise ValueError("%s must be a contiguous float32 tensor of >= d elements on %s" % (name, dev))
+
+
+def _nbytes(t: torch.Tensor) -> int:
+    return t.numel() * t.element_size()
+
+
 def normtest_step(grads: torch.Tensor, w: Optional[torch.Tensor], m: Optional[torch.Tensor],
                   v: Optional[torch.Tensor], hyper: nt_hyper, *, d: Optional[int] = None,
                   shard: Optional[nt_shard_info] = None, gbar_out: Optional[torch.Tensor] = None,
@@ -175,19 +208,9 @@ def normtest_step(grads: torch.Tensor, w: Optional[torch.Tensor], m: Optional[to
     grads: (J, ld) device tensor whose rows are the gradient vectors (last axis contiguous); the first
     d columns are used (default: all).  w, m, v: float32 device vectors of length >= d, updated in place.
     """
-    if grads.dim() != 2 or (grads.shape[1] > 1 and grads.stride(1) != 1):
-        raise ValueError("grads must be (J, ld) with a contiguous last axis")
-    J = grads.shape[0]
-    ld = grads.stride(0) if J > 1 else grads.shape[1]
-    d = grads.shape[1] if d is None else d
-    dev = grads.device
-    if dev.type != "cuda":
-        raise ValueError("normtest_step needs device tensors; there is no CPU path")
-    for name, t in (("w", w), ("m", m), ("v", v), ("gbar_out", gbar_out)):
-        if t is not None:
-            if t.dtype != torch.float32 or t.device != dev or not t.is_contiguous() or t.numel() < d:
-                raise ValueError("%s must be a contiguous float32 tensor of >= d elements on %s" % (name, dev))
-    need = normtest_workspace_bytes(J, d)
+    J, d, ld, dev = _matrix_layout(grads, d, "normtest_step")
+    _check_vectors(dev, d, w=w, m=m, v=v, gbar_out=gbar_out)
+    need = normtest_workspace_bytes_for(_gdtype(grads), J, d, hyper.flags)
     own_workspace = workspace is None
     if own_workspace:
         workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=dev)
@@ -199,7 +222,7 @@ def normtest_step(grads: torch.Tensor, w: Optional[torch.Tensor], m: Optional[to
         rc = lib().normtest_step(_ptr(grads), _gdtype(grads), J, d, ld, _ptr(w), _ptr(m), _ptr(v),
                                  _ptr(gbar_out), ctypes.byref(hyper),
                                  ctypes.byref(shard) if shard is not None else None,
-                                 _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                 _ptr(workspace), _nbytes(workspace),
                                  _ptr(result), ctypes.c_void_p(stream.cuda_stream))
     if rc != NT_OK:
         raise NormtestError(rc, "normtest_step")
@@ -218,19 +241,9 @@ def normtest_step_static(grads: torch.Tensor, w: Optional[torch.Tensor], m: Opti
                          stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
     """normtest_step without a workspace (the library's built-in scratch) and without any allocation here:
     the caller passes the device tensor for the nt_result."""
-    if grads.dim() != 2 or (grads.shape[1] > 1 and grads.stride(1) != 1):
-        raise ValueError("grads must be (J, ld) with a contiguous last axis")
-    J = grads.shape[0]
-    ld = grads.stride(0) if J > 1 else grads.shape[1]
-    d = grads.shape[1] if d is None else d
-    dev = grads.device
-    if dev.type != "cuda":
-        raise ValueError("normtest_step_static needs device tensors; there is no CPU path")
-    for name, t in (("w", w), ("m", m), ("v", v), ("gbar_out", gbar_out)):
-        if t is not None:
-            if t.dtype != torch.float32 or t.device != dev or not t.is_contiguous() or t.numel() < d:
-                raise ValueError("%s must be a contiguous float32 tensor of >= d elements on %s" % (name, dev))
-    if result is None or result.device != dev or result.numel() * result.element_size() < RESULT_BYTES:
+    J, d, ld, dev = _matrix_layout(grads, d, "normtest_step_static")
+    _check_vectors(dev, d, w=w, m=m, v=v, gbar_out=gbar_out)
+    if result is None or result.device != dev or _nbytes(result) < RESULT_BYTES:
         raise ValueError("result must be a device tensor of at least RESULT_BYTES bytes")
     if stream is None:
         stream = torch.cuda.current_stream(dev)
@@ -265,15 +278,13 @@ def normtest_step_rows(rows, w: Optional[torch.Tensor], m: Optional[torch.Tensor
     for r in rows:
         if r.dtype != rows[0].dtype or r.device != dev or r.dim() != 1 or not r.is_contiguous() or r.numel() < d:
             raise ValueError("rows must be contiguous 1-D tensors of one dtype and >= d elements on %s" % dev)
-    for name, t in (("w", w), ("m", m), ("v", v), ("gbar_out", gbar_out)):
-        if t is not None:
-            if t.dtype != torch.float32 or t.device != dev or not t.is_contiguous() or t.numel() < d:
-                raise ValueError("%s must be a contiguous float32 tensor of >= d elements on %s" % (name, dev))
+    _check_vectors(dev, d, w=w, m=m, v=v, gbar_out=gbar_out)
     if table is None:
         table = make_row_table(rows)
     own_workspace = workspace is None
     if own_workspace:
-        workspace = torch.empty(max(normtest_workspace_bytes(J, d), 8), dtype=torch.uint8, device=dev)
+        need = normtest_workspace_bytes_for(_gdtype(rows[0]), J, d, hyper.flags)
+        workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=dev)
     if result is None:
         result = torch.empty(RESULT_BYTES, dtype=torch.uint8, device=dev)
     if stream is None:
@@ -281,7 +292,7 @@ def normtest_step_rows(rows, w: Optional[torch.Tensor], m: Optional[torch.Tensor
     with torch.cuda.device(dev):
         rc = lib().normtest_step_rows(_ptr(table), _gdtype(rows[0]), J, d, _ptr(w), _ptr(m), _ptr(v), _ptr(gbar_out),
                                       ctypes.byref(hyper), ctypes.byref(shard) if shard is not None else None,
-                                      _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                      _ptr(workspace), _nbytes(workspace),
                                       _ptr(result), ctypes.c_void_p(stream.cuda_stream))
     if rc != NT_OK:
         raise NormtestError(rc, "normtest_step_rows")
@@ -297,20 +308,12 @@ def normtest_step_clipped(grads: torch.Tensor, w: torch.Tensor, m: torch.Tensor,
                           result: Optional[torch.Tensor] = None,
                           stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
     """Two-phase gradient-clipped step (statistics + gbar, then AdamW on the clipped gbar); see normtest_step."""
-    if grads.dim() != 2 or (grads.shape[1] > 1 and grads.stride(1) != 1):
-        raise ValueError("grads must be (J, ld) with a contiguous last axis")
-    J = grads.shape[0]
-    ld = grads.stride(0) if J > 1 else grads.shape[1]
-    d = grads.shape[1] if d is None else d
-    dev = grads.device
-    if dev.type != "cuda":
-        raise ValueError("normtest_step_clipped needs device tensors; there is no CPU path")
-    for name, t in (("w", w), ("m", m), ("v", v), ("gbar_buf", gbar_buf)):
-        if t is None or t.dtype != torch.float32 or t.device != dev or not t.is_contiguous() or t.numel() < d:
-            raise ValueError("%s must be a contiguous float32 tensor of >= d elements on %s" % (name, dev))
+    J, d, ld, dev = _matrix_layout(grads, d, "normtest_step_clipped")
+    _check_vectors(dev, d, required=True, w=w, m=m, v=v, gbar_buf=gbar_buf)
     own_workspace = workspace is None
     if own_workspace:
-        workspace = torch.empty(max(normtest_workspace_bytes(J, d), 8), dtype=torch.uint8, device=dev)
+        need = normtest_workspace_bytes_for(_gdtype(grads), J, d, hyper.flags | NT_WRITE_GBAR)
+        workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=dev)
     if result is None:
         result = torch.empty(RESULT_BYTES, dtype=torch.uint8, device=dev)
     if stream is None:
@@ -319,7 +322,7 @@ def normtest_step_clipped(grads: torch.Tensor, w: torch.Tensor, m: torch.Tensor,
         rc = lib().normtest_step_clipped(_ptr(grads), _gdtype(grads), J, d, ld, _ptr(w), _ptr(m), _ptr(v),
                                          _ptr(gbar_buf), float(max_norm), ctypes.byref(hyper),
                                          ctypes.byref(shard) if shard is not None else None,
-                                         _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                         _ptr(workspace), _nbytes(workspace),
                                          _ptr(result), ctypes.c_void_p(stream.cuda_stream))
     if rc != NT_OK:
         raise NormtestError(rc, "normtest_step_clipped")
@@ -336,9 +339,7 @@ def normtest_adamw_gbar(gbar: torch.Tensor, w: torch.Tensor, m: torch.Tensor, v:
     dev = gbar.device
     if dev.type != "cuda":
         raise ValueError("normtest_adamw_gbar needs device tensors; there is no CPU path")
-    for name, t in (("gbar", gbar), ("w", w), ("m", m), ("v", v)):
-        if t.dtype != torch.float32 or t.device != dev or not t.is_contiguous() or t.numel() < d:
-            raise ValueError("%s must be a contiguous float32 tensor of >= d elements on %s" % (name, dev))
+    _check_vectors(dev, d, required=True, gbar=gbar, w=w, m=m, v=v)
     if stream is None:
         stream = torch.cuda.current_stream(dev)
     with torch.cuda.device(dev):
@@ -361,11 +362,7 @@ def normtest_layer_stats(grads, layer_offsets: torch.Tensor, workspace: torch.Te
     if dev.type != "cuda":
         raise ValueError("normtest_layer_stats needs device tensors; there is no CPU path")
     if rows is None:
-        if grads.dim() != 2 or (grads.shape[1] > 1 and grads.stride(1) != 1):
-            raise ValueError("grads must be (J, ld) with a contiguous last axis")
-        J = grads.shape[0]
-        ld = grads.stride(0) if J > 1 else grads.shape[1]
-        d = grads.shape[1] if d is None else d
+        J, d, ld, _ = _matrix_layout(grads, d, "normtest_layer_stats")
         gptr = _ptr(grads)
     else:
         J = len(rows)
@@ -378,11 +375,11 @@ def normtest_layer_stats(grads, layer_offsets: torch.Tensor, workspace: torch.Te
             or not layer_offsets.is_contiguous() or layer_offsets.numel() < 2):
         raise ValueError("layer_offsets must be a contiguous int64 device vector of L+1 >= 2 entries")
     L = layer_offsets.numel() - 1
-    if workspace.device != dev or workspace.numel() * workspace.element_size() < normtest_workspace_bytes(J, d):
+    if workspace.device != dev or _nbytes(workspace) < normtest_workspace_bytes_for(_gdtype(first), J, d, NT_DO_STATS):
         raise ValueError("workspace must be the device workspace of the preceding step")
     if layers is None:
         layers = torch.empty(L * LAYER_BYTES, dtype=torch.uint8, device=dev)
-    elif layers.numel() * layers.element_size() < L * LAYER_BYTES:
+    elif _nbytes(layers) < L * LAYER_BYTES:
         raise ValueError("layers must hold L * sizeof(nt_layer_stats) bytes")
     if stream is None:
         stream = torch.cuda.current_stream(dev)

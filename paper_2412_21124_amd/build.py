@@ -19,10 +19,8 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(out: str = LIB, defines: dict | None = None, quiet: bool = True) -> str:
+def build_library(out: str = LIB, quiet: bool = True) -> str:
     cmd = ["hipcc", *HIPCC_FLAGS, "-I", INCLUDE]
-    for k, val in (defines or {}).items():
-        cmd.append("-D%s=%s" % (k, val))
     tmp = out + ".tmp.%d" % os.getpid()
     cmd += ["-o", tmp, SRC]
     res = subprocess.run(cmd, capture_output=True, text=True)

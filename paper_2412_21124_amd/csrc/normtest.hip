@@ -1,12 +1,12 @@
 // libnormtest: norm-test statistics pass fused with AdamW, hand-written for gfx950 (MI355X).
 //
 // One streaming kernel (k_step) reads the J gradient rows and w, m, v once, writes w, m, v once and
-// leaves four fp64 partial sums per fixed-size tile of coordinates (A, B, C and the count of
-// coordinates failing the coordinate-wise form of the test); k_reduce_groups / k_finalize then add the
-// tile partials in double-double arithmetic and take Alg. 1's decision on the device.  The partials stay
-// in the caller's workspace behind a small record of the step, from which k_layer_stats can regroup them
-// into a per-layer table.  k_adamw_gbar is the second phase of the gradient-clipped variant.  The path is
-// bound by HBM bandwidth (about two lane-operations per byte), so there is no MFMA here: the work is
+// leaves five fp64 values per fixed-size tile of coordinates (the sums A, B, C, the count of coordinates
+// failing the coordinate-wise form of the test, and their largest ratio); k_reduce_groups / k_finalize then add
+// the tile partials in double-double arithmetic and take Alg. 1's decision on the device.  The partials stay in the caller's workspace
+// behind a small record of the step, from which k_layer_stats can regroup them into a per-layer table.
+// k_adamw_gbar is the second phase of the gradient-clipped variant and of the many-row two-pass route.  The
+// path is bound by HBM bandwidth (about two lane-operations per byte), so there is no MFMA here: the work is
 // fully coalesced 8- and 16-byte accesses, fp32 per-coordinate arithmetic, fp64 accumulation and wave64
 // shuffle reductions.  Launch shapes (block size, sweeps per tile) differ per class of call and were
 // chosen by measurement; see tile_cfg().
@@ -29,86 +29,39 @@
 
 #include "normtest.h"
 
-#ifndef NT_BLOCK
-#define NT_BLOCK 1024         // threads per block, J <= 16, fused step and AdamW-only
-#endif
-#ifndef NT_ITERS
-#define NT_ITERS 1            // block sweeps per partial-sum tile for that class
-#endif
-#ifndef NT_BLOCK_STATS
-#define NT_BLOCK_STATS 512    // threads per block, J <= 16, statistics only: read-only, few bytes per lane, so
-#endif                        // smaller blocks that each walk a longer tile measured best
-#ifndef NT_ITERS_STATS
-#define NT_ITERS_STATS 8
-#endif
-#ifndef NT_BLOCK_STATS_GBAR
-#define NT_BLOCK_STATS_GBAR 512 // statistics that also store gbar (phase 1 of the clipped variant): one write stream
-#endif                          // changes the optimum to shorter tiles
-#ifndef NT_ITERS_STATS_GBAR
-#define NT_ITERS_STATS_GBAR 2
-#endif
-#ifndef NT_BLOCK_ADAMW
-#define NT_BLOCK_ADAMW 1024   // threads per block, J <= 16, AdamW only (test skipped)
-#endif
-#ifndef NT_ITERS_ADAMW
+// Launch shapes, chosen by measurement on MI355X (block size, block sweeps per partial-sum tile).
+#define NT_BLOCK 1024            // J <= 16, fused step: one sweep of a large block per tile
+#define NT_ITERS 1
+#define NT_BLOCK_STATS 512       // J <= 16, statistics only: read-only and few bytes per lane, so smaller blocks
+#define NT_ITERS_STATS 8         // that each walk a longer tile
+#define NT_BLOCK_STATS_GBAR 512  // statistics that also store gbar (phase 1 of the clipped variant): one write
+#define NT_ITERS_STATS_GBAR 2    // stream moves the optimum to shorter tiles
+#define NT_BLOCK_ADAMW 1024      // J <= 16, AdamW only (test skipped)
 #define NT_ITERS_ADAMW 1
-#endif
-#ifndef NT_BLOCK_LARGE
-#define NT_BLOCK_LARGE 256    // threads per block, J > 16 (rows are walked inside each sweep), all modes
-#endif
-#ifndef NT_ITERS_LARGE
+#define NT_BLOCK_LARGE 256       // J > 16 (rows are walked inside each sweep), all modes
 #define NT_ITERS_LARGE 2
-#endif
-#ifndef NT_BLOCKS_PER_CU
-#define NT_BLOCKS_PER_CU 4096 // grid = min(tiles, CUs * this); blocks stride over tiles beyond that
-#endif
-#ifndef NT_NT_GRAD
-#define NT_NT_GRAD 1          // nontemporal hint on gradient loads
-#endif
-#ifndef NT_NT_STATE
-#define NT_NT_STATE 1         // nontemporal hint on w, m, v loads
-#endif
-#ifndef NT_NT_STORE
-#define NT_NT_STORE 1         // nontemporal hint on stores
-#endif
-#ifndef NT_NT_COPY
-#define NT_NT_COPY 1          // nontemporal hint in the calibration copy kernel
-#endif
-#ifndef NT_ADAMW_BARRIER
-#define NT_ADAMW_BARRIER 1    // AdamW-only tiles end with a block barrier like the other modes (measured +2 %)
-#endif
-#ifndef NT_UNROLL
-#define NT_UNROLL 1           // unroll factor of the per-tile sweep loop
-#endif
-#ifndef NT_WAVES_PER_EU
-#define NT_WAVES_PER_EU 1     // occupancy the register allocator must leave room for (waves per SIMD)
-#endif
+#define NT_BLOCKS_PER_CU 4096    // grid = min(tiles, CUs * this); blocks stride over tiles beyond that
 
 #define NT_VEC 4              // coordinates per lane and sweep: 16-byte fp32 accesses, 8-byte bf16 row loads
-#define NT_TILE_MAX 16384      // every tile size divides this: the alignment that keeps shard results bit-identical
-#ifndef NT_AUX_BLOCK
-#define NT_AUX_BLOCK 1024     // threads per block of the AdamW-from-gbar and copy kernels
-#endif
-
-#define NT_PRAGMA_(x) _Pragma(#x)
-#define NT_PRAGMA_UNROLL(n) NT_PRAGMA_(unroll n)
+#define NT_TILE_MAX 16384     // every tile size divides this: the alignment that keeps shard results bit-identical
+#define NT_AUX_BLOCK 1024     // threads per block of the AdamW-from-gbar, copy and yardstick kernels
 
 #define NT_JCHUNK 16          // up to this many rows a coordinate's values are all held in registers
-#ifndef NT_MCHUNK
 #define NT_MCHUNK 16          // beyond that, rows are walked this many at a time (2 .. NT_JCHUNK + 1; 16 measured best)
-#endif
 #define NT_ROUND_TO_MAX (1ll << 31)  // bound on nt_hyper.round_to that keeps the rounding chain inside int64
 #define NT_FIN_THREADS 1024
-#define NT_NV 4                // values per tile partial: A, B, C and the count of failing coordinates
+#define NT_FIN_SMALL 1024       // up to this many records the finalize kernel runs with 256 threads
+#define NT_NSUM 4              // summed values per tile partial: A, B, C and the count of failing coordinates
+#define NT_NV 5                // values per tile partial: the sums, then the largest coordinate-wise ratio
 #define NT_GROUP_THREADS 256   // first-stage reduction: threads per block
 #define NT_GROUP_TILES 2048    // ... and tile partials per block
-#define NT_DIRECT_TILES 4096   // up to this many tiles the finalize kernel reads the tile partials itself
-#define NT_WS_HEADER 16        // doubles in front of the tile partials: a record of the step that wrote them
+#define NT_DIRECT_TILES 4096   // up to this many tiles one block reads the tile partials itself
+#define NT_WS_HEADER 32        // doubles in front of the tile partials: a record of the step that wrote them
+#define NT_WS_CONTROL 24       // ... of which this one starts the words the step's kernels hand to each other
 #define NT_WS_MAGIC 0x4e54574f524b5350ll
 #define NT_LAYER_THREADS 1024  // per-layer kernel: one block per layer
-#ifndef NT_TWO_PHASE_ROW_BYTES
 #define NT_TWO_PHASE_ROW_BYTES 192  // from this many gradient bytes per coordinate on (96 bf16 or 48 fp32 rows) the
-#endif                              // full step runs as statistics + gbar, then AdamW from gbar
+                                    // full step runs as statistics + gbar, then AdamW from gbar
 
 // Scratch of normtest_step_static: the per-tile partial sums and the record of the step, for callers that
 // cannot hand over (or allocate) a workspace.  One copy per GPU, held until the process ends.
@@ -135,7 +88,7 @@ struct F32 {
   static constexpr int VEC = 4;
   static constexpr int ESIZE = 4;
   typedef u32x4 raw_t;
-  __device__ static inline raw_t ldraw(const void* p) { return ld_vec<NT_NT_GRAD, raw_t>(p); }
+  __device__ static inline raw_t ldraw(const void* p) { return ld_vec<true, raw_t>(p); }
   __device__ static inline float val(const raw_t& r, int e) { return __builtin_bit_cast(float, (uint32_t)r[e]); }
   __device__ static inline float ld(const void* base, int64_t i) { return ((const float*)base)[i]; }
 };
@@ -144,7 +97,7 @@ struct BF16 {
   static constexpr int VEC = 4;
   static constexpr int ESIZE = 2;
   typedef u32x2 raw_t;
-  __device__ static inline raw_t ldraw(const void* p) { return ld_vec<NT_NT_GRAD, raw_t>(p); }
+  __device__ static inline raw_t ldraw(const void* p) { return ld_vec<true, raw_t>(p); }
   // bfloat16 is the high half of a binary32: widening is a shift or a mask
   __device__ static inline float val(const raw_t& r, int e) {
     uint32_t u = r[e >> 1];
@@ -174,6 +127,11 @@ struct StepParams {
   float coord_thr;   // eta^2 b_k (J - ddof) when the coordinate-wise count is wanted, else negative
 };
 
+// Words of the workspace record that kernels of one step hand to each other.
+struct WsControl {
+  unsigned int rows_aligned;  // pointer-table calls: 1 if every row pointer is 16-byte aligned
+};
+
 // Start of gradient row j: base + j*ld elements, or the j-th entry of the caller's pointer table.
 template <class GT, bool TABLE>
 __device__ inline const char* row_base(const StepParams& p, int j) {
@@ -183,14 +141,8 @@ __device__ inline const char* row_base(const StepParams& p, int j) {
     return (const char*)p.grads + (int64_t)j * p.ld * GT::ESIZE;
 }
 
-__device__ inline u32x4 ld16(const void* p) { return ld_vec<NT_NT_STATE, u32x4>(p); }
-__device__ inline void st16(void* p, f32x4 x) {
-#if NT_NT_STORE
-  __builtin_nontemporal_store(x, (f32x4*)p);
-#else
-  *(f32x4*)p = x;
-#endif
-}
+__device__ inline u32x4 ld16(const void* p) { return ld_vec<true, u32x4>(p); }
+__device__ inline void st16(void* p, f32x4 x) { __builtin_nontemporal_store(x, (f32x4*)p); }
 
 // AdamW on one coordinate (Alg. 1): moments, bias corrections folded into step_size and
 // inv_sqrt_bc2, decoupled decay.  sqrt and reciprocal are the 1-ulp hardware forms: the term they
@@ -208,9 +160,9 @@ __device__ inline void adamw_coord(const StepParams& p, float g, float& w, float
 }
 
 // fixed-order sum of a lane's VEC per-coordinate terms
-template <int VEC>
+template <int N>
 __device__ inline float lane_tree(const float* x) {
-  static_assert(VEC == 4, "lanes own four coordinates per sweep");
+  static_assert(N == 4, "per-coordinate terms leave fp32 in groups of four");
   return (x[0] + x[1]) + (x[2] + x[3]);
 }
 
@@ -219,43 +171,65 @@ __device__ inline double wave_sum(double x) {
   for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
   return x;
 }
+__device__ inline float wave_max(float x) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) x = __builtin_fmaxf(x, __shfl_xor(x, off, 64));
+  return x;
+}
+
+// What a lane gathers over the sweeps of one tile: the three sums in fp64 (each fed with fp32 sums of four
+// coordinates), the number of coordinates failing the coordinate-wise test and their largest ratio.
+struct LaneAcc {
+  double A = 0.0, B = 0.0, C = 0.0;
+  int nfail = 0;
+  float rmax = 0.f;
+};
 
 // Block partial of one tile -> partials[NT_NV*tile ..].  `buf` alternates between tiles so that one
 // barrier per tile is enough.
 template <int BLOCK>
-__device__ inline void tile_reduce(double a, double b, double c, double n, double (*red)[BLOCK / 64][NT_NV], int buf,
-                                   double* partials, int64_t tile) {
-  a = wave_sum(a);
-  b = wave_sum(b);
-  c = wave_sum(c);
-  n = wave_sum(n);
+__device__ inline void tile_reduce(const LaneAcc& acc, double (*red)[BLOCK / 64][NT_NV], int buf, double* partials,
+                                   int64_t tile) {
+  const double a = wave_sum(acc.A), b = wave_sum(acc.B), c = wave_sum(acc.C), n = wave_sum((double)acc.nfail);
+  const float r = wave_max(acc.rmax);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (lane == 0) {
     red[buf][wave][0] = a;
     red[buf][wave][1] = b;
     red[buf][wave][2] = c;
     red[buf][wave][3] = n;
+    red[buf][wave][4] = (double)r;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    double sa = red[buf][0][0], sb = red[buf][0][1], sc = red[buf][0][2], sn = red[buf][0][3];
+    double sa = red[buf][0][0], sb = red[buf][0][1], sc = red[buf][0][2], sn = red[buf][0][3], sr = red[buf][0][4];
 #pragma unroll
     for (int wv = 1; wv < BLOCK / 64; ++wv) {
       sa += red[buf][wv][0];
       sb += red[buf][wv][1];
       sc += red[buf][wv][2];
       sn += red[buf][wv][3];
+      sr = __builtin_fmax(sr, red[buf][wv][4]);
     }
     partials[NT_NV * tile + 0] = sa;
     partials[NT_NV * tile + 1] = sb;
     partials[NT_NV * tile + 2] = sc;
     partials[NT_NV * tile + 3] = sn;
+    partials[NT_NV * tile + 4] = sr;
   }
 }
 
-// Coordinate-wise form of the test (Sec. 4, Prop. 1): a coordinate fails when its centred sum c exceeds
-// eta^2 b_k (J - ddof) gbar^2.  thr < 0 switches the count off.
-__device__ inline int coord_fails(float thr, float c, float gb) { return (thr >= 0.f && c > thr * (gb * gb)) ? 1 : 0; }
+// Coordinate-wise form of the test (Sec. 4, Prop. 1): with thr = eta^2 b_k (J - ddof), a coordinate with centred
+// sum c and mean gb has the ratio c / (thr gb^2) and fails when that exceeds one.  A coordinate without spread
+// has ratio 0 whatever its mean; spread around a zero mean gives +inf.  thr < 0 switches both off.
+__device__ inline void coord_test(float thr, float c, float gb, LaneAcc& acc) {
+  if (thr >= 0.f) {
+    const float den = thr * (gb * gb);
+    acc.nfail += (c > den) ? 1 : 0;
+    const float rho = (c == 0.f) ? 0.f : c / den;
+    acc.rmax = __builtin_fmaxf(acc.rmax, rho);
+  }
+}
 
 // Per-chunk bookkeeping of the J > 16 walk, shared by the fast and the guarded path so that both
 // perform the same operations.  For one coordinate and a chunk of nb rows with shift K (the running
@@ -360,8 +334,7 @@ __device__ inline void guarded_tile(const StepParams& p, int64_t tile, int tile_
                                     int buf) {
   constexpr int VEC = GT::VEC;
   const int iters = tile_coords / (BLOCK * VEC);
-  double accA = 0.0, accB = 0.0, accC = 0.0;
-  int nfail = 0;
+  LaneAcc acc;
   for (int it = 0; it < iters; ++it) {
     const int64_t i0 = tile * (int64_t)tile_coords + ((int64_t)it * BLOCK + threadIdx.x) * VEC;
     float a[VEC], b[VEC], c[VEC];
@@ -378,7 +351,7 @@ __device__ inline void guarded_tile(const StepParams& p, int64_t tile, int tile_
         a[e] = aa;
         b[e] = sf * sf;
         c[e] = M2;
-        nfail += coord_fails(p.coord_thr, M2, gb);
+        if constexpr (MODE != MODE_ADAMW) coord_test(p.coord_thr, M2, gb, acc);
         if constexpr (MODE != MODE_STATS) {
           float w = p.w[i], m = p.m[i], v = p.v[i];
           adamw_coord(p, gb, w, m, v);
@@ -390,12 +363,12 @@ __device__ inline void guarded_tile(const StepParams& p, int64_t tile, int tile_
       }
     }
     if constexpr (MODE != MODE_ADAMW) {
-      accA += (double)lane_tree<VEC>(a);
-      accB += (double)lane_tree<VEC>(b);
-      accC += (double)lane_tree<VEC>(c);
+      acc.A += (double)lane_tree<VEC>(a);
+      acc.B += (double)lane_tree<VEC>(b);
+      acc.C += (double)lane_tree<VEC>(c);
     }
   }
-  if constexpr (MODE != MODE_ADAMW) tile_reduce<BLOCK>(accA, accB, accC, (double)nfail, red, buf, p.partials, tile);
+  if constexpr (MODE != MODE_ADAMW) tile_reduce<BLOCK>(acc, red, buf, p.partials, tile);
 }
 
 // AdamW on VEC coordinates whose state was loaded as 16-byte vectors, then the 16-byte stores.
@@ -442,12 +415,11 @@ template <class GT, int J, int MODE, int BLOCK, int ITERS, bool TABLE, bool GBAR
 __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red)[BLOCK / 64][NT_NV], int buf) {
   constexpr int VEC = GT::VEC;
   constexpr int TILE = BLOCK * VEC * ITERS;
-  double accA = 0.0, accB = 0.0, accC = 0.0;
-  int nfail = 0;
+  LaneAcc acc;
   // a statistics-only sweep with few rows has little in flight per lane: overlap sweeps up to about 64 bytes
   constexpr int ROW_BYTES = VEC * GT::ESIZE;
   constexpr int WANT = 64 / (J * ROW_BYTES);
-  constexpr int U = (MODE == MODE_STATS && ITERS > 1) ? (WANT >= 4 ? 4 : (WANT >= 2 ? 2 : 1)) : NT_UNROLL;
+  constexpr int U = (MODE == MODE_STATS && ITERS > 1) ? (WANT >= 4 ? 4 : (WANT >= 2 ? 2 : 1)) : 1;
 #pragma unroll U
   for (int it = 0; it < ITERS; ++it) {
     const int64_t i0 = tile * TILE + ((int64_t)it * BLOCK + threadIdx.x) * VEC;
@@ -462,6 +434,11 @@ __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red
         sm[q] = ld16(p.m + i0 + 4 * q);
         sv[q] = ld16(p.v + i0 + 4 * q);
       }
+      // Every load of the sweep is issued before any arithmetic: the compiler must neither sink loads below
+      // the arithmetic that precedes their use nor hoist arithmetic between them (measured: up to 5 % at 16
+      // rows against schedules that issue the state loads after the rows have arrived).  Statistics-only
+      // tiles are left free so that consecutive sweeps can overlap.
+      __builtin_amdgcn_sched_barrier(0);
     }
     double s[VEC];
     float gb[VEC];
@@ -491,19 +468,19 @@ __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red
       for (int e = 0; e < VEC; ++e) {
         const float sf = (float)s[e];
         b[e] = sf * sf;
-        nfail += coord_fails(p.coord_thr, c[e], gb[e]);
+        coord_test(p.coord_thr, c[e], gb[e], acc);
       }
-      accA += (double)lane_tree<VEC>(a);
-      accB += (double)lane_tree<VEC>(b);
-      accC += (double)lane_tree<VEC>(c);
+      acc.A += (double)lane_tree<VEC>(a);
+      acc.B += (double)lane_tree<VEC>(b);
+      acc.C += (double)lane_tree<VEC>(c);
     }
     if constexpr (MODE != MODE_STATS) adamw_store<VEC>(p, i0, gb, sw, sm, sv);
     if (GBAR && p.gbar) gbar_store<VEC>(p, i0, gb);
   }
-  if constexpr (MODE != MODE_ADAMW) tile_reduce<BLOCK>(accA, accB, accC, (double)nfail, red, buf, p.partials, tile);
-#if NT_ADAMW_BARRIER
+  if constexpr (MODE != MODE_ADAMW) tile_reduce<BLOCK>(acc, red, buf, p.partials, tile);
+  // AdamW-only tiles end with a block barrier like the other modes: the waves of a block then finish together
+  // and the next block's waves start together (measured +2 %)
   if constexpr (MODE == MODE_ADAMW) __syncthreads();
-#endif
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -537,8 +514,7 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
   constexpr int VEC = GT::VEC;
   constexpr int TILE = BLOCK * VEC * ITERS;
   const int J = p.J;
-  double accA = 0.0, accB = 0.0, accC = 0.0;
-  int nfail = 0;
+  LaneAcc acc;
 #pragma unroll 1
   for (int it = 0; it < ITERS; ++it) {
     const int64_t i0 = tile * TILE + ((int64_t)it * BLOCK + threadIdx.x) * VEC;
@@ -584,11 +560,11 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
       for (int e = 0; e < VEC; ++e) {
         const float sf = (float)S[e];
         b[e] = sf * sf;
-        nfail += coord_fails(p.coord_thr, M2[e], gb[e]);
+        coord_test(p.coord_thr, M2[e], gb[e], acc);
       }
-      accA += (double)lane_tree<VEC>(a);
-      accB += (double)lane_tree<VEC>(b);
-      accC += (double)lane_tree<VEC>(M2);
+      acc.A += (double)lane_tree<VEC>(a);
+      acc.B += (double)lane_tree<VEC>(b);
+      acc.C += (double)lane_tree<VEC>(M2);
     }
     if constexpr (MODE != MODE_STATS) {
       u32x4 sw[VEC / 4], sm[VEC / 4], sv[VEC / 4];
@@ -602,7 +578,7 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
     }
     if (GBAR && p.gbar) gbar_store<VEC>(p, i0, gb);
   }
-  if constexpr (MODE != MODE_ADAMW) tile_reduce<BLOCK>(accA, accB, accC, (double)nfail, red, buf, p.partials, tile);
+  if constexpr (MODE != MODE_ADAMW) tile_reduce<BLOCK>(acc, red, buf, p.partials, tile);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -613,16 +589,14 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
 // ---------------------------------------------------------------------------------------------
 // GBAR = false compiles the gbar store out (statistics-only launch class, so that sweeps can overlap).
 template <class GT, int J_T, int MODE, int BLOCK, int ITERS, bool TABLE, bool GBAR>
-__global__ __launch_bounds__(BLOCK, NT_WAVES_PER_EU) void k_step(StepParams p, int64_t nfull, int64_t ntiles) {
+__global__ __launch_bounds__(BLOCK) void k_step(StepParams p, int64_t nfull, int64_t ntiles, WsControl* ctl) {
   constexpr int TILE = BLOCK * GT::VEC * ITERS;
   static_assert(NT_TILE_MAX % TILE == 0, "tile sizes must divide NT_TILE_MAX");
   __shared__ double red[2][BLOCK / 64][NT_NV];
   int buf = 0;
   if constexpr (TABLE) {
-    // the host cannot see the row pointers: the fast tiles need all of them 16-byte aligned
-    uintptr_t bits = 0;
-    for (int j = 0; j < p.J; ++j) bits |= (uintptr_t)row_base<GT, true>(p, j);
-    if (bits & 15u) nfull = 0;
+    // the host cannot see the row pointers: k_rows_aligned has looked at them and left its verdict here
+    if (!ctl->rows_aligned) nfull = 0;
   }
   const int64_t nrest = ntiles - nfull;  // guarded tiles (0 or 1 on the aligned path)
   for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
@@ -638,6 +612,19 @@ __global__ __launch_bounds__(BLOCK, NT_WAVES_PER_EU) void k_step(StepParams p, i
     }
     buf ^= 1;
   }
+}
+
+// Pointer-table calls: are all J row pointers 16-byte aligned?  One small block, once per call, so that the
+// blocks of k_step need not walk the table themselves.
+__global__ __launch_bounds__(256) void k_rows_aligned(const void* const* rows, int J, WsControl* ctl) {
+  __shared__ unsigned int bits;
+  if (threadIdx.x == 0) bits = 0u;
+  __syncthreads();
+  unsigned int mine = 0u;
+  for (int j = threadIdx.x; j < J; j += 256) mine |= (unsigned int)((uintptr_t)rows[j] & 15u);
+  if (mine) atomicOr(&bits, mine);
+  __syncthreads();
+  if (threadIdx.x == 0) ctl->rows_aligned = bits ? 0u : 1u;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -744,97 +731,127 @@ __device__ inline dd dd_wave_sum(dd x) {
   }
   return x;
 }
-
-// Adds this thread's share (entries threadIdx.x, threadIdx.x + THREADS, ...) of n entries of NT_NV values
-// each into acc.  packed = false: plain tile partials {A, B, C, n_fail}; packed = true: double-double
-// group partials {A, A_lo, B, B_lo, C, C_lo, n, n_lo}.
-template <int THREADS>
-__device__ inline void dd_accumulate(const double* in, int64_t n, bool packed, dd* acc) {
-  for (int64_t t = threadIdx.x; t < n; t += THREADS) {
+__device__ inline double wave_max(double x) {
 #pragma unroll
-    for (int k = 0; k < NT_NV; ++k) {
+  for (int off = 32; off >= 1; off >>= 1) x = __builtin_fmax(x, __shfl_xor(x, off, 64));
+  return x;
+}
+
+// Running totals of partial records: the NT_NSUM sums in double-double and the largest ratio.
+struct Totals {
+  dd s[NT_NSUM];
+  double mx;
+};
+__device__ inline void totals_clear(Totals& t) {
+#pragma unroll
+  for (int k = 0; k < NT_NSUM; ++k) t.s[k] = {0.0, 0.0};
+  t.mx = 0.0;
+}
+
+// Adds this thread's share (entries threadIdx.x, threadIdx.x + THREADS, ...) of n records into acc.
+// packed = false: tile partials {A, B, C, n_fail, r_max}; packed = true: group partials
+// {A, A_lo, B, B_lo, C, C_lo, n, n_lo, r_max, unused}.
+template <int THREADS>
+__device__ inline void totals_accumulate(const double* in, int64_t n, bool packed, Totals& acc) {
+  for (int64_t t = threadIdx.x; t < n; t += THREADS) {
+    const double* rec = in + (packed ? 2 * NT_NV : NT_NV) * t;
+#pragma unroll
+    for (int k = 0; k < NT_NSUM; ++k) {
       dd x;
       if (!packed) {
-        x.hi = in[NT_NV * t + k];
+        x.hi = rec[k];
         x.lo = 0.0;
       } else {
-        x.hi = in[2 * NT_NV * t + 2 * k];
-        x.lo = in[2 * NT_NV * t + 2 * k + 1];
+        x.hi = rec[2 * k];
+        x.lo = rec[2 * k + 1];
       }
-      acc[k] = dd_add(acc[k], x);
+      acc.s[k] = dd_add(acc.s[k], x);
     }
+    acc.mx = __builtin_fmax(acc.mx, rec[packed ? 2 * NT_NSUM : NT_NSUM]);
   }
 }
 
-// Block total of the threads' accumulators; all threads take part, thread 0 returns the totals in tot[NT_NV].
+// Block total of the threads' accumulators; all threads take part, thread 0 returns the totals.
 template <int THREADS>
-__device__ inline void block_dd_finish(dd* acc, double (*sh)[2 * NT_NV], dd* tot) {
+__device__ inline void block_totals_finish(Totals& acc, double (*sh)[2 * NT_NV], Totals& tot) {
 #pragma unroll
-  for (int k = 0; k < NT_NV; ++k) acc[k] = dd_wave_sum(acc[k]);
+  for (int k = 0; k < NT_NSUM; ++k) acc.s[k] = dd_wave_sum(acc.s[k]);
+  acc.mx = wave_max(acc.mx);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (lane == 0) {
 #pragma unroll
-    for (int k = 0; k < NT_NV; ++k) {
-      sh[wave][2 * k] = acc[k].hi;
-      sh[wave][2 * k + 1] = acc[k].lo;
+    for (int k = 0; k < NT_NSUM; ++k) {
+      sh[wave][2 * k] = acc.s[k].hi;
+      sh[wave][2 * k + 1] = acc.s[k].lo;
     }
+    sh[wave][2 * NT_NSUM] = acc.mx;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
 #pragma unroll
-    for (int k = 0; k < NT_NV; ++k) {
-      tot[k].hi = sh[0][2 * k];
-      tot[k].lo = sh[0][2 * k + 1];
+    for (int k = 0; k < NT_NSUM; ++k) {
+      tot.s[k].hi = sh[0][2 * k];
+      tot.s[k].lo = sh[0][2 * k + 1];
       for (int wv = 1; wv < THREADS / 64; ++wv) {
         dd x = {sh[wv][2 * k], sh[wv][2 * k + 1]};
-        tot[k] = dd_add(tot[k], x);
+        tot.s[k] = dd_add(tot.s[k], x);
       }
     }
+    tot.mx = sh[0][2 * NT_NSUM];
+    for (int wv = 1; wv < THREADS / 64; ++wv) tot.mx = __builtin_fmax(tot.mx, sh[wv][2 * NT_NSUM]);
   }
 }
 
-// Sum of n entries of NT_NV values each (layouts as in dd_accumulate); thread 0 returns the totals.
+// Sum of n records (layouts as in totals_accumulate); thread 0 returns the totals.
 template <int THREADS>
-__device__ inline void block_dd_sum(const double* in, int64_t n, bool packed, double (*sh)[2 * NT_NV], dd* tot) {
-  dd acc[NT_NV];
-#pragma unroll
-  for (int k = 0; k < NT_NV; ++k) acc[k] = {0.0, 0.0};
-  dd_accumulate<THREADS>(in, n, packed, acc);
-  block_dd_finish<THREADS>(acc, sh, tot);
+__device__ inline void block_totals(const double* in, int64_t n, bool packed, double (*sh)[2 * NT_NV], Totals& tot) {
+  Totals acc;
+  totals_clear(acc);
+  totals_accumulate<THREADS>(in, n, packed, acc);
+  block_totals_finish<THREADS>(acc, sh, tot);
 }
 
-// First stage for long vectors: block g adds tile partials [g*NT_GROUP_TILES, ...) into one
-// double-double group partial.
-__global__ __launch_bounds__(NT_GROUP_THREADS) void k_reduce_groups(const double* partials, int64_t ntiles,
-                                                                    double* groups) {
+// First stage for long vectors: block g adds tile partials [g*NT_GROUP_TILES, ...) into one double-double
+// group partial.  The two stages are separate launches on purpose: the eight XCDs of this GPU do not share an
+// L2, so a block that waits for the other blocks' partials inside one kernel (a ticket taken after a device-wide
+// release, then a device-wide acquire) pays a write-back and an invalidation of its L2 on every block; measured,
+// that made the single launch slower (26 us at 15 groups) than the two small kernels it replaced (7 + 10 us),
+// whose visibility comes with the kernel boundary.
+__global__ __launch_bounds__(NT_GROUP_THREADS) void k_reduce_groups(const double* tiles, int64_t ntiles, double* groups) {
   __shared__ double sh[NT_GROUP_THREADS / 64][2 * NT_NV];
   const int64_t t0 = (int64_t)blockIdx.x * NT_GROUP_TILES;
   const int64_t n = (ntiles - t0 < NT_GROUP_TILES) ? (ntiles - t0) : NT_GROUP_TILES;
-  dd tot[NT_NV];
-  block_dd_sum<NT_GROUP_THREADS>(partials + NT_NV * t0, n, false, sh, tot);
+  Totals tot;
+  block_totals<NT_GROUP_THREADS>(tiles + NT_NV * t0, n, false, sh, tot);
   if (threadIdx.x == 0) {
+    double* rec = groups + 2 * NT_NV * (int64_t)blockIdx.x;
 #pragma unroll
-    for (int k = 0; k < NT_NV; ++k) {
-      groups[2 * NT_NV * (int64_t)blockIdx.x + 2 * k] = tot[k].hi;
-      groups[2 * NT_NV * (int64_t)blockIdx.x + 2 * k + 1] = tot[k].lo;
+    for (int k = 0; k < NT_NSUM; ++k) {
+      rec[2 * k] = tot.s[k].hi;
+      rec[2 * k + 1] = tot.s[k].lo;
     }
+    rec[2 * NT_NSUM] = tot.mx;
+    rec[2 * NT_NSUM + 1] = 0.0;
   }
 }
 
-// One block: partials (tile or group) -> A, B, C in double-double, then the decision.
-__global__ __launch_bounds__(NT_FIN_THREADS) void k_finalize(const double* in, int64_t n, bool packed, DecideParams q,
-                                                             nt_result* out, WsHeader hdr, WsHeader* hdr_out) {
-  __shared__ double sh[NT_FIN_THREADS / 64][2 * NT_NV];
+// One block: partials (tile or group) -> A, B, C in double-double, then the decision.  THREADS: 1024, or 256 for
+// up to NT_FIN_SMALL records (short vectors, where this kernel's latency is a large part of the step).
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void k_finalize(const double* in, int64_t n, bool packed, DecideParams q,
+                                                      nt_result* out, WsHeader hdr, WsHeader* hdr_out) {
+  __shared__ double sh[THREADS / 64][2 * NT_NV];
   const bool stats = (q.flags & NT_DO_STATS) != 0;
-  dd tot[NT_NV];
-#pragma unroll
-  for (int k = 0; k < NT_NV; ++k) tot[k] = {0.0, 0.0};
-  if (stats) block_dd_sum<NT_FIN_THREADS>(in, n, packed, sh, tot);
+  Totals tot;
+  totals_clear(tot);
+  if (stats) block_totals<THREADS>(in, n, packed, sh, tot);
   if (threadIdx.x != 0) return;
   *hdr_out = hdr;
   nt_result r;
   r.status = 0;
-  r.coord_fail = (stats && (q.flags & NT_COORD_TEST)) ? (int64_t)tot[3].hi : -1;
+  const bool coord = stats && (q.flags & NT_COORD_TEST);
+  r.coord_fail = coord ? (int64_t)tot.s[3].hi : -1;
+  r.coord_max_ratio = coord ? tot.mx : -1.0;
   const double nan = __builtin_nan("");
   if (!stats) {
     r.A = r.B = r.C = r.A_lo = r.B_lo = r.C_lo = nan;
@@ -844,9 +861,9 @@ __global__ __launch_bounds__(NT_FIN_THREADS) void k_finalize(const double* in, i
     r.next_b = q.b_k;
     r.status = NT_STATUS_NO_STATS;
   } else {
-    r.A = tot[0].hi; r.A_lo = tot[0].lo;
-    r.B = tot[1].hi; r.B_lo = tot[1].lo;
-    r.C = tot[2].hi; r.C_lo = tot[2].lo;
+    r.A = tot.s[0].hi; r.A_lo = tot.s[0].lo;
+    r.B = tot.s[1].hi; r.B_lo = tot.s[1].lo;
+    r.C = tot.s[2].hi; r.C_lo = tot.s[2].lo;
     if (q.flags & NT_PARTIAL) {
       r.gbar_sq = r.var_l1 = r.T = nan;
       r.clip_coef = 1.0;
@@ -865,8 +882,7 @@ __global__ __launch_bounds__(NT_FIN_THREADS) void k_finalize(const double* in, i
 // Sums over the coordinates [plo, phi) taken one by one, NT_LAYER_THREADS apart per thread.  J_T > 0: row
 // count known at compile time; J_T = 0: any J.
 template <class GT, bool TABLE, int J_T>
-__device__ inline void piece_sums(const StepParams& p, int64_t plo, int64_t phi, double& a, double& b, double& c,
-                                  int64_t& nfail) {
+__device__ inline void piece_sums(const StepParams& p, int64_t plo, int64_t phi, LaneAcc& acc) {
 #pragma unroll 2
   for (int64_t i = plo + threadIdx.x; i < phi; i += NT_LAYER_THREADS) {
     double S;
@@ -874,10 +890,10 @@ __device__ inline void piece_sums(const StepParams& p, int64_t plo, int64_t phi,
     coord_stats<GT, TABLE, J_T>(p, i, S, M2, aa);
     const float gb = (float)(S * p.inv_J);
     const float sf = (float)S;
-    a += (double)aa;
-    b += (double)(sf * sf);
-    c += (double)M2;
-    nfail += coord_fails(p.coord_thr, M2, gb);
+    acc.A += (double)aa;
+    acc.B += (double)(sf * sf);
+    acc.C += (double)M2;
+    coord_test(p.coord_thr, M2, gb, acc);
   }
 }
 
@@ -905,6 +921,7 @@ __global__ __launch_bounds__(NT_LAYER_THREADS) void k_layer_stats(StepParams p, 
     if (threadIdx.x == 0) {
       nt_layer_stats r;
       r.A = r.B = r.C = r.gbar_sq = r.var_l1 = r.T = nan;
+      r.coord_max_ratio = -1.0;
       r.n = hi - lo;
       r.coord_fail = -1;
       r.pass = 1;
@@ -922,40 +939,44 @@ __global__ __launch_bounds__(NT_LAYER_THREADS) void k_layer_stats(StepParams p, 
     last = hi / tc;
     tail_lo = last * tc;
   }
-  double a = 0.0, b = 0.0, c = 0.0;
-  int64_t nfail = 0;
-  for (int piece = 0; piece < 2; ++piece) {
-    const int64_t plo = piece ? tail_lo : lo, phi = piece ? hi : head_end;
+  LaneAcc piece;
+  for (int part = 0; part < 2; ++part) {
+    const int64_t plo = part ? tail_lo : lo, phi = part ? hi : head_end;
     if (plo >= phi) continue;
 #define NT_CASE(JJ) \
   case JJ:          \
-    piece_sums<GT, TABLE, JJ>(p, plo, phi, a, b, c, nfail); \
+    piece_sums<GT, TABLE, JJ>(p, plo, phi, piece); \
     break;
     switch (p.J) {
       NT_CASE(2) NT_CASE(3) NT_CASE(4) NT_CASE(5) NT_CASE(6) NT_CASE(7) NT_CASE(8) NT_CASE(9)
       NT_CASE(10) NT_CASE(11) NT_CASE(12) NT_CASE(13) NT_CASE(14) NT_CASE(15) NT_CASE(16)
-      default: piece_sums<GT, TABLE, 0>(p, plo, phi, a, b, c, nfail);
+      default: piece_sums<GT, TABLE, 0>(p, plo, phi, piece);
     }
 #undef NT_CASE
   }
-  dd acc[NT_NV] = {{a, 0.0}, {b, 0.0}, {c, 0.0}, {(double)nfail, 0.0}};
+  Totals acc;
+  acc.s[0] = {piece.A, 0.0};
+  acc.s[1] = {piece.B, 0.0};
+  acc.s[2] = {piece.C, 0.0};
+  acc.s[3] = {(double)piece.nfail, 0.0};
+  acc.mx = (double)piece.rmax;
   const double* tiles = ws + NT_WS_HEADER;
   const double* groups = tiles + NT_NV * h.ntiles;
   const int64_t g0 = (first + NT_GROUP_TILES - 1) / NT_GROUP_TILES, g1 = last / NT_GROUP_TILES;
   if (h.ngroups > 0 && g0 < g1) {
-    dd_accumulate<NT_LAYER_THREADS>(tiles + NT_NV * first, g0 * NT_GROUP_TILES - first, false, acc);
-    dd_accumulate<NT_LAYER_THREADS>(groups + 2 * NT_NV * g0, g1 - g0, true, acc);
-    dd_accumulate<NT_LAYER_THREADS>(tiles + NT_NV * g1 * NT_GROUP_TILES, last - g1 * NT_GROUP_TILES, false, acc);
+    totals_accumulate<NT_LAYER_THREADS>(tiles + NT_NV * first, g0 * NT_GROUP_TILES - first, false, acc);
+    totals_accumulate<NT_LAYER_THREADS>(groups + 2 * NT_NV * g0, g1 - g0, true, acc);
+    totals_accumulate<NT_LAYER_THREADS>(tiles + NT_NV * g1 * NT_GROUP_TILES, last - g1 * NT_GROUP_TILES, false, acc);
   } else {
-    dd_accumulate<NT_LAYER_THREADS>(tiles + NT_NV * first, last - first, false, acc);
+    totals_accumulate<NT_LAYER_THREADS>(tiles + NT_NV * first, last - first, false, acc);
   }
-  dd tot[NT_NV];
-  block_dd_finish<NT_LAYER_THREADS>(acc, sh, tot);
+  Totals tot;
+  block_totals_finish<NT_LAYER_THREADS>(acc, sh, tot);
   if (threadIdx.x != 0) return;
   nt_result t;
-  t.A = tot[0].hi;
-  t.B = tot[1].hi;
-  t.C = tot[2].hi;
+  t.A = tot.s[0].hi;
+  t.B = tot.s[1].hi;
+  t.C = tot.s[2].hi;
   t.status = 0;
   DecideParams q = h.q;
   q.b_max = 0;
@@ -969,8 +990,9 @@ __global__ __launch_bounds__(NT_LAYER_THREADS) void k_layer_stats(StepParams p, 
   r.gbar_sq = t.gbar_sq;
   r.var_l1 = t.var_l1;
   r.T = t.T;
+  r.coord_max_ratio = (h.coord_thr >= 0.0) ? tot.mx : -1.0;
   r.n = hi - lo;
-  r.coord_fail = (h.coord_thr >= 0.0) ? (int64_t)tot[3].hi : -1;
+  r.coord_fail = (h.coord_thr >= 0.0) ? (int64_t)tot.s[3].hi : -1;
   r.pass = t.pass;
   r.status = status | (t.status & (NT_STATUS_NONFINITE | NT_STATUS_ZERO_GRAD_NORM | NT_STATUS_T_SATURATED));
   out[l] = r;
@@ -1005,13 +1027,8 @@ __global__ __launch_bounds__(NT_AUX_BLOCK) void k_adamw_gbar(StepParams p, const
 
 __global__ __launch_bounds__(NT_AUX_BLOCK) void k_copy16(f32x4* dst, const u32x4* src, int64_t n16) {
   for (int64_t i = (int64_t)blockIdx.x * NT_AUX_BLOCK + threadIdx.x; i < n16; i += (int64_t)gridDim.x * NT_AUX_BLOCK) {
-    u32x4 x = ld_vec<NT_NT_COPY, u32x4>(src + i);
-    f32x4 y = __builtin_bit_cast(f32x4, x);
-#if NT_NT_COPY
-    __builtin_nontemporal_store(y, dst + i);
-#else
-    dst[i] = y;
-#endif
+    const u32x4 x = ld16(src + i);
+    st16(dst + i, __builtin_bit_cast(f32x4, x));
   }
 }
 
@@ -1127,18 +1144,19 @@ bool hyper_ok(const nt_hyper* h, int64_t J) {
 }
 
 template <class GT, int MODE, bool TABLE, int BS, int IS, bool GBAR>
-hipError_t launch_step_shape(const StepParams& p, int64_t nfull, int64_t ntiles, int grid, hipStream_t st) {
+hipError_t launch_step_shape(const StepParams& p, int64_t nfull, int64_t ntiles, WsControl* ctl, int grid,
+                             hipStream_t st) {
 #define NT_CASE(JJ)                                                                                             \
   case JJ:                                                                                                      \
     hipLaunchKernelGGL((k_step<GT, JJ, MODE, BS, IS, TABLE, GBAR>), dim3(grid), dim3(BS), 0, st, p, nfull,      \
-                       ntiles);                                                                                 \
+                       ntiles, ctl);                                                                            \
     break;
   switch (p.J) {
     NT_CASE(2) NT_CASE(3) NT_CASE(4) NT_CASE(5) NT_CASE(6) NT_CASE(7) NT_CASE(8) NT_CASE(9)
     NT_CASE(10) NT_CASE(11) NT_CASE(12) NT_CASE(13) NT_CASE(14) NT_CASE(15) NT_CASE(16)
     default:
       hipLaunchKernelGGL((k_step<GT, 0, MODE, NT_BLOCK_LARGE, NT_ITERS_LARGE, TABLE, true>), dim3(grid),
-                         dim3(NT_BLOCK_LARGE), 0, st, p, nfull, ntiles);
+                         dim3(NT_BLOCK_LARGE), 0, st, p, nfull, ntiles, ctl);
   }
 #undef NT_CASE
   return hipGetLastError();
@@ -1146,29 +1164,39 @@ hipError_t launch_step_shape(const StepParams& p, int64_t nfull, int64_t ntiles,
 
 // picks the launch class (block size, sweeps per tile) that tile_cfg() describes
 template <class GT, int MODE, bool TABLE>
-hipError_t launch_step(const StepParams& p, int64_t nfull, int64_t ntiles, int grid, hipStream_t st) {
+hipError_t launch_step(const StepParams& p, int64_t nfull, int64_t ntiles, WsControl* ctl, int grid, hipStream_t st) {
   if constexpr (MODE == MODE_STATS) {
     if (p.gbar)
-      return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS_GBAR, NT_ITERS_STATS_GBAR, true>(p, nfull, ntiles, grid,
-                                                                                                 st);
-    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS, NT_ITERS_STATS, false>(p, nfull, ntiles, grid, st);
+      return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS_GBAR, NT_ITERS_STATS_GBAR, true>(p, nfull, ntiles, ctl,
+                                                                                                 grid, st);
+    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS, NT_ITERS_STATS, false>(p, nfull, ntiles, ctl, grid, st);
   } else if constexpr (MODE == MODE_ADAMW) {
-    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_ADAMW, NT_ITERS_ADAMW, true>(p, nfull, ntiles, grid, st);
+    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_ADAMW, NT_ITERS_ADAMW, true>(p, nfull, ntiles, ctl, grid, st);
   } else {
-    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK, NT_ITERS, true>(p, nfull, ntiles, grid, st);
+    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK, NT_ITERS, true>(p, nfull, ntiles, ctl, grid, st);
   }
 }
 
 template <class GT, bool TABLE>
-hipError_t launch_step_mode(int mode, const StepParams& p, int64_t nfull, int64_t ntiles, int grid, hipStream_t st) {
+hipError_t launch_step_mode(int mode, const StepParams& p, int64_t nfull, int64_t ntiles, WsControl* ctl, int grid,
+                            hipStream_t st) {
   switch (mode) {
-    case MODE_FULL: return launch_step<GT, MODE_FULL, TABLE>(p, nfull, ntiles, grid, st);
-    case MODE_STATS: return launch_step<GT, MODE_STATS, TABLE>(p, nfull, ntiles, grid, st);
-    default: return launch_step<GT, MODE_ADAMW, TABLE>(p, nfull, ntiles, grid, st);
+    case MODE_FULL: return launch_step<GT, MODE_FULL, TABLE>(p, nfull, ntiles, ctl, grid, st);
+    case MODE_STATS: return launch_step<GT, MODE_STATS, TABLE>(p, nfull, ntiles, ctl, grid, st);
+    default: return launch_step<GT, MODE_ADAMW, TABLE>(p, nfull, ntiles, ctl, grid, st);
   }
 }
 
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+inline void launch_finalize(const double* in, int64_t n, bool packed, const DecideParams& q, nt_result* out,
+                            const WsHeader& hdr, WsHeader* hdr_out, hipStream_t st) {
+  if (n <= NT_FIN_SMALL)
+    hipLaunchKernelGGL(k_finalize<256>, dim3(1), dim3(256), 0, st, in, n, packed, q, out, hdr, hdr_out);
+  else
+    hipLaunchKernelGGL(k_finalize<NT_FIN_THREADS>, dim3(1), dim3(NT_FIN_THREADS), 0, st, in, n, packed, q, out, hdr,
+                       hdr_out);
+}
 
 }  // namespace
 
@@ -1190,11 +1218,24 @@ static size_t partials_bytes(int64_t J, int64_t d) {
 // passes: statistics that store only gbar, then AdamW from gbar.  The fp32 gbar buffer for that lives
 // behind the partials (plus slack to align it to 16 bytes) unless the caller asked for gbar anyway.
 static inline bool two_phase(int64_t J, int esize) { return J * esize >= NT_TWO_PHASE_ROW_BYTES; }
+// does a call with these flags take the two-pass route and keep gbar in the workspace?
+static inline bool gbar_in_workspace(int64_t J, int esize, uint32_t flags) {
+  const uint32_t both = NT_DO_STATS | NT_DO_ADAMW;
+  return (flags & both) == both && !(flags & (NT_ONE_PASS | NT_WRITE_GBAR)) && two_phase(J, esize);
+}
+static inline size_t gbar_bytes(int64_t d) { return (((size_t)d * sizeof(float) + 15u) & ~(size_t)15u) + 16; }
 
 size_t normtest_workspace_bytes(int64_t J, int64_t d) {
   if (J < 2 || d < 0) return 0;
   size_t need = partials_bytes(J, d);
-  if (two_phase(J, 4)) need += (((size_t)d * sizeof(float) + 15u) & ~(size_t)15u) + 16;  // dtype unknown here
+  if (two_phase(J, 4)) need += gbar_bytes(d);  // dtype and flags unknown here: the larger of the two
+  return need;
+}
+
+size_t normtest_workspace_bytes_for(nt_dtype gdtype, int64_t J, int64_t d, uint32_t flags) {
+  if (J < 2 || d < 0 || (gdtype != NT_F32 && gdtype != NT_BF16)) return 0;
+  size_t need = partials_bytes(J, d);
+  if (gbar_in_workspace(J, gdtype == NT_F32 ? 4 : 2, flags)) need += gbar_bytes(d);
   return need;
 }
 
@@ -1234,7 +1275,7 @@ static int check_step_args(const void* grads, nt_dtype gdtype, int64_t J, int64_
         shard->shard_offset < 0 || shard->d_global < 0 || shard->shard_offset + d > shard->d_global)
       return NT_ERR_BAD_ARG;
   }
-  if (workspace_bytes < normtest_workspace_bytes(J, d)) return NT_ERR_WORKSPACE_TOO_SMALL;
+  if (workspace_bytes < normtest_workspace_bytes_for(gdtype, J, d, flags)) return NT_ERR_WORKSPACE_TOO_SMALL;
   return NT_OK;
 }
 
@@ -1265,8 +1306,14 @@ static int enqueue_step(const void* grads, bool table, nt_dtype gdtype, int64_t 
                     ? (float)(hyper->eta * hyper->eta * (double)hyper->b_k * (double)(J - hyper->ddof))
                     : -1.0f;
 
+  WsControl* ctl = (WsControl*)((double*)workspace + NT_WS_CONTROL);
   if (ntiles > 0) {
-    // row alignment: checked here for a strided matrix, by the kernel itself for a pointer table
+    // row alignment: checked here for a strided matrix, by a small kernel for a pointer table
+    if (table) {
+      hipLaunchKernelGGL(k_rows_aligned, dim3(1), dim3(256), 0, st, (const void* const*)grads, (int)J, ctl);
+      const hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return hip_code(e);
+    }
     bool al = table || (aligned16(grads) && ((ld * esize) % 16 == 0));
     if (mode != MODE_STATS) al = al && aligned16(w) && aligned16(m) && aligned16(v);
     if (p.gbar) al = al && aligned16(p.gbar);
@@ -1275,11 +1322,11 @@ static int enqueue_step(const void* grads, bool table, nt_dtype gdtype, int64_t 
     const int grid = (int)(ntiles < max_grid ? ntiles : max_grid);
     hipError_t e;
     if (table)
-      e = (gdtype == NT_F32) ? launch_step_mode<F32, true>(mode, p, nfull, ntiles, grid, st)
-                             : launch_step_mode<BF16, true>(mode, p, nfull, ntiles, grid, st);
+      e = (gdtype == NT_F32) ? launch_step_mode<F32, true>(mode, p, nfull, ntiles, ctl, grid, st)
+                             : launch_step_mode<BF16, true>(mode, p, nfull, ntiles, ctl, grid, st);
     else
-      e = (gdtype == NT_F32) ? launch_step_mode<F32, false>(mode, p, nfull, ntiles, grid, st)
-                             : launch_step_mode<BF16, false>(mode, p, nfull, ntiles, grid, st);
+      e = (gdtype == NT_F32) ? launch_step_mode<F32, false>(mode, p, nfull, ntiles, ctl, grid, st)
+                             : launch_step_mode<BF16, false>(mode, p, nfull, ntiles, ctl, grid, st);
     if (e != hipSuccess) return hip_code(e);
   }
 
@@ -1313,11 +1360,9 @@ static int enqueue_step(const void* grads, bool table, nt_dtype gdtype, int64_t 
     hipLaunchKernelGGL(k_reduce_groups, dim3((unsigned)ngroups), dim3(NT_GROUP_THREADS), 0, st, partials, ntiles, groups);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_code(e);
-    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(NT_FIN_THREADS), 0, st, (const double*)groups, ngroups, true, q, result_dev,
-                       hdr, hdr_out);
+    launch_finalize(groups, ngroups, true, q, result_dev, hdr, hdr_out, st);
   } else {
-    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(NT_FIN_THREADS), 0, st, partials, ntiles, false, q, result_dev, hdr,
-                       hdr_out);
+    launch_finalize(partials, ntiles, false, q, result_dev, hdr, hdr_out, st);
   }
   return hip_code(hipGetLastError());
 }
@@ -1534,9 +1579,11 @@ int normtest_combine(const nt_result* partials, int32_t n, int64_t J, const nt_h
   dd tot[3] = {{0.0, 0.0}, {0.0, 0.0}, {0.0, 0.0}};
   uint32_t status = 0;
   int64_t coord_fail = 0;  // the count is additive over shards; missing in one shard = missing in the total
+  double coord_max = 0.0;  // the largest ratio over shards is the largest of the shards' values
   for (int32_t s = 0; s < n; ++s) {
     if (partials[s].status & NT_STATUS_NO_STATS) return NT_ERR_BAD_ARG;
     coord_fail = (coord_fail < 0 || partials[s].coord_fail < 0) ? -1 : coord_fail + partials[s].coord_fail;
+    if (partials[s].coord_fail >= 0 && partials[s].coord_max_ratio > coord_max) coord_max = partials[s].coord_max_ratio;
     const dd a = {partials[s].A, partials[s].A_lo}, b = {partials[s].B, partials[s].B_lo},
              c = {partials[s].C, partials[s].C_lo};
     tot[0] = dd_add(tot[0], a);
@@ -1571,6 +1618,7 @@ int normtest_combine(const nt_result* partials, int32_t n, int64_t J, const nt_h
   q.flags = NT_DO_STATS;
   decide(q, &r);
   r.coord_fail = coord_fail;
+  r.coord_max_ratio = coord_fail < 0 ? -1.0 : coord_max;
   *out = r;
   return NT_OK;
 }

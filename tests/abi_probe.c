@@ -21,11 +21,12 @@ int main(void) {
   FIELD(nt_result, A); FIELD(nt_result, B); FIELD(nt_result, C); FIELD(nt_result, A_lo); FIELD(nt_result, B_lo);
   FIELD(nt_result, C_lo); FIELD(nt_result, gbar_sq); FIELD(nt_result, var_l1); FIELD(nt_result, T);
   FIELD(nt_result, clip_coef); FIELD(nt_result, next_b); FIELD(nt_result, coord_fail); FIELD(nt_result, pass);
-  FIELD(nt_result, status);
+  FIELD(nt_result, status); FIELD(nt_result, coord_max_ratio);
   printf("size nt_layer_stats %zu\n", sizeof(nt_layer_stats));
   FIELD(nt_layer_stats, A); FIELD(nt_layer_stats, B); FIELD(nt_layer_stats, C); FIELD(nt_layer_stats, gbar_sq);
   FIELD(nt_layer_stats, var_l1); FIELD(nt_layer_stats, T); FIELD(nt_layer_stats, n);
   FIELD(nt_layer_stats, coord_fail); FIELD(nt_layer_stats, pass); FIELD(nt_layer_stats, status);
+  FIELD(nt_layer_stats, coord_max_ratio);
   printf("enum NT_F32 %d\nenum NT_BF16 %d\n", (int)NT_F32, (int)NT_BF16);
   printf("enum NT_DO_STATS %u\nenum NT_DO_ADAMW %u\nenum NT_PARTIAL %u\nenum NT_WRITE_GBAR %u\nenum NT_COORD_TEST %u\n"
          "enum NT_ONE_PASS %u\n",
@@ -36,8 +37,8 @@ int main(void) {
          NT_STATUS_NONFINITE, NT_STATUS_ZERO_GRAD_NORM, NT_STATUS_CLAMPED, NT_STATUS_PARTIAL_ONLY,
          NT_STATUS_T_SATURATED, NT_STATUS_NO_STATS, NT_STATUS_BAD_RANGE);
   printf("enum NT_OK %d\nenum NT_ERR_BAD_ARG %d\nenum NT_ERR_UNSUPPORTED %d\nenum NT_ERR_WORKSPACE_TOO_SMALL %d\n"
-         "enum NT_ERR_HIP_BASE %d\n",
-         NT_OK, NT_ERR_BAD_ARG, NT_ERR_UNSUPPORTED, NT_ERR_WORKSPACE_TOO_SMALL, NT_ERR_HIP_BASE);
+         "enum NT_ERR_TOO_LARGE %d\nenum NT_ERR_HIP_BASE %d\n",
+         NT_OK, NT_ERR_BAD_ARG, NT_ERR_UNSUPPORTED, NT_ERR_WORKSPACE_TOO_SMALL, NT_ERR_TOO_LARGE, NT_ERR_HIP_BASE);
 
   /* host-only calls: two shards of the hand example g_1=(1,2), g_2=(3,6) split per coordinate
    * (coordinate 1: A=10, B=16, C=2; coordinate 2: A=40, B=64, C=8), eta=0.5, ddof=1: T = 10/(0.25*20) = 2 */
@@ -56,6 +57,10 @@ int main(void) {
     printf("resplit %lld %lld %lld\n", (long long)micro, (long long)accum, (long long)glob);
     printf("clip %.17g\n", normtest_clip_coef(4.0, 1.0));
     printf("workspace %zu tile %lld\n", normtest_workspace_bytes(8, 1000000), (long long)normtest_tile_coords(8));
+    printf("workspace_for %zu %zu %zu\n", normtest_workspace_bytes_for(NT_BF16, 64, 1000000, NT_DO_STATS | NT_DO_ADAMW),
+           normtest_workspace_bytes_for(NT_F32, 64, 1000000, NT_DO_STATS | NT_DO_ADAMW),
+           normtest_workspace_bytes(64, 1000000));
+    printf("static_max %lld\n", (long long)normtest_static_max_coords(8));
     printf("strerror %s\n", normtest_strerror(NT_ERR_WORKSPACE_TOO_SMALL));
     if (normtest_layer_stats(NULL, 0, NT_BF16, 8, 100, 100, NULL, 1, NULL, NULL, NULL) != NT_ERR_BAD_ARG) return 4;
   }

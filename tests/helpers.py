@@ -175,22 +175,39 @@ def oracle_adamw_check(grads, d, w0, m0, v0, w1, m1, v1, h: synth.Hyper, ranges=
 
 def oracle_coord_counts(grads, d, h: synth.Hyper, band: float = STATS_RTOL, chunk: int = ORACLE_CHUNK,
                         threads: int | None = None):
-    """(fail, near, pass) counts of the coordinate-wise test over the first d columns, streamed in chunks."""
+    """(fail, near, pass, max_ratio) of the coordinate-wise test over the first d columns, streamed in chunks:
+    the three counts and the largest ratio Var_i / (eta^2 b_k gbar_i^2)."""
     threads = n_threads() if threads is None else threads
     ranges = [(lo, min(d, lo + chunk)) for lo in range(0, d, chunk)]
 
     def work(r):
-        return oracle.coord_test(synth.grads_as_numpy(grads, r[0], r[1]), h.eta, h.b_k, h.ddof, band)
+        G = synth.grads_as_numpy(grads, r[0], r[1])
+        return oracle.coord_test(G, h.eta, h.b_k, h.ddof, band) + (oracle.coord_max_ratio(G, h.eta, h.b_k, h.ddof),)
 
     if len(ranges) <= 1 or threads == 1:
         parts = [work(r) for r in ranges]
     else:
         with ThreadPoolExecutor(threads) as ex:
             parts = list(ex.map(work, ranges))
-    return tuple(sum(p[k] for p in parts) for k in range(3))
+    return tuple(sum(p[k] for p in parts) for k in range(3)) + (max([p[3] for p in parts], default=0.0),)
 
 
 def assert_coord_count(got: int, counts):
     """The kernel decides each coordinate in fp32: coordinates within the band of equality may fall either way."""
-    fail, near, ok = counts
+    fail, near = counts[0], counts[1]
     assert fail <= got <= fail + near, "coord_fail %d not in [%d, %d]" % (got, fail, fail + near)
+
+
+def assert_coord_ratio(got: float, want: float, rtol: float = STATS_RTOL):
+    """Largest coordinate-wise ratio: the kernel forms each ratio in fp32 (about 1e-6 relative), so the largest
+    agrees to the statistics tolerance; an infinite one (spread around an exactly zero mean) must be infinite."""
+    if math.isinf(want):
+        assert got == want, "coord_max_ratio %r, oracle inf" % got
+    else:
+        assert abs(got - want) <= rtol * abs(want), "coord_max_ratio %r, oracle %r" % (got, want)
+
+
+def assert_coord_matches(res: dict, counts):
+    """Count and largest ratio of a result against oracle_coord_counts' 4-tuple."""
+    assert_coord_count(res["coord_fail"], counts)
+    assert_coord_ratio(res["coord_max_ratio"], counts[3])

@@ -63,3 +63,41 @@ def test_product_and_oracle_share_nothing():
     synth = open(os.path.join(pkg, "synth.py")).read()
     for word in ("beta1 *", "sqrt(v", "weight_decay *", "eta *", "ceil("):
         assert word not in synth, word
+
+
+def test_traffic_is_quoted_from_the_tracked_profile_or_absent(tmp_path):
+    """roofline.traffic is never a constant in bench.py: it is the figure the tracked counter profile holds for the
+    kernel source as it stands, and null once the source differs from the profiled one."""
+    import json
+    sys.path.insert(0, ROOT)
+    import bench
+    src = tmp_path / "kernel.hip"
+    src.write_text("// kernel v1\n")
+    prof = tmp_path / "traffic.json"
+    prof.write_text(json.dumps({"kernel_source_sha256": bench.kernel_source_sha256(str(src)),
+                                "entries": {"flat_1p5b/full": {"hbm_bytes_per_step": 60010000000.0}}}))
+    assert bench.traffic_from_profile("flat_1p5b", "full", str(prof), str(src)) == 60010000000.0
+    assert bench.traffic_from_profile("flat_1p5b", "stats", str(prof), str(src)) is None    # not profiled
+    src.write_text("// kernel v2\n")                                                         # the kernel changed
+    assert bench.traffic_from_profile("flat_1p5b", "full", str(prof), str(src)) is None
+    assert bench.traffic_from_profile("flat_1p5b", "full", str(tmp_path / "missing.json"), str(src)) is None
+    # no byte count is written into bench.py itself
+    text = open(os.path.join(ROOT, "bench.py")).read()
+    assert "6.0010e10" not in text and "60010000000" not in text and "MEASURED_TRAFFIC" not in text
+
+
+def test_tracked_traffic_profile_is_well_formed():
+    """If profiles/traffic.json is there, the value bench.py would print is the file's own, for every entry."""
+    import json
+    sys.path.insert(0, ROOT)
+    import bench
+    if not os.path.exists(bench.TRAFFIC_FILE):
+        return
+    prof = json.load(open(bench.TRAFFIC_FILE))
+    assert set(prof) >= {"kernel_source_sha256", "entries", "calibration"}
+    current = prof["kernel_source_sha256"] == bench.kernel_source_sha256()
+    for key, entry in prof["entries"].items():
+        wl, mode = key.split("/")
+        got = bench.traffic_from_profile(wl, mode)
+        assert got == (float(entry["hbm_bytes_per_step"]) if current else None), key
+        assert entry["hbm_bytes_per_step"] == entry["fetch_bytes"] + entry["write_bytes"]

@@ -83,8 +83,9 @@ def check_layers(wl, res, layers, offsets, coord=False):
         if coord:
             fail, near, _ = want["coord"]
             assert fail <= got["coord_fail"] <= fail + near, (tag, got["coord_fail"], fail, near)
+            H.assert_coord_ratio(got["coord_max_ratio"], want["coord_max_ratio"])
         else:
-            assert got["coord_fail"] == -1
+            assert got["coord_fail"] == -1 and got["coord_max_ratio"] == -1.0
     # the layers of a partition add up to the step's own sums (pieces of tiles are re-added coordinate by
     # coordinate, the step adds four fp32 terms at a time: agreement to fp32 rounding, averaged over the piece)
     if offsets[0] == 0 and offsets[-1] == wl.d:
@@ -92,6 +93,7 @@ def check_layers(wl, res, layers, offsets, coord=False):
             assert math.fsum(x[k] for x in layers) == pytest.approx(res[k], rel=1e-7), k
         if coord:
             assert sum(x["coord_fail"] for x in layers) == res["coord_fail"]
+            assert max(x["coord_max_ratio"] for x in layers) == res["coord_max_ratio"]
 
 
 CASES = [

@@ -432,14 +432,15 @@ def test_coordinatewise_count_matches_oracle(J, gdtype, d, sigma, b_k):
     state0 = [t.clone() for t in (wl.w, wl.m, wl.v)]
     plain = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper)
     plain_state = [t.clone() for t in (wl.w, wl.m, wl.v)]
-    assert plain["coord_fail"] == -1
+    assert plain["coord_fail"] == -1 and plain["coord_max_ratio"] == -1.0
     counts = H.oracle_coord_counts(wl.grads, d, wl.hyper)
-    assert sum(counts) == d and counts[1] < max(10, d // 1000)      # the band must stay a thin sliver
+    assert sum(counts[:3]) == d and counts[1] < max(10, d // 1000)      # the band must stay a thin sliver
+    assert counts[3] > 0.0
     for mode_flags in (FULL, B.NT_DO_STATS):
         for t, s0 in zip((wl.w, wl.m, wl.v), state0):
             t.copy_(s0)
         res = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper, flags=mode_flags | B.NT_COORD_TEST)
-        H.assert_coord_count(res["coord_fail"], counts)
+        H.assert_coord_matches(res, counts)
         if mode_flags == FULL:                                          # asking for the count changes nothing else
             for k in ("A", "B", "C", "T", "next_b", "pass", "status"):
                 assert res[k] == plain[k], k
@@ -454,12 +455,12 @@ def test_coordinatewise_count_degenerate_and_sharded():
     same = wl.grads[0:1].repeat(J, 1).contiguous()
     same[:, :100] = 0
     res = gpu_step(same, wl.w, wl.m, wl.v, wl.hyper, flags=B.NT_DO_STATS | B.NT_COORD_TEST)
-    assert res["coord_fail"] == 0
+    assert res["coord_fail"] == 0 and res["coord_max_ratio"] == 0.0
     # zero mean with spread fails whatever the batch size
     same[0, :100] = 1.0
     same[1, :100] = -1.0
     res = gpu_step(same, wl.w, wl.m, wl.v, wl.hyper, flags=B.NT_DO_STATS | B.NT_COORD_TEST)
-    assert res["coord_fail"] == 100
+    assert res["coord_fail"] == 100 and res["coord_max_ratio"] == math.inf
     # shards: counts add up in normtest_combine, and the guarded (misaligned) path counts the same
     whole = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper, flags=B.NT_DO_STATS | B.NT_COORD_TEST)
     cuts = [0, 16384, 2 * 16384, d]
@@ -469,19 +470,23 @@ def test_coordinatewise_count_degenerate_and_sharded():
                             hyper_of(wl.hyper, B.NT_DO_STATS | B.NT_PARTIAL | B.NT_COORD_TEST))
         torch.cuda.synchronize()
         parts.append(B.read_result(r))
-    assert B.normtest_combine(parts, J, hyper_of(wl.hyper)).coord_fail == whole["coord_fail"]
+    comb = B.normtest_combine(parts, J, hyper_of(wl.hyper))
+    assert comb.coord_fail == whole["coord_fail"]
+    # the largest ratio over the shards is the largest of the shards' values, bit for bit
+    assert comb.coord_max_ratio == whole["coord_max_ratio"] == max(p.coord_max_ratio for p in parts)
     big = torch.zeros((J, d + 1), dtype=torch.bfloat16, device=DEV)
     big[:, 1:] = wl.grads
     off = gpu_step(big[:, 1:], wl.w, wl.m, wl.v, wl.hyper, flags=B.NT_DO_STATS | B.NT_COORD_TEST)
-    assert off["coord_fail"] == whole["coord_fail"]
+    assert off["coord_fail"] == whole["coord_fail"] and off["coord_max_ratio"] == whole["coord_max_ratio"]
     # the clipped two-phase step counts too (its statistics phase uses another tile shape)
     gbar = torch.empty(d, dtype=torch.float32, device=DEV)
     r = B.normtest_step_clipped(wl.grads, wl.w, wl.m, wl.v, gbar, 1.0, hyper_of(wl.hyper, FULL | B.NT_COORD_TEST))
     torch.cuda.synchronize()
     assert B.read_result(r).coord_fail == whole["coord_fail"]
+    assert B.read_result(r).coord_max_ratio == whole["coord_max_ratio"]
     r = B.normtest_step_clipped(wl.grads, wl.w, wl.m, wl.v, gbar, 1.0, hyper_of(wl.hyper, FULL))
     torch.cuda.synchronize()
-    assert B.read_result(r).coord_fail == -1
+    assert B.read_result(r).coord_fail == -1 and B.read_result(r).coord_max_ratio == -1.0
 
 
 # ------------------------------------------------------------------ rows given as separate allocations
@@ -685,7 +690,7 @@ def test_structural_sweep_over_entry_points_flags_and_alignment():
                 if not partial:
                     H.assert_decision_matches(r, ref, h)
                 if coord:
-                    H.assert_coord_count(r["coord_fail"], H.oracle_coord_counts(grads, d, h))
+                    H.assert_coord_matches(r, H.oracle_coord_counts(grads, d, h))
                 else:
                     assert r["coord_fail"] == -1
             else:
@@ -725,7 +730,7 @@ def test_maximum_row_count():
     H.assert_stats_close(res, ref)
     H.assert_decision_matches(res, ref, h)
     H.oracle_adamw_check(grads, d, w0, m0, v0, w, m, v, h)
-    H.assert_coord_count(res["coord_fail"], H.oracle_coord_counts(grads, d, h))
+    H.assert_coord_matches(res, H.oracle_coord_counts(grads, d, h))
 
 
 # ------------------------------------------------------------------ memory safety and graph capture
@@ -761,6 +766,36 @@ def test_canaries_around_every_buffer_survive(J, gdtype, flags):
         assert r.status in (0, B.NT_STATUS_NO_STATS)
 
 
+@pytest.mark.parametrize("J,gdtype,flags", [(64, torch.bfloat16, FULL), (64, torch.float32, FULL | B.NT_ONE_PASS),
+                                            (96, torch.bfloat16, FULL | B.NT_ONE_PASS), (96, torch.bfloat16, FULL),
+                                            (64, torch.float32, FULL), (512, torch.bfloat16, B.NT_DO_STATS)])
+def test_workspace_of_exactly_the_size_for_this_call_is_enough(J, gdtype, flags):
+    """normtest_workspace_bytes_for(gdtype, J, d, flags) is what the call needs and all it touches: guard bytes
+    right behind a workspace of exactly that size survive, the result matches the oracle, and bf16 calls below 96
+    rows (or NT_ONE_PASS calls) are not asked for the 4 d bytes of gbar that the general size reserves."""
+    d = 5 * 2048 + 333
+    guard = 512
+    wl = synth.make("t", J, d, gdtype=gdtype, sigma=1e-2, seed=77 + J, device=DEV,
+                    hyper=synth.Hyper(b_k=64, round_to=1, step=5))
+    w0, m0, v0 = wl.w.clone(), wl.m.clone(), wl.v.clone()
+    need = B.normtest_workspace_bytes_for(B._gdtype(wl.grads), J, d, flags)
+    upper = B.normtest_workspace_bytes(J, d)
+    two_pass = flags == FULL and J * wl.grads.element_size() >= 192
+    assert need == upper if two_pass else need <= upper - 4 * d
+    raw = torch.full((guard + need + guard,), 0x5A, dtype=torch.uint8, device=DEV)
+    res = B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hyper_of(wl.hyper, flags), workspace=raw[guard:guard + need])
+    torch.cuda.synchronize()
+    assert bool((raw[:guard] == 0x5A).all()) and bool((raw[guard + need:] == 0x5A).all())
+    got = B.read_result(res).as_dict()
+    ref = H.oracle_full(wl.grads, d, J, wl.hyper)
+    H.assert_stats_close(got, ref)
+    H.assert_decision_matches(got, ref, wl.hyper)
+    if flags & B.NT_DO_ADAMW:
+        H.oracle_adamw_check(wl.grads, d, w0, m0, v0, wl.w, wl.m, wl.v, wl.hyper)
+    with pytest.raises(B.NormtestError):
+        B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hyper_of(wl.hyper, flags), workspace=raw[guard:guard + need - 8])
+
+
 @pytest.mark.parametrize("J,gdtype", [(96, torch.bfloat16), (48, torch.float32), (100, torch.float32),
                                       (257, torch.bfloat16)])
 def test_many_rows_take_two_passes_inside_the_workspace(J, gdtype):
@@ -787,7 +822,7 @@ def test_many_rows_take_two_passes_inside_the_workspace(J, gdtype):
         H.assert_stats_close(got, ref)
         H.assert_decision_matches(got, ref, wl.hyper)
         H.oracle_adamw_check(wl.grads, d, w0, m0, v0, wl.w, wl.m, wl.v, wl.hyper)
-        H.assert_coord_count(got["coord_fail"], H.oracle_coord_counts(wl.grads, d, wl.hyper))
+        H.assert_coord_matches(got, H.oracle_coord_counts(wl.grads, d, wl.hyper))
         # the fused single pass, forced, leaves the same bits in the state and the same result
         w1, m1, v1 = w0.clone(), m0.clone(), v0.clone()
         res1 = B.normtest_step(wl.grads, w1, m1, v1, hyper_of(wl.hyper, FULL | B.NT_COORD_TEST | B.NT_ONE_PASS))

@@ -67,6 +67,7 @@ class Case:
         if self.coord:
             band = 0.0 if self.exact else H.STATS_RTOL
             H.assert_coord_count(self.res["coord_fail"], oracle.coord_test(self.G, h.eta, h.b_k, h.ddof, band))
+            H.assert_coord_ratio(self.res["coord_max_ratio"], oracle.coord_max_ratio(self.G, h.eta, h.b_k, h.ddof))
 
 
 @pytest.fixture(scope="module")
@@ -104,6 +105,17 @@ def cases():
     g = wl.grads.clone()
     g[1] = -g[0]
     add("zero_mean", wl, grads=g, coord=False)
+    # coordinates that carry nothing (all rows zero) next to live ones: their ratio is 0, not 0/0
+    wl = synth.make("s", 8, 12000, gdtype=torch.bfloat16, sigma=1e-2, seed=7, device=DEV, hyper=synth.Hyper(b_k=64, round_to=1))
+    g = wl.grads.clone()
+    g[:, :50] = 0
+    add("dead_coordinates", wl, grads=g)
+    # ... and coordinates whose rows cancel exactly: spread around a zero mean, the largest ratio is infinite
+    g = g.clone()
+    g[:, 50:60] = 0
+    g[0, 50:60] = 1.0
+    g[1, 50:60] = -1.0
+    add("cancelling_coordinates", wl, grads=g)
     # exact equalities (hand example g_1 = (1,2), g_2 = (3,6), eta = 1/2, ddof 0: T = 1; per coordinate ratio 4 at eta 1/4)
     two = torch.tensor([[1.0, 2.0], [3.0, 6.0]], device=DEV)
     z = lambda: torch.zeros(2, device=DEV)

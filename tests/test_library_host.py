@@ -33,9 +33,9 @@ def test_every_declared_symbol_is_exported():
 
 def test_struct_layouts_match_header():
     assert ctypes.sizeof(B.nt_hyper) == 6 * 8 + 4 * 8 + 4 + 4
-    assert ctypes.sizeof(B.nt_result) == 10 * 8 + 8 + 8 + 4 + 4
+    assert ctypes.sizeof(B.nt_result) == 10 * 8 + 8 + 8 + 4 + 4 + 8
     assert ctypes.sizeof(B.nt_shard_info) == 4 + 4 + 8 + 8
-    assert ctypes.sizeof(B.nt_layer_stats) == 6 * 8 + 8 + 8 + 4 + 4
+    assert ctypes.sizeof(B.nt_layer_stats) == 6 * 8 + 8 + 8 + 4 + 4 + 8
 
 
 def test_plain_c_client_sees_the_layout_the_binding_assumes(tmp_path):
@@ -68,13 +68,16 @@ def test_plain_c_client_sees_the_layout_the_binding_assumes(tmp_path):
             n_enum += 1
     for k, cls in mirrors.items():
         assert seen[k] == len(cls._fields_), k          # every field of the mirror exists in the header and back
-    assert n_enum == 20
-    lines = {l.split()[0]: l.split()[1:] for l in out if l.split()[0] in ("combine", "resplit", "clip", "workspace", "tile", "strerror")}
+    assert n_enum == 21
+    lines = {l.split()[0]: l.split()[1:] for l in out if l.split()[0] in ("combine", "resplit", "clip", "workspace", "workspace_for", "static_max", "strerror")}
     A, Bv, C, T, passed, next_b = lines["combine"]
     assert (float(A), float(Bv), float(C), float(T), int(passed), int(next_b)) == (50.0, 80.0, 10.0, 2.0, 0, 2)
     assert [int(x) for x in lines["resplit"]] == [8, 256, 8192]
     assert float(lines["clip"][0]) == pytest.approx(1.0 / (2.0 + 1e-6), rel=1e-15)
     assert int(lines["workspace"][0]) == B.normtest_workspace_bytes(8, 1000000) and int(lines["workspace"][2]) == 16384
+    bf16_64, f32_64, any_64 = (int(x) for x in lines["workspace_for"])
+    assert bf16_64 < f32_64 == any_64 and f32_64 - bf16_64 == 4 * 1000000 + 16
+    assert int(lines["static_max"][0]) == B.normtest_static_max_coords(8)
 
 
 def test_workspace_and_tiles():
@@ -86,15 +89,45 @@ def test_workspace_and_tiles():
             need = B.normtest_workspace_bytes(J, d)
             if J >= 48:          # many rows: room for an fp32 gbar behind the partials (two-pass route)
                 need -= (4 * d + 15) // 16 * 16 + 16
-            # a 128-byte record, four doubles per tile (tiles are at most tc and at least 1024 coordinates), and
+            # a 256-byte record, five doubles per tile (tiles are at most tc and at least 1024 coordinates), and
             # a small second level
-            lo = 128 + 32 * max(1, -(-d // tc))
-            hi = 128 + 32 * max(1, -(-d // 1024))
+            lo = 256 + 40 * max(1, -(-d // tc))
+            hi = 256 + 40 * max(1, -(-d // 1024))
             assert lo <= need <= hi + hi // 256 + 64
             assert need >= prev and need % 8 == 0 and B.normtest_workspace_bytes(J, d) % 8 == 0
             prev = need
     assert B.normtest_tile_coords(1) == 0
     assert B.normtest_workspace_bytes(1, 10) == 0 and B.normtest_workspace_bytes(4, -1) == 0
+
+
+def test_workspace_size_for_a_known_call():
+    """The size for a known dtype and flags never exceeds the general one; the 4 d bytes for gbar are asked for
+    only where the two-pass route runs and has to keep gbar itself."""
+    full = B.NT_DO_STATS | B.NT_DO_ADAMW
+    d = 3_000_001
+    gbar = (4 * d + 15) // 16 * 16 + 16
+    for J in (2, 16, 47, 48, 95, 96, 512):
+        upper = B.normtest_workspace_bytes(J, d)
+        base = B.normtest_workspace_bytes_for(B.NT_BF16, J, d, B.NT_DO_STATS)
+        for gd, esize in ((B.NT_BF16, 2), (B.NT_F32, 4)):
+            two_pass = J * esize >= 192
+            assert B.normtest_workspace_bytes_for(gd, J, d, full) == base + (gbar if two_pass else 0)
+            for flags in (full | B.NT_ONE_PASS, full | B.NT_WRITE_GBAR, B.NT_DO_STATS, B.NT_DO_ADAMW,
+                          B.NT_DO_STATS | B.NT_PARTIAL | B.NT_WRITE_GBAR):
+                assert B.normtest_workspace_bytes_for(gd, J, d, flags) == base
+            assert B.normtest_workspace_bytes_for(gd, J, d, full) <= upper
+        assert upper == base + (gbar if J >= 48 else 0)
+    assert B.normtest_workspace_bytes_for(7, 8, 100, full) == 0
+    assert B.normtest_workspace_bytes_for(B.NT_BF16, 1, 100, full) == 0
+    # the step checks exactly this size: a bf16 call with 64 rows is accepted with the smaller workspace ...
+    hy = B.make_hyper(step=1, b_k=32, flags=full)
+    small = B.normtest_workspace_bytes_for(B.NT_BF16, 64, 1 << 20, full)
+    assert small < B.normtest_workspace_bytes(64, 1 << 20)
+    assert _call(J=64, d=1 << 20, gdtype=B.NT_BF16, hyper=hy, ws_bytes=small - 8) == B.NT_ERR_WORKSPACE_TOO_SMALL
+    # ... and an fp32 call with as many rows is told that it is too small
+    assert _call(J=64, d=1 << 20, gdtype=B.NT_F32, hyper=hy, ws_bytes=small) == B.NT_ERR_WORKSPACE_TOO_SMALL
+    one = B.make_hyper(step=1, b_k=32, flags=full | B.NT_ONE_PASS)
+    assert _call(J=64, d=1 << 20, gdtype=B.NT_F32, hyper=one, ws_bytes=small - 8) == B.NT_ERR_WORKSPACE_TOO_SMALL
 
 
 def _call(J=4, d=64, ld=None, gdtype=B.NT_F32, grads=0x1000, w=0x2000, m=0x3000, v=0x4000, gbar=None,
@@ -179,9 +212,9 @@ def test_static_entry_point_validates_before_launch():
 
     for J in (2, 8, 16, 17, 512):
         top = B.normtest_static_max_coords(J)
-        assert top > 10 ** 9
+        assert top > (16 * 10 ** 8 if J <= 16 else 8 * 10 ** 8)    # the headline size fits
         assert call(J=J, d=top + 1) == B.NT_ERR_TOO_LARGE
-        assert B.normtest_workspace_bytes(J, top) - (4 * top + 32 if J >= 48 else 0) <= 16 << 20
+        assert B.normtest_workspace_bytes_for(B.NT_BF16, J, top, B.NT_DO_STATS) <= 16 << 20
     assert B.normtest_static_max_coords(1) == 0
     assert call(J=1) == B.NT_ERR_BAD_ARG
     assert call(d=-1) == B.NT_ERR_BAD_ARG
@@ -404,10 +437,15 @@ def test_combine_adds_shards_in_double_double():
 
 def test_combine_adds_coordinate_counts():
     hy = B.make_hyper(eta=0.1, b_k=32)
-    parts = [B.nt_result(A=1.0, B=1.0, C=1.0, coord_fail=k) for k in (3, 0, 11)]
-    assert B.normtest_combine(parts, 4, hy).coord_fail == 14
+    parts = [B.nt_result(A=1.0, B=1.0, C=1.0, coord_fail=k, coord_max_ratio=r) for k, r in ((3, 2.5), (0, 0.75), (11, 40.0))]
+    out = B.normtest_combine(parts, 4, hy)
+    assert out.coord_fail == 14 and out.coord_max_ratio == 40.0          # counts add, the largest ratio is the largest
+    parts[0].coord_max_ratio = math.inf
+    assert B.normtest_combine(parts, 4, hy).coord_max_ratio == math.inf
     parts[1].coord_fail = -1
-    assert B.normtest_combine(parts, 4, hy).coord_fail == -1
+    parts[1].coord_max_ratio = -1.0
+    out = B.normtest_combine(parts, 4, hy)
+    assert out.coord_fail == -1 and out.coord_max_ratio == -1.0           # missing in one shard: missing in the total
 
 
 def test_combine_rejects_bad_input():
