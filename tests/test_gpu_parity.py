@@ -961,3 +961,62 @@ def test_calib_copy():
     B.normtest_calib_copy(dst, src)
     torch.cuda.synchronize()
     assert torch.equal(src, dst)
+
+
+def test_calib_streams_touches_only_its_streams():
+    """The stream-mix yardstick: written streams change, read streams and the bytes behind the declared size do
+    not; in-place streams keep the exclusive-or structure (a second call restores nothing but stays in bounds);
+    unsupported mixes and short buffers are refused before any launch."""
+    coords = 3 * 4096 + 8
+    for row_reads, reads, writes, rmw in ((8, 0, 3, True), (0, 11, 3, False), (16, 0, 0, False), (0, 0, 1, False), (8, 3, 3, False)):
+        need = B.calib_streams_bytes(coords, row_reads, reads, writes)
+        guard = 4096
+        buf = torch.randint(0, 255, (need + guard,), dtype=torch.uint8, device=DEV)
+        before = buf.clone()
+        B.normtest_calib_streams(buf[:need], coords, row_reads, reads, writes, rmw)
+        torch.cuda.synchronize()
+        r2 = (coords * 2 + 255) // 256 * 256
+        r4 = (coords * 4 + 255) // 256 * 256
+        read_end = row_reads * r2 + reads * r4
+        assert torch.equal(buf[:read_end], before[:read_end])                       # read streams untouched
+        assert torch.equal(buf[need - 16:], before[need - 16:])                      # spare word and guard untouched
+        for k in range(writes):
+            lo = read_end + k * r4
+            assert not torch.equal(buf[lo:lo + 4 * coords], before[lo:lo + 4 * coords])   # written
+            assert torch.equal(buf[lo + 4 * coords:lo + r4], before[lo + 4 * coords:lo + r4])  # padding of the stream
+    small = torch.zeros(1 << 16, dtype=torch.uint8, device=DEV)
+    for args, code in (((coords, 8, 0, 3, True), B.NT_ERR_WORKSPACE_TOO_SMALL), ((4, 7, 0, 3, True), B.NT_ERR_UNSUPPORTED),
+                       ((4, 0, 0, 0, False), B.NT_ERR_UNSUPPORTED), ((5, 0, 1, 0, False), B.NT_ERR_BAD_ARG),
+                       ((4, 17, 0, 0, False), B.NT_ERR_UNSUPPORTED)):
+        with pytest.raises(B.NormtestError) as e:
+            B.normtest_calib_streams(small, *args)
+        assert e.value.code == code, args
+
+
+def test_long_row_table_with_one_misaligned_row_at_the_end():
+    """300 separately allocated rows: the alignment of all of them is checked once per call by a small kernel
+    (more rows than that kernel has threads); a single row off by one element, the last one, must send the whole
+    call down the guarded path, with the same bits as the aligned call and as the strided matrix."""
+    J, d = 300, 2 * 2048 + 100
+    wl = synth.make("t", J, d, gdtype=torch.bfloat16, sigma=1e-2, seed=91, device=DEV, hyper=synth.Hyper(b_k=512, round_to=1))
+    state0 = [t.clone() for t in (wl.w, wl.m, wl.v)]
+    ref = gpu_step(wl.grads, wl.w, wl.m, wl.v, wl.hyper, flags=FULL | B.NT_COORD_TEST)
+    ref_state = [t.clone() for t in (wl.w, wl.m, wl.v)]
+    oracle_ref = H.oracle_full(wl.grads, d, J, wl.hyper)
+    H.assert_stats_close(ref, oracle_ref)
+    H.assert_decision_matches(ref, oracle_ref, wl.hyper)
+    for misaligned_row in (None, J - 1):
+        rows = []
+        for j in range(J):
+            buf = torch.zeros(d + 16, dtype=torch.bfloat16, device=DEV)
+            off = 1 if j == misaligned_row else 0
+            rows.append(buf[off:off + d])
+            rows[-1].copy_(wl.grads[j, :d])
+        assert all(r.data_ptr() % 16 == 0 for r in rows[:J - 1]) and (rows[-1].data_ptr() % 16 == 0) == (misaligned_row is None)
+        for t, s0 in zip((wl.w, wl.m, wl.v), state0):
+            t.copy_(s0)
+        res = B.normtest_step_rows(rows, wl.w, wl.m, wl.v, hyper_of(wl.hyper, FULL | B.NT_COORD_TEST))
+        torch.cuda.synchronize()
+        assert B.read_result(res).as_dict() == ref
+        for a, b in zip((wl.w, wl.m, wl.v), ref_state):
+            assert torch.equal(a, b)
