@@ -73,3 +73,41 @@ def test_static_entry_point_rejects_what_does_not_fit():
     assert "scratch" in B.normtest_strerror(rc)
     torch.cuda.synchronize()
     assert not res.any()
+
+
+def test_static_entry_point_under_graph_capture():
+    """What the entry point is for: captured in a HIP graph (it records kernel launches only: no allocation, no
+    memset), every replay, with eager work in between, reproduces the eager results of normtest_step bit for bit."""
+    dev = "cuda:0"
+    wl = synth.make("noalloc_graph", 8, 5 * 16384 + 99, gdtype=torch.bfloat16, seed=9, device=dev,
+                    hyper=synth.Hyper(b_k=256, round_to=128, b_max=8192, step=10))
+    hy = hyper_of(wl.hyper, B.NT_DO_STATS | B.NT_DO_ADAMW)
+    state0 = [t.clone() for t in (wl.w, wl.m, wl.v)]
+    eager = []
+    for _ in range(2):                                   # reference: two consecutive steps of the workspace entry point
+        res = B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hy)
+        torch.cuda.synchronize()
+        eager.append((bytes(B.read_result(res)), [t.clone() for t in (wl.w, wl.m, wl.v)]))
+    for t, s in zip((wl.w, wl.m, wl.v), state0):
+        t.copy_(s)
+    result = torch.zeros(B.RESULT_BYTES, dtype=torch.uint8, device=dev)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        B.normtest_step_static(wl.grads, wl.w, wl.m, wl.v, hy, result, stream=side)      # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.normtest_step_static(wl.grads, wl.w, wl.m, wl.v, hy, result, stream=torch.cuda.current_stream())
+    for rounds in range(2):
+        for t, s in zip((wl.w, wl.m, wl.v), state0):
+            t.copy_(s)
+        for k in range(2):
+            result.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert bytes(B.read_result(result)) == eager[k][0]
+            for a, b in zip((wl.w, wl.m, wl.v), eager[k][1]):
+                assert torch.equal(a, b)
+            _ = (torch.randn(1 << 16, device=dev) * 2).sum().item()     # unrelated eager work between replays
