@@ -815,8 +815,8 @@ __device__ inline void block_totals(const double* in, int64_t n, bool packed, do
 // group partial.  The two stages are separate launches on purpose: the eight XCDs of this GPU do not share an
 // L2, so a block that waits for the other blocks' partials inside one kernel (a ticket taken after a device-wide
 // release, then a device-wide acquire) pays a write-back and an invalidation of its L2 on every block; measured,
-// that made the single launch slower (26 us at 15 groups) than the two small kernels it replaced (7 + 10 us),
-// whose visibility comes with the kernel boundary.
+// that made the single launch slower (26 us at 15 groups) than these two small kernels (8 + 5 us), whose
+// visibility comes with the kernel boundary.
 __global__ __launch_bounds__(NT_GROUP_THREADS) void k_reduce_groups(const double* tiles, int64_t ntiles, double* groups) {
   __shared__ double sh[NT_GROUP_THREADS / 64][2 * NT_NV];
   const int64_t t0 = (int64_t)blockIdx.x * NT_GROUP_TILES;
