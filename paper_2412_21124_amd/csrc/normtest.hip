@@ -41,6 +41,16 @@
 #define NT_BLOCK_LARGE 256       // J > 16 (rows are walked inside each sweep), all modes
 #define NT_ITERS_LARGE 2
 #define NT_BLOCKS_PER_CU 4096    // grid = min(tiles, CUs * this); blocks stride over tiles beyond that
+// A long vector is walked by several launches of the step kernel, each over a run of consecutive tiles.  Blocks
+// that start together move through their load and store phases together, so the memory system sees chip-wide
+// bursts of reads and of writes instead of an even mix, which it serves faster; inside one long launch that
+// lockstep drifts apart within some tens of block generations.  A kernel boundary restores it at the price of a
+// drained machine for a few microseconds.  Coordinates per launch, by class (measured; 0: one launch):
+#define NT_CHUNK_FULL (1ll << 27)        // J <= 16, fused step (+3 % at d = 1.5e9, +1 % at 16 rows)
+#define NT_CHUNK_ADAMW (1ll << 25)       // J <= 16, AdamW only (+5 %)
+#define NT_CHUNK_STATS_GBAR (1ll << 27)  // J <= 16, statistics + stored gbar (+2 % on the clipped step)
+#define NT_CHUNK_STATS 0                 // statistics only: nothing is written, nothing to gain
+#define NT_CHUNK_LARGE (1ll << 23)       // J > 16, modes that update the state in the same pass (+7 % at 64 rows)
 
 #define NT_VEC 4              // coordinates per lane and sweep: 16-byte fp32 accesses, 8-byte bf16 row loads
 #define NT_TILE_MAX 16384     // every tile size divides this: the alignment that keeps shard results bit-identical
@@ -582,14 +592,16 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
 }
 
 // ---------------------------------------------------------------------------------------------
-// Kernels.  Block b takes tiles b, b + gridDim.x, ...; tiles below nfull are whole and aligned (fast
-// path), the others go through the guarded path.  When the vector ends in a ragged tile, block 0
-// takes it first so that the slow tile overlaps with everything else.
+// Kernels.  A launch covers the slots slot0 .. slot1-1 of the ntiles tile slots; block b takes slots slot0 + b,
+// slot0 + b + gridDim.x, ...; tiles below nfull are whole and aligned (fast path), the others go through the
+// guarded path.  When the vector ends in a ragged tile, it has slot 0, so that the slow tile overlaps with
+// everything else.
 // J_T = 0 selects the J > 16 row-walking variant.
 // ---------------------------------------------------------------------------------------------
 // GBAR = false compiles the gbar store out (statistics-only launch class, so that sweeps can overlap).
 template <class GT, int J_T, int MODE, int BLOCK, int ITERS, bool TABLE, bool GBAR>
-__global__ __launch_bounds__(BLOCK) void k_step(StepParams p, int64_t nfull, int64_t ntiles, WsControl* ctl) {
+__global__ __launch_bounds__(BLOCK) void k_step(StepParams p, int64_t nfull, int64_t ntiles, int64_t slot0, int64_t slot1,
+                                                 WsControl* ctl) {
   constexpr int TILE = BLOCK * GT::VEC * ITERS;
   static_assert(NT_TILE_MAX % TILE == 0, "tile sizes must divide NT_TILE_MAX");
   __shared__ double red[2][BLOCK / 64][NT_NV];
@@ -599,7 +611,7 @@ __global__ __launch_bounds__(BLOCK) void k_step(StepParams p, int64_t nfull, int
     if (!ctl->rows_aligned) nfull = 0;
   }
   const int64_t nrest = ntiles - nfull;  // guarded tiles (0 or 1 on the aligned path)
-  for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+  for (int64_t t = slot0 + blockIdx.x; t < slot1; t += gridDim.x) {
     // rotate: the first nrest slots are the guarded tiles nfull.., then the fast tiles 0..nfull-1
     const int64_t tile = (t < nrest) ? nfull + t : t - nrest;
     if (tile < nfull) {
@@ -1111,6 +1123,18 @@ inline TileCfg tile_cfg(int64_t J, int mode, bool gbar) {
   if (mode == MODE_ADAMW) return {NT_BLOCK_ADAMW, NT_ITERS_ADAMW};
   return {NT_BLOCK, NT_ITERS};
 }
+// tile slots per launch of the step kernel for the same classes (at least one, at most all)
+inline int64_t launch_tiles(int64_t J, int mode, bool gbar, int64_t ntiles) {
+  int64_t coords;
+  if (J > NT_JCHUNK)
+    coords = (mode == MODE_STATS) ? NT_CHUNK_STATS : NT_CHUNK_LARGE;
+  else if (mode == MODE_STATS)
+    coords = gbar ? NT_CHUNK_STATS_GBAR : NT_CHUNK_STATS;
+  else
+    coords = (mode == MODE_ADAMW) ? NT_CHUNK_ADAMW : NT_CHUNK_FULL;
+  const int64_t n = coords / tile_cfg(J, mode, gbar).coords();
+  return (n < 1 || n > ntiles) ? ntiles : n;
+}
 // smallest tile any mode uses for this J: sizes the workspace
 inline int64_t min_tile_coords(int64_t J) {
   int64_t best = tile_cfg(J, MODE_FULL, false).coords();
@@ -1144,22 +1168,29 @@ bool hyper_ok(const nt_hyper* h, int64_t J) {
 }
 
 template <class GT, int MODE, bool TABLE, int BS, int IS, bool GBAR>
-hipError_t launch_step_shape(const StepParams& p, int64_t nfull, int64_t ntiles, WsControl* ctl, int grid,
+hipError_t launch_step_shape(const StepParams& p, int64_t nfull, int64_t ntiles, WsControl* ctl, int max_grid,
                              hipStream_t st) {
+  const int64_t per_launch = launch_tiles(p.J, MODE, MODE == MODE_STATS && p.gbar != nullptr, ntiles);
+  for (int64_t slot0 = 0; slot0 < ntiles; slot0 += per_launch) {
+    const int64_t slot1 = (ntiles - slot0 < per_launch) ? ntiles : slot0 + per_launch;
+    const unsigned grid = (unsigned)((slot1 - slot0 < max_grid) ? slot1 - slot0 : max_grid);
 #define NT_CASE(JJ)                                                                                             \
   case JJ:                                                                                                      \
     hipLaunchKernelGGL((k_step<GT, JJ, MODE, BS, IS, TABLE, GBAR>), dim3(grid), dim3(BS), 0, st, p, nfull,      \
-                       ntiles, ctl);                                                                            \
+                       ntiles, slot0, slot1, ctl);                                                              \
     break;
-  switch (p.J) {
-    NT_CASE(2) NT_CASE(3) NT_CASE(4) NT_CASE(5) NT_CASE(6) NT_CASE(7) NT_CASE(8) NT_CASE(9)
-    NT_CASE(10) NT_CASE(11) NT_CASE(12) NT_CASE(13) NT_CASE(14) NT_CASE(15) NT_CASE(16)
-    default:
-      hipLaunchKernelGGL((k_step<GT, 0, MODE, NT_BLOCK_LARGE, NT_ITERS_LARGE, TABLE, true>), dim3(grid),
-                         dim3(NT_BLOCK_LARGE), 0, st, p, nfull, ntiles, ctl);
-  }
+    switch (p.J) {
+      NT_CASE(2) NT_CASE(3) NT_CASE(4) NT_CASE(5) NT_CASE(6) NT_CASE(7) NT_CASE(8) NT_CASE(9)
+      NT_CASE(10) NT_CASE(11) NT_CASE(12) NT_CASE(13) NT_CASE(14) NT_CASE(15) NT_CASE(16)
+      default:
+        hipLaunchKernelGGL((k_step<GT, 0, MODE, NT_BLOCK_LARGE, NT_ITERS_LARGE, TABLE, true>), dim3(grid),
+                           dim3(NT_BLOCK_LARGE), 0, st, p, nfull, ntiles, slot0, slot1, ctl);
+    }
 #undef NT_CASE
-  return hipGetLastError();
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 // picks the launch class (block size, sweeps per tile) that tile_cfg() describes
