@@ -302,10 +302,12 @@ int normtest_calib_copy(void* dst, const void* src, size_t bytes, void* hip_stre
  * multiple of 256; contents are irrelevant and are overwritten.  Supported mixes (else NT_ERR_UNSUPPORTED):
  * row_reads = 0 with reads in {0, 1, 2, 4, 8, 11} and writes in {0..3} (not both 0), rmw = 0; 1 or 3 in-place
  * streams alone; row_reads in {4, 8, 16} alone or with 3 in-place streams; 8 row reads + 1 write; 8 row reads +
- * 3 reads + 3 writes.  Enqueued on the stream.
+ * 3 reads + 3 writes.  launch_coords > 0 (a multiple of 4): the walk is split into kernel launches of that many
+ * coordinates each (rounded down to whole 4096-coordinate blocks), the way normtest_step walks a long vector;
+ * 0: one launch.  Enqueued on the stream.
  */
 int normtest_calib_streams(void* buf, size_t buf_bytes, int64_t coords, int row_reads, int reads, int writes,
-                           int rmw, void* hip_stream);
+                           int rmw, int64_t launch_coords, void* hip_stream);
 
 /* Static, human-readable text for a return code. */
 const char* normtest_strerror(int code);

@@ -131,7 +131,7 @@ def lib(path: Optional[str] = None):
         L.normtest_calib_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.normtest_calib_copy.restype = ctypes.c_int
         L.normtest_calib_streams.argtypes = [vp, ctypes.c_size_t, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                             ctypes.c_int, vp]
+                                             ctypes.c_int, i64, vp]
         L.normtest_calib_streams.restype = ctypes.c_int
         L.normtest_strerror.argtypes = [ctypes.c_int]
         L.normtest_strerror.restype = ctypes.c_char_p
@@ -452,11 +452,11 @@ def calib_streams_bytes(coords: int, row_reads: int, reads: int, writes: int) ->
 
 
 def normtest_calib_streams(buf: torch.Tensor, coords: int, row_reads: int, reads: int, writes: int, rmw: bool = False,
-                           stream: Optional[torch.cuda.Stream] = None) -> None:
+                           launch_coords: int = 0, stream: Optional[torch.cuda.Stream] = None) -> None:
     if stream is None:
         stream = torch.cuda.current_stream(buf.device)
     with torch.cuda.device(buf.device):
         rc = lib().normtest_calib_streams(_ptr(buf), buf.numel() * buf.element_size(), coords, row_reads, reads, writes,
-                                          1 if rmw else 0, ctypes.c_void_p(stream.cuda_stream))
+                                          1 if rmw else 0, launch_coords, ctypes.c_void_p(stream.cuda_stream))
     if rc != NT_OK:
         raise NormtestError(rc, "normtest_calib_streams")

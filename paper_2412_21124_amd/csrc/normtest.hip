@@ -50,6 +50,7 @@
 #define NT_CHUNK_ADAMW (1ll << 25)       // J <= 16, AdamW only (+5 %)
 #define NT_CHUNK_STATS_GBAR (1ll << 27)  // J <= 16, statistics + stored gbar (+2 % on the clipped step)
 #define NT_CHUNK_STATS 0                 // statistics only: nothing is written, nothing to gain
+#define NT_CHUNK_ADAMW_GBAR (1ll << 25)  // AdamW from a stored gbar (second phase of the clipped and two-pass steps)
 #define NT_CHUNK_LARGE (1ll << 23)       // J > 16, modes that update the state in the same pass (+7 % at 64 rows)
 
 #define NT_VEC 4              // coordinates per lane and sweep: 16-byte fp32 accesses, 8-byte bf16 row loads
@@ -1014,10 +1015,10 @@ __global__ __launch_bounds__(NT_LAYER_THREADS) void k_layer_stats(StepParams p, 
 // 4 coordinates per lane; lanes whose 4 coordinates are not all below d, or unaligned buffers, go
 // element by element.
 __global__ __launch_bounds__(NT_AUX_BLOCK) void k_adamw_gbar(StepParams p, const float* gbar, float grad_scale,
-                                                         const nt_result* res, int aligned) {
+                                                         const nt_result* res, int aligned, int64_t block0) {
   float scale = grad_scale;
   if (res) scale *= (float)res->clip_coef;
-  const int64_t i0 = ((int64_t)blockIdx.x * NT_AUX_BLOCK + threadIdx.x) * NT_VEC;
+  const int64_t i0 = ((block0 + blockIdx.x) * NT_AUX_BLOCK + threadIdx.x) * NT_VEC;
   if (i0 >= p.d) return;
   if (aligned && i0 + NT_VEC <= p.d) {
     const u32x4 sg = ld16(gbar + i0);
@@ -1063,8 +1064,8 @@ struct CalibStreams {
 };
 
 template <int R8, int R16, int W, bool RMW>
-__global__ __launch_bounds__(NT_AUX_BLOCK) void k_calib_streams(CalibStreams s, int64_t ngroups) {
-  for (int64_t i = (int64_t)blockIdx.x * NT_AUX_BLOCK + threadIdx.x; i < ngroups; i += (int64_t)gridDim.x * NT_AUX_BLOCK) {
+__global__ __launch_bounds__(NT_AUX_BLOCK) void k_calib_streams(CalibStreams s, int64_t group0, int64_t group1) {
+  for (int64_t i = group0 + (int64_t)blockIdx.x * NT_AUX_BLOCK + threadIdx.x; i < group1; i += (int64_t)gridDim.x * NT_AUX_BLOCK) {
     u32x2 a[R8 > 0 ? R8 : 1];
     u32x4 b[R16 > 0 ? R16 : 1];
     u32x4 c[W > 0 ? W : 1];
@@ -1411,10 +1412,17 @@ static int enqueue_adamw_gbar(const float* gbar, int64_t d, float* w, float* m, 
   fill_adamw_params(p, hyper);
   const int aligned = aligned16(gbar) && aligned16(w) && aligned16(m) && aligned16(v);
   const int64_t per_block = (int64_t)NT_AUX_BLOCK * NT_VEC;
-  const int64_t grid = (d + per_block - 1) / per_block;
-  hipLaunchKernelGGL(k_adamw_gbar, dim3((unsigned)grid), dim3(NT_AUX_BLOCK), 0, st, p, gbar, (float)grad_scale, result_dev,
-                     aligned);
-  return hip_code(hipGetLastError());
+  const int64_t nblocks = (d + per_block - 1) / per_block;
+  // in runs of blocks, like the step kernel (see NT_CHUNK_FULL)
+  const int64_t per_launch = NT_CHUNK_ADAMW_GBAR / per_block;
+  for (int64_t b0 = 0; b0 < nblocks; b0 += per_launch) {
+    const int64_t grid = (nblocks - b0 < per_launch) ? nblocks - b0 : per_launch;
+    hipLaunchKernelGGL(k_adamw_gbar, dim3((unsigned)grid), dim3(NT_AUX_BLOCK), 0, st, p, gbar, (float)grad_scale,
+                       result_dev, aligned, b0);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_code(e);
+  }
+  return NT_OK;
 }
 
 // The step as the caller's flags describe it: one fused pass, or for many rows (two_phase) the statistics
@@ -1667,8 +1675,9 @@ int normtest_calib_copy(void* dst, const void* src, size_t bytes, void* hip_stre
 }
 
 int normtest_calib_streams(void* buf, size_t buf_bytes, int64_t coords, int row_reads, int reads, int writes, int rmw,
-                           void* hip_stream) {
-  if (!buf || !aligned16(buf) || coords < 0 || (coords & 3) || row_reads < 0 || reads < 0 || writes < 0)
+                           int64_t launch_coords, void* hip_stream) {
+  if (!buf || !aligned16(buf) || coords < 0 || (coords & 3) || row_reads < 0 || reads < 0 || writes < 0 ||
+      launch_coords < 0 || (launch_coords & 3))
     return NT_ERR_BAD_ARG;
   if (row_reads > NT_CALIB_MAX_R8 || reads > NT_CALIB_MAX_R16 || writes > NT_CALIB_MAX_W || row_reads + reads + writes == 0)
     return NT_ERR_UNSUPPORTED;
@@ -1685,14 +1694,21 @@ int normtest_calib_streams(void* buf, size_t buf_bytes, int64_t coords, int row_
   for (int k = 0; k < writes; ++k, at += vec_bytes) s.w[k] = at;
   s.sink = (uint32_t*)at;
   const int64_t ngroups = coords / 4;
-  const int64_t want = (ngroups + NT_AUX_BLOCK - 1) / NT_AUX_BLOCK;
+  // like the step kernel, in launches over runs of consecutive coordinates (whole blocks) if the caller says so
+  const int64_t per_block = NT_AUX_BLOCK;
+  int64_t per_launch = launch_coords > 0 ? launch_coords / 4 / per_block * per_block : ngroups;
+  if (per_launch < per_block) per_launch = per_block;
   const int64_t max_grid = (int64_t)cu_count() * NT_BLOCKS_PER_CU;
-  const int grid = (int)(want < max_grid ? want : max_grid);
   hipStream_t st = (hipStream_t)hip_stream;
   bool found = false;
 #define NT_CALIB(R8, R16, W, RMW)                                                                                  \
   if (!found && row_reads == R8 && reads == R16 && writes == W && (rmw != 0) == RMW) {                              \
-    hipLaunchKernelGGL((k_calib_streams<R8, R16, W, RMW>), dim3(grid), dim3(NT_AUX_BLOCK), 0, st, s, ngroups);     \
+    for (int64_t g0 = 0; g0 < ngroups; g0 += per_launch) {                                                         \
+      const int64_t g1 = (ngroups - g0 < per_launch) ? ngroups : g0 + per_launch;                                  \
+      const int64_t want = (g1 - g0 + per_block - 1) / per_block;                                                  \
+      const int grid = (int)(want < max_grid ? want : max_grid);                                                   \
+      hipLaunchKernelGGL((k_calib_streams<R8, R16, W, RMW>), dim3(grid), dim3(NT_AUX_BLOCK), 0, st, s, g0, g1);    \
+    }                                                                                                              \
     found = true;                                                                                                  \
   }
 #define NT_CALIB_ROW(R16) NT_CALIB(0, R16, 0, false) NT_CALIB(0, R16, 1, false) NT_CALIB(0, R16, 2, false) NT_CALIB(0, R16, 3, false)

@@ -968,13 +968,21 @@ def test_calib_streams_touches_only_its_streams():
     not; in-place streams keep the exclusive-or structure (a second call restores nothing but stays in bounds);
     unsupported mixes and short buffers are refused before any launch."""
     coords = 3 * 4096 + 8
-    for row_reads, reads, writes, rmw in ((8, 0, 3, True), (0, 11, 3, False), (16, 0, 0, False), (0, 0, 1, False), (8, 3, 3, False)):
+    for row_reads, reads, writes, rmw, lc in ((8, 0, 3, True, 0), (0, 11, 3, False, 0), (16, 0, 0, False, 0), (0, 0, 1, False, 0),
+                                              (8, 3, 3, False, 0), (8, 0, 3, True, 4096), (8, 0, 3, True, 8192 + 4),
+                                              (0, 2, 2, False, 4)):
         need = B.calib_streams_bytes(coords, row_reads, reads, writes)
         guard = 4096
         buf = torch.randint(0, 255, (need + guard,), dtype=torch.uint8, device=DEV)
         before = buf.clone()
-        B.normtest_calib_streams(buf[:need], coords, row_reads, reads, writes, rmw)
+        B.normtest_calib_streams(buf[:need], coords, row_reads, reads, writes, rmw, launch_coords=lc)
         torch.cuda.synchronize()
+        if lc:
+            # split into several launches the walk leaves the same bytes as in one
+            once = before.clone()
+            B.normtest_calib_streams(once[:need], coords, row_reads, reads, writes, rmw)
+            torch.cuda.synchronize()
+            assert torch.equal(buf, once), (row_reads, reads, writes, rmw, lc)
         r2 = (coords * 2 + 255) // 256 * 256
         r4 = (coords * 4 + 255) // 256 * 256
         read_end = row_reads * r2 + reads * r4

@@ -229,7 +229,7 @@ def test_calib_streams_validates_before_launch():
     """The yardstick refuses unsupported mixes, ragged sizes and short buffers without touching the GPU."""
     L = B.lib()
     coords = 3 * 4096 + 8
-    call = lambda buf, nbytes, c, a, r, w, rmw: L.normtest_calib_streams(buf, nbytes, c, a, r, w, rmw, None)
+    call = lambda buf, nbytes, c, a, r, w, rmw, lc=0: L.normtest_calib_streams(buf, nbytes, c, a, r, w, rmw, lc, None)
     assert call(0x10000, 1 << 16, coords, 8, 0, 3, 1) == B.NT_ERR_WORKSPACE_TOO_SMALL
     assert call(0x10000, B.calib_streams_bytes(coords, 8, 0, 3) - 1, coords, 8, 0, 3, 1) == B.NT_ERR_WORKSPACE_TOO_SMALL
     assert call(0x10000, 1 << 16, 4, 7, 0, 3, 1) == B.NT_ERR_UNSUPPORTED       # no kernel for 7 row reads
@@ -238,6 +238,8 @@ def test_calib_streams_validates_before_launch():
     assert call(0x10000, 1 << 16, 4, 17, 0, 0, 0) == B.NT_ERR_UNSUPPORTED
     assert call(0x10000, 1 << 16, 5, 0, 1, 0, 0) == B.NT_ERR_BAD_ARG           # coords not a multiple of 4
     assert call(0x10008, 1 << 16, 4, 0, 1, 0, 0) == B.NT_ERR_BAD_ARG           # buffer not 16-byte aligned
+    assert call(0x10000, 1 << 16, 4, 0, 1, 0, 0, -4) == B.NT_ERR_BAD_ARG       # negative launch size
+    assert call(0x10000, 1 << 16, 4, 0, 1, 0, 0, 6) == B.NT_ERR_BAD_ARG        # launch size not a multiple of 4
     assert call(None, 1 << 16, 4, 0, 1, 0, 0) == B.NT_ERR_BAD_ARG
     assert call(0x10000, 1 << 16, 0, 0, 1, 0, 0) == B.NT_OK                    # nothing to do
 
