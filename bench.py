@@ -387,8 +387,9 @@ def main():
         "result": {k: t["result"][k] for k in ("T", "pass", "next_b", "status")},
         "roofline": {
             "bound": "hbm",
-            "kernel": "k_step (the fused streaming kernel, launched over runs of 2^27 coordinates; the HIP events bracket "
-                      "the whole step: every k_step launch, the gaps between them and the reduction kernels, a few us)",
+            "kernel": "k_step (the fused streaming kernel; a long vector takes several launches of it, each over a run of "
+                      "consecutive tiles; the HIP events bracket the whole step: every k_step launch, the gaps between "
+                      "them and the reduction kernels)",
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
