@@ -129,7 +129,6 @@ def cpu_baseline(wl, sample_coords: int):
 
 MODE_TEXT = {
     "full": "stats+decision+fused AdamW in one pass",
-    "full_two_pass": "statistics + decision, then AdamW from the stored mean (the library's two-pass route for many rows)",
     "stats": "statistics and decision only",
     "adamw": "mean + AdamW only (test skipped)",
     "clipped": "two-phase gradient-clipped step (stats+gbar, then AdamW)",
@@ -225,16 +224,14 @@ def time_steps(wl, mode: str, steps: int, warmup: int, *, one_pass=False, layers
     wall = time.perf_counter() - t0
     ev_ms = sorted(s.elapsed_time(e) for s, e in zip(starts, stops))
     res = B.read_result(result).as_dict()
-    # from 192 gradient bytes per coordinate on the library runs the full step as two passes
-    two_pass = mode == "full" and not one_pass and wl.J * wl.grad_bytes >= 192
     alg_bytes = wl.d * bytes_per_param
     ev_avg = sum(ev_ms) / len(ev_ms)
     return {
-        "flags": flags, "bytes_per_param": bytes_per_param, "alg_bytes": alg_bytes, "two_pass": two_pass,
+        "flags": flags, "bytes_per_param": bytes_per_param, "alg_bytes": alg_bytes,
         "wall_ms_per_step": wall * 1e3 / steps, "ev_avg": ev_avg, "ev_median": ev_ms[len(ev_ms) // 2],
         "ev_min": ev_ms[0], "ev_max": ev_ms[-1], "result": res, "workspace_bytes": ws_bytes,
         "layers": 0 if layer_off is None else layer_off.numel() - 1,
-        "route": MODE_TEXT["full_two_pass" if two_pass else mode],
+        "route": MODE_TEXT[mode],
     }
 
 
@@ -330,7 +327,7 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and time replays (removes launch gaps; matters for small d)")
     ap.add_argument("--one-pass", action="store_true",
-                    help="keep the fused single pass where the library would take its two-pass route (many rows)")
+                    help="set NT_ONE_PASS (accepted and without effect: the step is one pass at every row count)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true",
                     help="skip the other workloads of the benchmark set (they run after the headline by default)")

@@ -43,8 +43,8 @@ enum {
   NT_PARTIAL = 4u,    /* FSDP shard: stop at the additive sums A, B, C; decide in normtest_combine */
   NT_WRITE_GBAR = 8u, /* also store gbar (fp32[d]) to gbar_out                                   */
   NT_COORD_TEST = 16u, /* also the coordinate-wise form of the test: count of failing coordinates, largest ratio */
-  NT_ONE_PASS = 32u   /* keep the full step in one fused pass even for many rows (see normtest_workspace_bytes): */
-                      /* same bits, 8 bytes per coordinate less traffic, measured slower from 96 bf16 / 48 fp32 rows */
+  NT_ONE_PASS = 32u   /* accepted and without effect: the step is always one fused pass (the flag once kept       */
+                      /* many-row steps from being split into statistics + gbar and AdamW from gbar)               */
 };
 
 /* nt_result.status bits */
@@ -129,16 +129,13 @@ typedef struct {
  * same J, dtype and flags. */
 int64_t normtest_tile_coords(int64_t J);
 
-/* Bytes of device workspace normtest_step needs for J rows of d coordinates (0 if J or d is invalid): a few
- * doubles per tile (and a 256-byte record), and from 48 rows on also 4 d bytes, because with 192 or more gradient bytes per coordinate
- * (96 bf16 or 48 fp32 rows) the full step runs as two passes (statistics that store gbar, then AdamW from
- * gbar: faster there, same bits) and keeps gbar in the workspace unless NT_WRITE_GBAR names a buffer for it. */
+/* Bytes of device workspace normtest_step needs for J rows of d coordinates (0 if J or d is invalid): a 256-byte
+ * record of the step and a few doubles per tile of coordinates (about 0.01 byte per coordinate). */
 size_t normtest_workspace_bytes(int64_t J, int64_t d);
 
 /* The same for a known gradient dtype and nt_hyper.flags: what normtest_step (and the other step entry points)
- * check for exactly that call.  Never more than normtest_workspace_bytes(J, d), which covers every dtype and
- * flag: the 4 d bytes for gbar are needed only by a full step (NT_DO_STATS | NT_DO_ADAMW) of at least 192
- * gradient bytes per coordinate without NT_ONE_PASS and without NT_WRITE_GBAR.  0 if an argument is invalid. */
+ * check for exactly that call.  Equal to normtest_workspace_bytes(J, d) for every valid dtype and flag word (the
+ * two differed while many-row steps kept gbar in the workspace); 0 if an argument is invalid. */
 size_t normtest_workspace_bytes_for(nt_dtype gdtype, int64_t J, int64_t d, uint32_t flags);
 
 /*
@@ -183,9 +180,7 @@ int normtest_step_rows(const void* const* grad_rows_dev, nt_dtype gdtype, int64_
  * normtest_step, without `workspace`: the tile partial sums and the record of the step go to a 16 MiB array that
  * the library holds in each GPU's memory (a static __device__ array; no hipMalloc, hipFree or other allocating
  * call is made here, on any path).  Limits: d <= normtest_static_max_coords(J) (about 1.7e9 coordinates up to
- * 16 rows, 0.86e9 beyond), else NT_ERR_TOO_LARGE and nothing is enqueued.  With many rows (96 bf16 / 48 fp32 or
- * more) normtest_step's two-pass route needs 4 d bytes for gbar: here it is taken only when NT_WRITE_GBAR names a
- * gbar_out buffer, otherwise the single fused pass runs (same bits).  The array keeps the last call's contents;
+ * 16 rows, 3.4e9 beyond), else NT_ERR_TOO_LARGE and nothing is enqueued.  The array keeps the last call's contents;
  * nothing in it has to be cleared between calls.  All calls on one GPU share it: two calls that overlap in time
  * on the same GPU (different streams, or graphs replayed concurrently) race and give wrong statistics; calls on
  * one stream, or ordered by events, are fine.  normtest_layer_stats cannot follow this call (it needs the

@@ -5,7 +5,7 @@
 // failing the coordinate-wise form of the test, and their largest ratio); k_reduce_groups / k_finalize then add
 // the tile partials in double-double arithmetic and take Alg. 1's decision on the device.  The partials stay in the caller's workspace
 // behind a small record of the step, from which k_layer_stats can regroup them into a per-layer table.
-// k_adamw_gbar is the second phase of the gradient-clipped variant and of the many-row two-pass route.  The
+// k_adamw_gbar is the second phase of the gradient-clipped variant.  The
 // path is bound by HBM bandwidth (about two lane-operations per byte), so there is no MFMA here: the work is
 // fully coalesced 8- and 16-byte accesses, fp32 per-coordinate arithmetic, fp64 accumulation and wave64
 // shuffle reductions.  Launch shapes (block size, sweeps per tile) differ per class of call and were
@@ -38,8 +38,10 @@
 #define NT_ITERS_STATS_GBAR 2    // stream moves the optimum to shorter tiles
 #define NT_BLOCK_ADAMW 1024      // J <= 16, AdamW only (test skipped)
 #define NT_ITERS_ADAMW 1
-#define NT_BLOCK_LARGE 256       // J > 16 (rows are walked inside each sweep), all modes
-#define NT_ITERS_LARGE 2
+#define NT_BLOCK_LARGE 128       // J > 16 (rows are walked inside each sweep), all modes: a block walks the rows of
+#define NT_ITERS_LARGE 16        // all its sweeps first and updates the state of all of them afterwards
+#define NT_LDS_PAD_LARGE 0       // extra LDS bytes per block of that class (caps the blocks per CU)
+#define NT_GENS_LARGE 1          // ... and a launch holds this many generations of blocks (CUs x blocks per CU)
 #define NT_BLOCKS_PER_CU 4096    // grid = min(tiles, CUs * this); blocks stride over tiles beyond that
 // A long vector is walked by several launches of the step kernel, each over a run of consecutive tiles.  Blocks
 // that start together move through their load and store phases together, so the memory system sees chip-wide
@@ -50,8 +52,8 @@
 #define NT_CHUNK_ADAMW (1ll << 25)       // J <= 16, AdamW only (+5 %)
 #define NT_CHUNK_STATS_GBAR (1ll << 27)  // J <= 16, statistics + stored gbar (+2 % on the clipped step)
 #define NT_CHUNK_STATS 0                 // statistics only: nothing is written, nothing to gain
-#define NT_CHUNK_ADAMW_GBAR (1ll << 25)  // AdamW from a stored gbar (second phase of the clipped and two-pass steps)
-#define NT_CHUNK_LARGE (1ll << 23)       // J > 16, modes that update the state in the same pass (+7 % at 64 rows)
+#define NT_CHUNK_ADAMW_GBAR (1ll << 25)  // AdamW from a stored gbar (second phase of the clipped step)
+// J > 16, modes that write per coordinate: one generation of blocks per launch, see launch_step_shape
 
 #define NT_VEC 4              // coordinates per lane and sweep: 16-byte fp32 accesses, 8-byte bf16 row loads
 #define NT_TILE_MAX 16384     // every tile size divides this: the alignment that keeps shard results bit-identical
@@ -71,8 +73,6 @@
 #define NT_WS_CONTROL 24       // ... of which this one starts the words the step's kernels hand to each other
 #define NT_WS_MAGIC 0x4e54574f524b5350ll
 #define NT_LAYER_THREADS 1024  // per-layer kernel: one block per layer
-#define NT_TWO_PHASE_ROW_BYTES 192  // from this many gradient bytes per coordinate on (96 bf16 or 48 fp32 rows) the
-                                    // full step runs as statistics + gbar, then AdamW from gbar
 
 // Scratch of normtest_step_static: the per-tile partial sums and the record of the step, for callers that
 // cannot hand over (or allocate) a workspace.  One copy per GPU, held until the process ends.
@@ -520,10 +520,18 @@ __device__ inline void chunk_accumulate(const typename GT::raw_t* raw, int nb, c
     }
 }
 
+// The state update (and the gbar store) of a tile is deferred: the means of all its sweeps wait in LDS until every
+// row has been read, then w, m, v of all sweeps are read and written in one go.  With many rows the writes are a few
+// per cent of the traffic, and the memory system charges writes sprinkled among reads several times their volume;
+// gathered at the end of a block's life, and with all blocks of a launch living at the same time (one generation
+// per launch), they reach it as a dense burst.
 template <class GT, int MODE, int BLOCK, int ITERS, bool TABLE, bool GBAR>
-__device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double (*red)[BLOCK / 64][NT_NV], int buf) {
+__device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double (*red)[BLOCK / 64][NT_NV], int buf,
+                                       f32x4* gbs) {
   constexpr int VEC = GT::VEC;
+  static_assert(VEC == 4, "one 16-byte LDS slot per lane and sweep");
   constexpr int TILE = BLOCK * VEC * ITERS;
+  constexpr bool WRITES = (MODE != MODE_STATS) || GBAR;
   const int J = p.J;
   LaneAcc acc;
 #pragma unroll 1
@@ -577,19 +585,34 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
       acc.B += (double)lane_tree<VEC>(b);
       acc.C += (double)lane_tree<VEC>(M2);
     }
-    if constexpr (MODE != MODE_STATS) {
-      u32x4 sw[VEC / 4], sm[VEC / 4], sv[VEC / 4];
-#pragma unroll
-      for (int q4 = 0; q4 < VEC / 4; ++q4) {
-        sw[q4] = ld16(p.w + i0 + 4 * q4);
-        sm[q4] = ld16(p.m + i0 + 4 * q4);
-        sv[q4] = ld16(p.v + i0 + 4 * q4);
-      }
-      adamw_store<VEC>(p, i0, gb, sw, sm, sv);
-    }
-    if (GBAR && p.gbar) gbar_store<VEC>(p, i0, gb);
+    if constexpr (WRITES) gbs[it * BLOCK + threadIdx.x] = f32x4{gb[0], gb[1], gb[2], gb[3]};
   }
-  if constexpr (MODE != MODE_ADAMW) tile_reduce<BLOCK>(acc, red, buf, p.partials, tile);
+  // the barrier inside keeps the waves of the block together on their way into the write phase
+  if constexpr (MODE != MODE_ADAMW)
+    tile_reduce<BLOCK>(acc, red, buf, p.partials, tile);
+  else
+    __syncthreads();
+  if constexpr (WRITES) {
+    if (MODE != MODE_STATS || p.gbar) {
+#pragma unroll 2
+      for (int it = 0; it < ITERS; ++it) {
+        const int64_t i0 = tile * TILE + ((int64_t)it * BLOCK + threadIdx.x) * VEC;
+        const f32x4 g4 = gbs[it * BLOCK + threadIdx.x];   // this lane's own values: no barrier needed for them
+        const float gb[VEC] = {g4[0], g4[1], g4[2], g4[3]};
+        if constexpr (MODE != MODE_STATS) {
+          u32x4 sw[VEC / 4], sm[VEC / 4], sv[VEC / 4];
+#pragma unroll
+          for (int q4 = 0; q4 < VEC / 4; ++q4) {
+            sw[q4] = ld16(p.w + i0 + 4 * q4);
+            sm[q4] = ld16(p.m + i0 + 4 * q4);
+            sv[q4] = ld16(p.v + i0 + 4 * q4);
+          }
+          adamw_store<VEC>(p, i0, gb, sw, sm, sv);
+        }
+        if (GBAR && p.gbar) gbar_store<VEC>(p, i0, gb);
+      }
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -606,6 +629,9 @@ __global__ __launch_bounds__(BLOCK) void k_step(StepParams p, int64_t nfull, int
   constexpr int TILE = BLOCK * GT::VEC * ITERS;
   static_assert(NT_TILE_MAX % TILE == 0, "tile sizes must divide NT_TILE_MAX");
   __shared__ double red[2][BLOCK / 64][NT_NV];
+  // J > 16: the means of a tile's sweeps wait here for the deferred state update (see fast_tile_multi)
+  constexpr bool DEFER = (J_T == 0) && ((MODE != MODE_STATS) || GBAR);
+  __shared__ f32x4 gbs[DEFER ? ITERS * BLOCK + NT_LDS_PAD_LARGE / 16 : 1];
   int buf = 0;
   if constexpr (TABLE) {
     // the host cannot see the row pointers: k_rows_aligned has looked at them and left its verdict here
@@ -619,7 +645,7 @@ __global__ __launch_bounds__(BLOCK) void k_step(StepParams p, int64_t nfull, int
       if constexpr (J_T > 0)
         fast_tile<GT, J_T, MODE, BLOCK, ITERS, TABLE, GBAR>(p, tile, red, buf);
       else
-        fast_tile_multi<GT, MODE, BLOCK, ITERS, TABLE, GBAR>(p, tile, red, buf);
+        fast_tile_multi<GT, MODE, BLOCK, ITERS, TABLE, GBAR>(p, tile, red, buf, gbs);
     } else {
       guarded_tile<GT, J_T, MODE, BLOCK, TABLE, GBAR>(p, tile, TILE, red, buf);
     }
@@ -1128,7 +1154,7 @@ inline TileCfg tile_cfg(int64_t J, int mode, bool gbar) {
 inline int64_t launch_tiles(int64_t J, int mode, bool gbar, int64_t ntiles) {
   int64_t coords;
   if (J > NT_JCHUNK)
-    coords = (mode == MODE_STATS) ? NT_CHUNK_STATS : NT_CHUNK_LARGE;
+    return ntiles;   // generations of blocks, not coordinates: launch_step_shape knows the kernel's occupancy
   else if (mode == MODE_STATS)
     coords = gbar ? NT_CHUNK_STATS_GBAR : NT_CHUNK_STATS;
   else
@@ -1171,7 +1197,19 @@ bool hyper_ok(const nt_hyper* h, int64_t J) {
 template <class GT, int MODE, bool TABLE, int BS, int IS, bool GBAR>
 hipError_t launch_step_shape(const StepParams& p, int64_t nfull, int64_t ntiles, WsControl* ctl, int max_grid,
                              hipStream_t st) {
-  const int64_t per_launch = launch_tiles(p.J, MODE, MODE == MODE_STATS && p.gbar != nullptr, ntiles);
+  int64_t per_launch = launch_tiles(p.J, MODE, MODE == MODE_STATS && p.gbar != nullptr, ntiles);
+  if (p.J > NT_JCHUNK && (MODE != MODE_STATS || p.gbar != nullptr)) {
+    // blocks that write per coordinate do so at the end of their lives: a launch holds whole generations of blocks
+    // (as many as the chip runs at a time), so that all of them read together and write together
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_step<GT, 0, MODE, NT_BLOCK_LARGE, NT_ITERS_LARGE, TABLE, true>,
+                                                     NT_BLOCK_LARGE, 0) != hipSuccess || per_cu < 1) {
+      (void)hipGetLastError();
+      per_cu = 4;
+    }
+    per_launch = (int64_t)cu_count() * per_cu * NT_GENS_LARGE;
+    if (per_launch > ntiles) per_launch = ntiles;
+  }
   for (int64_t slot0 = 0; slot0 < ntiles; slot0 += per_launch) {
     const int64_t slot1 = (ntiles - slot0 < per_launch) ? ntiles : slot0 + per_launch;
     const unsigned grid = (unsigned)((slot1 - slot0 < max_grid) ? slot1 - slot0 : max_grid);
@@ -1245,30 +1283,16 @@ static size_t partials_bytes(int64_t J, int64_t d) {
   return (size_t)(NT_WS_HEADER + n * NT_NV + ngroups * 2 * NT_NV) * sizeof(double);
 }
 
-// With many rows the few bytes written per coordinate disturb the read stream far more than their share
-// (sparse writes cost the memory system about ten times their volume), and the step is faster as two
-// passes: statistics that store only gbar, then AdamW from gbar.  The fp32 gbar buffer for that lives
-// behind the partials (plus slack to align it to 16 bytes) unless the caller asked for gbar anyway.
-static inline bool two_phase(int64_t J, int esize) { return J * esize >= NT_TWO_PHASE_ROW_BYTES; }
-// does a call with these flags take the two-pass route and keep gbar in the workspace?
-static inline bool gbar_in_workspace(int64_t J, int esize, uint32_t flags) {
-  const uint32_t both = NT_DO_STATS | NT_DO_ADAMW;
-  return (flags & both) == both && !(flags & (NT_ONE_PASS | NT_WRITE_GBAR)) && two_phase(J, esize);
-}
-static inline size_t gbar_bytes(int64_t d) { return (((size_t)d * sizeof(float) + 15u) & ~(size_t)15u) + 16; }
-
 size_t normtest_workspace_bytes(int64_t J, int64_t d) {
   if (J < 2 || d < 0) return 0;
-  size_t need = partials_bytes(J, d);
-  if (two_phase(J, 4)) need += gbar_bytes(d);  // dtype and flags unknown here: the larger of the two
-  return need;
+  return partials_bytes(J, d);
 }
 
+// dtype and flags do not change the size (they did while many-row steps kept gbar in the workspace)
 size_t normtest_workspace_bytes_for(nt_dtype gdtype, int64_t J, int64_t d, uint32_t flags) {
+  (void)flags;
   if (J < 2 || d < 0 || (gdtype != NT_F32 && gdtype != NT_BF16)) return 0;
-  size_t need = partials_bytes(J, d);
-  if (gbar_in_workspace(J, gdtype == NT_F32 ? 4 : 2, flags)) need += gbar_bytes(d);
-  return need;
+  return partials_bytes(J, d);
 }
 
 // AdamW constants in fp64 on the host, rounded once to fp32.
@@ -1425,24 +1449,13 @@ static int enqueue_adamw_gbar(const float* gbar, int64_t d, float* w, float* m, 
   return NT_OK;
 }
 
-// The step as the caller's flags describe it: one fused pass, or for many rows (two_phase) the statistics
-// pass that stores gbar followed by AdamW from gbar, which leaves the same bits in w, m, v and the result.
+// The step as the caller's flags describe it, always one pass (NT_ONE_PASS, which once kept many-row steps from
+// being split into two passes, is accepted and changes nothing).
 static int enqueue_step_routed(const void* grads, bool table, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld,
                                float* w, float* m, float* v, float* gbar_out, const nt_hyper* hyper, void* workspace,
                                nt_result* result_dev, hipStream_t st) {
-  const uint32_t flags = hyper->flags;
-  const uint32_t both = NT_DO_STATS | NT_DO_ADAMW;
-  if ((flags & both) != both || (flags & NT_ONE_PASS) || !two_phase(J, gdtype == NT_F32 ? 4 : 2))
-    return enqueue_step(grads, table, gdtype, J, d, ld, w, m, v, gbar_out, flags, hyper, 0.0, workspace, result_dev, st);
-  float* gbar = gbar_out;
-  if (!(flags & NT_WRITE_GBAR)) {
-    const uintptr_t behind = (uintptr_t)workspace + partials_bytes(J, d);
-    gbar = (float*)((behind + 15u) & ~(uintptr_t)15u);
-  }
-  const int rc = enqueue_step(grads, table, gdtype, J, d, ld, nullptr, nullptr, nullptr, gbar,
-                              (flags & ~(uint32_t)NT_DO_ADAMW) | NT_WRITE_GBAR, hyper, 0.0, workspace, result_dev, st);
-  if (rc != NT_OK) return rc;
-  return enqueue_adamw_gbar(gbar, d, w, m, v, hyper, 1.0, nullptr, st);
+  return enqueue_step(grads, table, gdtype, J, d, ld, w, m, v, gbar_out, hyper->flags, hyper, 0.0, workspace,
+                      result_dev, st);
 }
 
 int normtest_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld, float* w, float* m,
@@ -1503,9 +1516,7 @@ int normtest_step_static(const void* grads, nt_dtype gdtype, int64_t J, int64_t 
                          nt_result* result_dev, void* hip_stream) {
   if (!hyper) return NT_ERR_BAD_ARG;
   if (J >= 2 && J <= (1 << 20) && d > normtest_static_max_coords(J)) return NT_ERR_TOO_LARGE;
-  // many rows: the two-pass route needs room for gbar, which only the caller can give (NT_WRITE_GBAR)
   nt_hyper hy = *hyper;
-  if (!(hy.flags & NT_WRITE_GBAR)) hy.flags |= NT_ONE_PASS;
   // validate with a stand-in for the workspace (any non-null, aligned address: nothing is enqueued here)
   const int rc = check_step_args(grads, gdtype, J, d, ld, w, m, v, gbar_out, hy.flags, &hy, shard, (const void*)256,
                                  (size_t)-1, result_dev);

@@ -76,7 +76,7 @@ def test_plain_c_client_sees_the_layout_the_binding_assumes(tmp_path):
     assert float(lines["clip"][0]) == pytest.approx(1.0 / (2.0 + 1e-6), rel=1e-15)
     assert int(lines["workspace"][0]) == B.normtest_workspace_bytes(8, 1000000) and int(lines["workspace"][2]) == 16384
     bf16_64, f32_64, any_64 = (int(x) for x in lines["workspace_for"])
-    assert bf16_64 < f32_64 == any_64 and f32_64 - bf16_64 == 4 * 1000000 + 16
+    assert bf16_64 == f32_64 == any_64 == B.normtest_workspace_bytes(64, 1000000)
     assert int(lines["static_max"][0]) == B.normtest_static_max_coords(8)
 
 
@@ -87,8 +87,6 @@ def test_workspace_and_tiles():
         prev = 0
         for d in (0, 1, tc, tc + 1, 5000 * tc, 1_500_000_000):
             need = B.normtest_workspace_bytes(J, d)
-            if J >= 48:          # many rows: room for an fp32 gbar behind the partials (two-pass route)
-                need -= (4 * d + 15) // 16 * 16 + 16
             # a 256-byte record, five doubles per tile (tiles are at most tc and at least 1024 coordinates), and
             # a small second level
             lo = 256 + 40 * max(1, -(-d // tc))
@@ -101,33 +99,25 @@ def test_workspace_and_tiles():
 
 
 def test_workspace_size_for_a_known_call():
-    """The size for a known dtype and flags never exceeds the general one; the 4 d bytes for gbar are asked for
-    only where the two-pass route runs and has to keep gbar itself."""
+    """The size for a known dtype and flags is the general one for every valid dtype and flag word (no call keeps
+    a gbar buffer in the workspace: the step is one pass at every row count), and it is what the step checks."""
     full = B.NT_DO_STATS | B.NT_DO_ADAMW
     d = 3_000_001
-    gbar = (4 * d + 15) // 16 * 16 + 16
     for J in (2, 16, 47, 48, 95, 96, 512):
         upper = B.normtest_workspace_bytes(J, d)
-        base = B.normtest_workspace_bytes_for(B.NT_BF16, J, d, B.NT_DO_STATS)
-        for gd, esize in ((B.NT_BF16, 2), (B.NT_F32, 4)):
-            two_pass = J * esize >= 192
-            assert B.normtest_workspace_bytes_for(gd, J, d, full) == base + (gbar if two_pass else 0)
-            for flags in (full | B.NT_ONE_PASS, full | B.NT_WRITE_GBAR, B.NT_DO_STATS, B.NT_DO_ADAMW,
+        assert upper < 256 + d // 16                  # a record and a few doubles per tile, nothing d-sized
+        for gd in (B.NT_BF16, B.NT_F32):
+            for flags in (full, full | B.NT_ONE_PASS, full | B.NT_WRITE_GBAR, B.NT_DO_STATS, B.NT_DO_ADAMW,
                           B.NT_DO_STATS | B.NT_PARTIAL | B.NT_WRITE_GBAR):
-                assert B.normtest_workspace_bytes_for(gd, J, d, flags) == base
-            assert B.normtest_workspace_bytes_for(gd, J, d, full) <= upper
-        assert upper == base + (gbar if J >= 48 else 0)
+                assert B.normtest_workspace_bytes_for(gd, J, d, flags) == upper
     assert B.normtest_workspace_bytes_for(7, 8, 100, full) == 0
     assert B.normtest_workspace_bytes_for(B.NT_BF16, 1, 100, full) == 0
-    # the step checks exactly this size: a bf16 call with 64 rows is accepted with the smaller workspace ...
     hy = B.make_hyper(step=1, b_k=32, flags=full)
-    small = B.normtest_workspace_bytes_for(B.NT_BF16, 64, 1 << 20, full)
-    assert small < B.normtest_workspace_bytes(64, 1 << 20)
-    assert _call(J=64, d=1 << 20, gdtype=B.NT_BF16, hyper=hy, ws_bytes=small - 8) == B.NT_ERR_WORKSPACE_TOO_SMALL
-    # ... and an fp32 call with as many rows is told that it is too small
-    assert _call(J=64, d=1 << 20, gdtype=B.NT_F32, hyper=hy, ws_bytes=small) == B.NT_ERR_WORKSPACE_TOO_SMALL
+    need = B.normtest_workspace_bytes_for(B.NT_BF16, 64, 1 << 20, full)
+    for gd in (B.NT_BF16, B.NT_F32):
+        assert _call(J=64, d=1 << 20, gdtype=gd, hyper=hy, ws_bytes=need - 8) == B.NT_ERR_WORKSPACE_TOO_SMALL
     one = B.make_hyper(step=1, b_k=32, flags=full | B.NT_ONE_PASS)
-    assert _call(J=64, d=1 << 20, gdtype=B.NT_F32, hyper=one, ws_bytes=small - 8) == B.NT_ERR_WORKSPACE_TOO_SMALL
+    assert _call(J=64, d=1 << 20, gdtype=B.NT_F32, hyper=one, ws_bytes=need - 8) == B.NT_ERR_WORKSPACE_TOO_SMALL
 
 
 def _call(J=4, d=64, ld=None, gdtype=B.NT_F32, grads=0x1000, w=0x2000, m=0x3000, v=0x4000, gbar=None,

@@ -55,7 +55,7 @@ def test_static_scratch_matches_workspace_entry_point_on_calls_in_a_row():
     run_both(8, 20_000_003, torch.bfloat16, 3, full)
     print("call 4 (smaller again, statistics only, many rows): J=40 bf16 d=%d" % (3 * tc + 12), flush=True)
     run_both(40, 3 * tc + 12, torch.bfloat16, 4, B.NT_DO_STATS)
-    print("call 5: J=128 bf16 (the workspace entry point takes two passes, this one a single pass: same bits)", flush=True)
+    print("call 5: J=128 bf16 (many rows: the state update deferred to the end of each block's walk)", flush=True)
     run_both(128, 2 * tc + 8, torch.bfloat16, 5, full)
 
 
