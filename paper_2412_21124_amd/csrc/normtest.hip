@@ -1194,6 +1194,25 @@ bool hyper_ok(const nt_hyper* h, int64_t J) {
   return true;
 }
 
+// How many blocks of the many-row kernel a CU holds at a time (the runtime's occupancy query, asked once per
+// device and kernel; 4 if it cannot be had).
+template <class GT, int MODE, bool TABLE>
+int large_blocks_per_cu() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 4;
+  int n = __atomic_load_n(&cached[dev], __ATOMIC_RELAXED);
+  if (n <= 0) {
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_step<GT, 0, MODE, NT_BLOCK_LARGE, NT_ITERS_LARGE, TABLE, true>,
+                                                     NT_BLOCK_LARGE, 0) != hipSuccess || n < 1) {
+      (void)hipGetLastError();
+      n = 4;
+    }
+    __atomic_store_n(&cached[dev], n, __ATOMIC_RELAXED);
+  }
+  return n;
+}
+
 template <class GT, int MODE, bool TABLE, int BS, int IS, bool GBAR>
 hipError_t launch_step_shape(const StepParams& p, int64_t nfull, int64_t ntiles, WsControl* ctl, int max_grid,
                              hipStream_t st) {
@@ -1201,12 +1220,7 @@ hipError_t launch_step_shape(const StepParams& p, int64_t nfull, int64_t ntiles,
   if (p.J > NT_JCHUNK && (MODE != MODE_STATS || p.gbar != nullptr)) {
     // blocks that write per coordinate do so at the end of their lives: a launch holds whole generations of blocks
     // (as many as the chip runs at a time), so that all of them read together and write together
-    int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_step<GT, 0, MODE, NT_BLOCK_LARGE, NT_ITERS_LARGE, TABLE, true>,
-                                                     NT_BLOCK_LARGE, 0) != hipSuccess || per_cu < 1) {
-      (void)hipGetLastError();
-      per_cu = 4;
-    }
+    const int per_cu = large_blocks_per_cu<GT, MODE, TABLE>();
     per_launch = (int64_t)cu_count() * per_cu * NT_GENS_LARGE;
     if (per_launch > ntiles) per_launch = ntiles;
   }

@@ -872,10 +872,13 @@ def test_result_in_pinned_host_memory_and_two_streams():
             assert torch.equal(a, b)
 
 
-def test_step_can_be_captured_in_a_hip_graph():
+@pytest.mark.parametrize("J,d", [(8, 5 * 16384 + 99), (24, 2 * 8388608 + 3 * 8192 + 99)])
+def test_step_can_be_captured_in_a_hip_graph(J, d):
     """The step allocates nothing and records only kernel launches, so it can be captured; every replay,
-    with eager work and synchronisation in between, must reproduce the eager result bit for bit."""
-    wl = synth.make("t", 8, 5 * 16384 + 99, gdtype=torch.bfloat16, seed=32, device=DEV)
+    with eager work and synchronisation in between, must reproduce the eager result bit for bit.  The second case
+    has more than 16 rows and is long enough for several launches of the step kernel (one generation of blocks
+    each) inside the captured graph."""
+    wl = synth.make("t", J, d, gdtype=torch.bfloat16, seed=32, device=DEV)
     state0 = [t.clone() for t in (wl.w, wl.m, wl.v)]
     hy = hyper_of(wl.hyper)
     ws = torch.empty(B.normtest_workspace_bytes(wl.J, wl.d), dtype=torch.uint8, device=DEV)
