@@ -149,7 +149,10 @@ size_t normtest_workspace_bytes_for(nt_dtype gdtype, int64_t J, int64_t d, uint3
  * hip_stream: a hipStream_t (NULL = the default stream).
  *
  * Everything is enqueued on the stream; the result and the updated state are valid once the caller
- * has synchronised it.  Any pointer alignment is accepted: rows, w, m, v (and gbar_out) that are not
+ * has synchronised it.  A call enqueues kernel launches only (no memsets, copies or allocations): a long vector
+ * is walked by several launches of the same kernel over consecutive runs of tiles (about one per 1.3e8
+ * coordinates up to 16 rows, one per 8e6 beyond; the memory system serves blocks that start together faster),
+ * followed by one or two small reduction kernels; results do not depend on how many launches there were.  Any pointer alignment is accepted: rows, w, m, v (and gbar_out) that are not
  * all 16-byte aligned take a slower path with bit-identical results.  d == 0 succeeds (sums are 0).
  * AdamW is fused into the same pass: it has been applied even if status reports NONFINITE.
  * Returns NT_OK or a negative code; on any error nothing was enqueued and no buffer was touched,

@@ -8,8 +8,12 @@
 // k_adamw_gbar is the second phase of the gradient-clipped variant.  The
 // path is bound by HBM bandwidth (about two lane-operations per byte), so there is no MFMA here: the work is
 // fully coalesced 8- and 16-byte accesses, fp32 per-coordinate arithmetic, fp64 accumulation and wave64
-// shuffle reductions.  Launch shapes (block size, sweeps per tile) differ per class of call and were
-// chosen by measurement; see tile_cfg().
+// shuffle reductions.  Launch shapes (block size, sweeps per tile, coordinates per launch) differ per class of
+// call and were chosen by measurement; see tile_cfg() and the NT_CHUNK_* constants.  Two things about the memory
+// system shape the host side: blocks that start together stay in step for a while and are served faster than an
+// even mix of loads and stores, so a long vector is walked by several launches; and writes sprinkled among many
+// reads cost several times their volume, so with more than 16 rows a block updates the state of its whole tile
+// only after it has read all the rows (fast_tile_multi).
 //
 // Numerics.  The centred sum C = sum_j (g_j - gbar)^2 is formed directly from the J values of a
 // coordinate held in registers, never as A - B/J (which cancels badly when the workers agree).  A
