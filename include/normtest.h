@@ -183,7 +183,7 @@ int normtest_step_rows(const void* const* grad_rows_dev, nt_dtype gdtype, int64_
  * normtest_step, without `workspace`: the tile partial sums and the record of the step go to a 16 MiB array that
  * the library holds in each GPU's memory (a static __device__ array; no hipMalloc, hipFree or other allocating
  * call is made here, on any path).  Limits: d <= normtest_static_max_coords(J) (about 1.7e9 coordinates up to
- * 16 rows, 3.4e9 beyond), else NT_ERR_TOO_LARGE and nothing is enqueued.  The array keeps the last call's contents;
+ * 16 rows, 0.86e9 beyond), else NT_ERR_TOO_LARGE and nothing is enqueued.  The array keeps the last call's contents;
  * nothing in it has to be cleared between calls.  All calls on one GPU share it: two calls that overlap in time
  * on the same GPU (different streams, or graphs replayed concurrently) race and give wrong statistics; calls on
  * one stream, or ordered by events, are fine.  normtest_layer_stats cannot follow this call (it needs the

@@ -44,7 +44,9 @@
 #define NT_ITERS_ADAMW 1
 #define NT_BLOCK_LARGE 128       // J > 16 (rows are walked inside each sweep), all modes: a block walks the rows of
 #define NT_ITERS_LARGE 16        // all its sweeps first and updates the state of all of them afterwards
-#define NT_LDS_PAD_LARGE 0       // extra LDS bytes per block of that class (caps the blocks per CU)
+#define NT_LDS_PAD_LARGE 1024    // LDS bytes on top of the 32 KB of means: four blocks per CU in every mode (five are slower)
+#define NT_BLOCK_LARGE_STATS 256 // J > 16, statistics only (nothing written per coordinate): short tiles, so that a
+#define NT_ITERS_LARGE_STATS 2   // vector of a few million coordinates still gives every CU several blocks
 #define NT_GENS_LARGE 1          // ... and a launch holds this many generations of blocks (CUs x blocks per CU)
 #define NT_BLOCKS_PER_CU 4096    // grid = min(tiles, CUs * this); blocks stride over tiles beyond that
 // A long vector is walked by several launches of the step kernel, each over a run of consecutive tiles.  Blocks
@@ -1148,7 +1150,9 @@ struct TileCfg {
   int64_t coords() const { return (int64_t)block * NT_VEC * iters; }
 };
 inline TileCfg tile_cfg(int64_t J, int mode, bool gbar) {
-  if (J > NT_JCHUNK) return {NT_BLOCK_LARGE, NT_ITERS_LARGE};
+  if (J > NT_JCHUNK)
+    return (mode == MODE_STATS && !gbar) ? TileCfg{NT_BLOCK_LARGE_STATS, NT_ITERS_LARGE_STATS}
+                                         : TileCfg{NT_BLOCK_LARGE, NT_ITERS_LARGE};
   if (mode == MODE_STATS && gbar) return {NT_BLOCK_STATS_GBAR, NT_ITERS_STATS_GBAR};
   if (mode == MODE_STATS) return {NT_BLOCK_STATS, NT_ITERS_STATS};
   if (mode == MODE_ADAMW) return {NT_BLOCK_ADAMW, NT_ITERS_ADAMW};
@@ -1240,8 +1244,12 @@ hipError_t launch_step_shape(const StepParams& p, int64_t nfull, int64_t ntiles,
       NT_CASE(2) NT_CASE(3) NT_CASE(4) NT_CASE(5) NT_CASE(6) NT_CASE(7) NT_CASE(8) NT_CASE(9)
       NT_CASE(10) NT_CASE(11) NT_CASE(12) NT_CASE(13) NT_CASE(14) NT_CASE(15) NT_CASE(16)
       default:
-        hipLaunchKernelGGL((k_step<GT, 0, MODE, NT_BLOCK_LARGE, NT_ITERS_LARGE, TABLE, true>), dim3(grid),
-                           dim3(NT_BLOCK_LARGE), 0, st, p, nfull, ntiles, slot0, slot1, ctl);
+        if (MODE == MODE_STATS && p.gbar == nullptr)
+          hipLaunchKernelGGL((k_step<GT, 0, MODE, NT_BLOCK_LARGE_STATS, NT_ITERS_LARGE_STATS, TABLE, false>), dim3(grid),
+                             dim3(NT_BLOCK_LARGE_STATS), 0, st, p, nfull, ntiles, slot0, slot1, ctl);
+        else
+          hipLaunchKernelGGL((k_step<GT, 0, MODE, NT_BLOCK_LARGE, NT_ITERS_LARGE, TABLE, true>), dim3(grid),
+                             dim3(NT_BLOCK_LARGE), 0, st, p, nfull, ntiles, slot0, slot1, ctl);
     }
 #undef NT_CASE
     const hipError_t e = hipGetLastError();
