@@ -69,7 +69,7 @@
 #define NT_MCHUNK 16          // beyond that, rows are walked this many at a time (2 .. NT_JCHUNK + 1; 16 measured best)
 #define NT_ROUND_TO_MAX (1ll << 31)  // bound on nt_hyper.round_to that keeps the rounding chain inside int64
 #define NT_FIN_THREADS 1024
-#define NT_FIN_SMALL 1024       // up to this many records the finalize kernel runs with 256 threads
+#define NT_FIN_SMALL 4096       // up to this many records the finalize kernel runs with 256 threads
 #define NT_NSUM 4              // summed values per tile partial: A, B, C and the count of failing coordinates
 #define NT_NV 5                // values per tile partial: the sums, then the largest coordinate-wise ratio
 #define NT_GROUP_THREADS 256   // first-stage reduction: threads per block
