@@ -42,12 +42,15 @@
 #define NT_ITERS_STATS_GBAR 2    // stream moves the optimum to shorter tiles
 #define NT_BLOCK_ADAMW 1024      // J <= 16, AdamW only (test skipped)
 #define NT_ITERS_ADAMW 1
-#define NT_BLOCK_LARGE 128       // J > 16 (rows are walked inside each sweep), all modes: a block walks the rows of
-#define NT_ITERS_LARGE 16        // all its sweeps first and updates the state of all of them afterwards
+#define NT_BLOCK_LARGE 128       // J > 16 (rows are walked inside each sweep), every mode that writes per coordinate:
+#define NT_ITERS_LARGE 16        // a block walks the rows of all its sweeps first and writes for all of them afterwards,
+#define NT_GENS_LARGE 1          // and a launch holds this many generations of blocks (CUs x blocks per CU)
 #define NT_LDS_PAD_LARGE 1024    // LDS bytes on top of the 32 KB of means: four blocks per CU in every mode (five are slower)
+#define NT_FEW_ROWS 20           // 17 .. this many rows: the same tile as 256 threads x 8 sweeps (fused step +9 % at 17 rows,
+#define NT_BLOCK_FEW 256         // +7 % at 20, +3 % at 24 but AdamW only -1 % there, -1.5 % at 28): the walk is short
+#define NT_ITERS_FEW 8           // there, and a block's life with it
 #define NT_BLOCK_LARGE_STATS 256 // J > 16, statistics only (nothing written per coordinate): short tiles, so that a
 #define NT_ITERS_LARGE_STATS 2   // vector of a few million coordinates still gives every CU several blocks
-#define NT_GENS_LARGE 1          // ... and a launch holds this many generations of blocks (CUs x blocks per CU)
 #define NT_BLOCKS_PER_CU 4096    // grid = min(tiles, CUs * this); blocks stride over tiles beyond that
 // A long vector is walked by several launches of the step kernel, each over a run of consecutive tiles.  Blocks
 // that start together move through their load and store phases together, so the memory system sees chip-wide
@@ -1158,11 +1161,12 @@ inline TileCfg tile_cfg(int64_t J, int mode, bool gbar) {
   if (mode == MODE_ADAMW) return {NT_BLOCK_ADAMW, NT_ITERS_ADAMW};
   return {NT_BLOCK, NT_ITERS};
 }
+static_assert(NT_BLOCK_FEW * NT_ITERS_FEW == NT_BLOCK_LARGE * NT_ITERS_LARGE, "both many-row shapes own the same tile");
 // tile slots per launch of the step kernel for the same classes (at least one, at most all)
 inline int64_t launch_tiles(int64_t J, int mode, bool gbar, int64_t ntiles) {
   int64_t coords;
   if (J > NT_JCHUNK)
-    return ntiles;   // generations of blocks, not coordinates: launch_step_shape knows the kernel's occupancy
+    return ntiles;   // one launch, or generations of blocks: launch_step_shape knows the kernel's occupancy
   else if (mode == MODE_STATS)
     coords = gbar ? NT_CHUNK_STATS_GBAR : NT_CHUNK_STATS;
   else
@@ -1204,15 +1208,15 @@ bool hyper_ok(const nt_hyper* h, int64_t J) {
 
 // How many blocks of the many-row kernel a CU holds at a time (the runtime's occupancy query, asked once per
 // device and kernel; 4 if it cannot be had).
-template <class GT, int MODE, bool TABLE>
+template <class GT, int MODE, bool TABLE, int BS, int IS>
 int large_blocks_per_cu() {
   static int cached[64] = {0};
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 4;
   int n = __atomic_load_n(&cached[dev], __ATOMIC_RELAXED);
   if (n <= 0) {
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_step<GT, 0, MODE, NT_BLOCK_LARGE, NT_ITERS_LARGE, TABLE, true>,
-                                                     NT_BLOCK_LARGE, 0) != hipSuccess || n < 1) {
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_step<GT, 0, MODE, BS, IS, TABLE, true>, BS, 0) != hipSuccess ||
+        n < 1) {
       (void)hipGetLastError();
       n = 4;
     }
@@ -1228,7 +1232,8 @@ hipError_t launch_step_shape(const StepParams& p, int64_t nfull, int64_t ntiles,
   if (p.J > NT_JCHUNK && (MODE != MODE_STATS || p.gbar != nullptr)) {
     // blocks that write per coordinate do so at the end of their lives: a launch holds whole generations of blocks
     // (as many as the chip runs at a time), so that all of them read together and write together
-    const int per_cu = large_blocks_per_cu<GT, MODE, TABLE>();
+    const int per_cu = (p.J <= NT_FEW_ROWS) ? large_blocks_per_cu<GT, MODE, TABLE, NT_BLOCK_FEW, NT_ITERS_FEW>()
+                                            : large_blocks_per_cu<GT, MODE, TABLE, NT_BLOCK_LARGE, NT_ITERS_LARGE>();
     per_launch = (int64_t)cu_count() * per_cu * NT_GENS_LARGE;
     if (per_launch > ntiles) per_launch = ntiles;
   }
@@ -1247,6 +1252,9 @@ hipError_t launch_step_shape(const StepParams& p, int64_t nfull, int64_t ntiles,
         if (MODE == MODE_STATS && p.gbar == nullptr)
           hipLaunchKernelGGL((k_step<GT, 0, MODE, NT_BLOCK_LARGE_STATS, NT_ITERS_LARGE_STATS, TABLE, false>), dim3(grid),
                              dim3(NT_BLOCK_LARGE_STATS), 0, st, p, nfull, ntiles, slot0, slot1, ctl);
+        else if (p.J <= NT_FEW_ROWS)
+          hipLaunchKernelGGL((k_step<GT, 0, MODE, NT_BLOCK_FEW, NT_ITERS_FEW, TABLE, true>), dim3(grid),
+                             dim3(NT_BLOCK_FEW), 0, st, p, nfull, ntiles, slot0, slot1, ctl);
         else
           hipLaunchKernelGGL((k_step<GT, 0, MODE, NT_BLOCK_LARGE, NT_ITERS_LARGE, TABLE, true>), dim3(grid),
                              dim3(NT_BLOCK_LARGE), 0, st, p, nfull, ntiles, slot0, slot1, ctl);

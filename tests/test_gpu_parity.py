@@ -106,7 +106,7 @@ def test_small_J_ragged(J, gdtype):
     full_parity(wl, check_gbar=(J % 4 == 0))
 
 
-@pytest.mark.parametrize("J", [17, 31, 32, 48, 100])
+@pytest.mark.parametrize("J", [17, 20, 21, 31, 32, 48, 100])
 @pytest.mark.parametrize("gdtype", [torch.float32, torch.bfloat16])
 def test_large_J_ragged(J, gdtype):
     d = 5 * 4096 + 777
