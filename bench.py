@@ -135,7 +135,7 @@ MODE_TEXT = {
 }
 
 
-def time_steps(wl, mode: str, steps: int, warmup: int, *, one_pass=False, layers=0, graph=False, calib_copy_gib=0):
+def time_steps(wl, mode: str, steps: int, warmup: int, *, layers=0, graph=False, calib_copy_gib=0):
     """Run `warmup` + `steps` steps of one workload and mode; HIP events on the launch stream bracket every step."""
     import torch
     from paper_2412_21124_amd import binding as B
@@ -146,8 +146,6 @@ def time_steps(wl, mode: str, steps: int, warmup: int, *, one_pass=False, layers
              "clipped": B.NT_DO_STATS | B.NT_DO_ADAMW}[mode]
     if wl.name == "fsdp_shard" and mode in ("full", "stats"):
         flags |= B.NT_PARTIAL
-    if one_pass:
-        flags |= B.NT_ONE_PASS
     # bytes per coordinate: J gradient reads; + read/write of w, m, v; the clipped variant also writes and re-reads gbar
     bytes_per_param = wl.J * wl.grad_bytes + {"full": 24, "stats": 0, "adamw": 24, "clipped": 32}[mode]
     gbar_buf = torch.empty(wl.d, dtype=torch.float32, device=dev) if mode == "clipped" else None
@@ -332,8 +330,6 @@ def main():
                          "N > 0 = N layers of uneven, unaligned sizes")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and time replays (removes launch gaps; matters for small d)")
-    ap.add_argument("--one-pass", action="store_true",
-                    help="set NT_ONE_PASS (accepted and without effect: the step is one pass at every row count)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true",
                     help="skip the other workloads of the benchmark set (they run after the headline by default)")
@@ -353,10 +349,10 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     wl = make_workload(args.workload, dev, args.scale)
-    t = time_steps(wl, args.mode, args.steps, args.warmup, one_pass=args.one_pass, layers=args.layers,
+    t = time_steps(wl, args.mode, args.steps, args.warmup, layers=args.layers,
                    graph=args.graph, calib_copy_gib=args.calib_copy_gib)
     headline = (args.workload == HEADLINE and args.mode == "full" and args.scale == 1.0 and not args.layers
-                and not args.graph and not args.one_pass)
+                and not args.graph)
     ms_per_step = t["wall_ms_per_step"]
     value = t["alg_bytes"] / (ms_per_step * 1e-3) / 1e9
     achieved = t["alg_bytes"] / (t["ev_avg"] * 1e-3) / 1e9
@@ -404,7 +400,7 @@ def main():
             # counter-measured HBM bytes per step, quoted from the tracked profile of this kernel source (null if the
             # source has changed since that run, or if this is not a profiled configuration)
             "traffic": (traffic_from_profile(wl.name, args.mode)
-                        if (args.scale == 1.0 and not args.layers and not args.one_pass) else None),
+                        if (args.scale == 1.0 and not args.layers) else None),
         },
     }
     if not args.no_cpu_baseline and args.mode == "full":
