@@ -492,7 +492,8 @@ def test_coordinatewise_count_degenerate_and_sharded():
 # ------------------------------------------------------------------ rows given as separate allocations
 
 @pytest.mark.parametrize("J,gdtype,flags", [(8, torch.bfloat16, FULL), (4, torch.float32, FULL),
-                                            (37, torch.bfloat16, FULL), (8, torch.bfloat16, B.NT_DO_STATS)])
+                                            (37, torch.bfloat16, FULL), (18, torch.float32, FULL),
+                                            (8, torch.bfloat16, B.NT_DO_STATS)])
 def test_row_table_gives_the_same_bits_as_the_strided_matrix(J, gdtype, flags):
     d = 3 * 16384 + 2222
     wl = synth.make("t", J, d, gdtype=gdtype, sigma=1e-2, seed=50 + J, device=DEV)
@@ -737,7 +738,8 @@ def test_maximum_row_count():
 
 @pytest.mark.parametrize("J,gdtype,flags", [(8, torch.bfloat16, FULL), (4, torch.float32, FULL),
                                             (33, torch.bfloat16, FULL), (8, torch.bfloat16, B.NT_DO_STATS),
-                                            (16, torch.bfloat16, B.NT_DO_ADAMW)])
+                                            (16, torch.bfloat16, B.NT_DO_ADAMW), (19, torch.bfloat16, B.NT_DO_ADAMW),
+                                            (20, torch.float32, FULL)])
 def test_canaries_around_every_buffer_survive(J, gdtype, flags):
     """Every buffer the library may write sits between guard words; after a step (ragged d, with and
     without alignment) the guards and everything past d are untouched."""
