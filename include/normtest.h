@@ -85,8 +85,12 @@ typedef struct {
   uint32_t flags;                             /* NT_DO_* | NT_PARTIAL | NT_WRITE_GBAR | NT_COORD_TEST | NT_ONE_PASS */
 } nt_hyper;
 
-/* Where this call's coordinates sit in the full parameter vector (Sec. 3.3).  Informational: the sums
- * are additive over coordinates, so a shard needs nothing from the others. */
+/* Where this call's coordinates sit in the full parameter vector (Sec. 3.3).  The sums are additive over
+ * coordinates, so a shard needs nothing from the others; the record is checked for consistency, and d_global
+ * has one effect: the library cuts long vectors (2^26 coordinates and more) of 7 to 16 fp32 or 14 to 16 bf16
+ * rows into larger tiles than short ones (a step with AdamW only, which forms no sums: from 5 and 10 rows), and
+ * a call with a shard record is cut the way a vector of d_global coordinates is (a call without one: the way a
+ * vector of d is). */
 typedef struct {
   int32_t shard_id, num_shards;
   int64_t shard_offset, d_global;
@@ -126,7 +130,10 @@ typedef struct {
 
 /* Alignment, in coordinates, of the partial-sum tiles for J rows (every tile size divides it).  Results are
  * bit-identical for any split of a vector into calls whose boundaries are multiples of this, for the
- * same J, dtype and flags. */
+ * same J, dtype and flags, when each call names the vector's full length in shard->d_global (without shard
+ * records: when the parts and the whole are all shorter than 2^26 coordinates, or all at least that long, or
+ * the row count is outside the ranges named at nt_shard_info).  The updated w, m, v and a stored gbar never
+ * depend on how a vector is cut. */
 int64_t normtest_tile_coords(int64_t J);
 
 /* Bytes of device workspace normtest_step needs for J rows of d coordinates (0 if J or d is invalid): a 256-byte

@@ -12,8 +12,9 @@
 // call and were chosen by measurement; see tile_cfg() and the NT_CHUNK_* constants.  Two things about the memory
 // system shape the host side: blocks that start together stay in step for a while and are served faster than an
 // even mix of loads and stores, so a long vector is walked by several launches; and writes sprinkled among many
-// reads cost several times their volume, so with more than 16 rows a block updates the state of its whole tile
-// only after it has read all the rows (fast_tile_multi).
+// reads cost several times their volume, so with more than 16 rows (fast_tile_multi), and in long vectors from 28
+// bytes of gradient per coordinate on (fast_tile_defer), a block updates the state of its whole tile only after it
+// has read all the rows.
 //
 // Numerics.  The centred sum C = sum_j (g_j - gbar)^2 is formed directly from the J values of a
 // coordinate held in registers, never as A - B/J (which cancels badly when the workers agree).  A
@@ -49,6 +50,17 @@
 #define NT_FEW_ROWS 20           // 17 .. this many rows: the same tile as 256 threads x 8 sweeps (fused step +9 % at 17 rows,
 #define NT_BLOCK_FEW 256         // +7 % at 20, +3 % at 24 but AdamW only -1 % there, -1.5 % at 28): the walk is short
 #define NT_ITERS_FEW 8           // there, and a block's life with it
+// Up to 16 rows with at least NT_DEFER_ROW_BYTES of gradient per coordinate (14 bf16 or 7 fp32 rows; AdamW only:
+// NT_DEFER_ROW_BYTES_ADAMW, 10 or 5 rows), in a vector of at least NT_DEFER_COORDS coordinates: a step that writes
+// per coordinate runs like the many-row one, rows in registers but the update deferred and one generation of blocks
+// per launch (+2 .. +8 % there; with fewer bytes per coordinate, or fewer than some eight generations, the
+// interleaved class is as fast or faster).
+#define NT_DEFER_ROW_BYTES 28
+#define NT_DEFER_ROW_BYTES_ADAMW 20
+#define NT_DEFER_COORDS (1ll << 26)
+#define NT_BLOCK_DEFER 128
+#define NT_ITERS_DEFER 16
+#define NT_DEFER_UNROLL 1        // row sweeps in flight per lane in that class
 #define NT_BLOCK_LARGE_STATS 256 // J > 16, statistics only (nothing written per coordinate): short tiles, so that a
 #define NT_ITERS_LARGE_STATS 2   // vector of a few million coordinates still gives every CU several blocks
 #define NT_BLOCKS_PER_CU 4096    // grid = min(tiles, CUs * this); blocks stride over tiles beyond that
@@ -427,10 +439,50 @@ __device__ inline void gbar_store(const StepParams& p, int64_t i0, const float* 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fast tile, J <= 16 known at compile time: all J rows of a group of VEC coordinates sit in
-// registers; needs 16-byte aligned rows and state and a tile that lies wholly below d.
+// Fast tiles, J <= 16 known at compile time: all J rows of a group of VEC coordinates sit in
+// registers; they need 16-byte aligned rows and state and a tile that lies wholly below d.
 // The row sum is carried in fp64 so that the mean is correctly rounded even when the rows cancel.
 // ---------------------------------------------------------------------------------------------
+// One sweep's arithmetic: the means of the lane's VEC coordinates into gb, the sweep's sums into acc.
+template <class GT, int J, int MODE>
+__device__ inline void sweep_rows(const StepParams& p, const typename GT::raw_t* raw, float* gb, LaneAcc& acc) {
+  constexpr int VEC = GT::VEC;
+  double s[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) s[e] = (double)GT::val(raw[0], e);
+#pragma unroll
+  for (int j = 1; j < J; ++j)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) s[e] += (double)GT::val(raw[j], e);
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) gb[e] = (float)(s[e] * p.inv_J);
+
+  if constexpr (MODE != MODE_ADAMW) {
+    float a[VEC], c[VEC], b[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) a[e] = c[e] = 0.f;
+#pragma unroll
+    for (int j = 0; j < J; ++j)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        const float x = GT::val(raw[j], e);
+        const float r = x - gb[e];
+        c[e] = __builtin_fmaf(r, r, c[e]);
+        a[e] = __builtin_fmaf(x, x, a[e]);
+      }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const float sf = (float)s[e];
+      b[e] = sf * sf;
+      coord_test(p.coord_thr, c[e], gb[e], acc);
+    }
+    acc.A += (double)lane_tree<VEC>(a);
+    acc.B += (double)lane_tree<VEC>(b);
+    acc.C += (double)lane_tree<VEC>(c);
+  }
+}
+
+// State update interleaved with the rows: each sweep reads its rows and w, m, v, and writes the state back.
 template <class GT, int J, int MODE, int BLOCK, int ITERS, bool TABLE, bool GBAR>
 __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red)[BLOCK / 64][NT_NV], int buf) {
   constexpr int VEC = GT::VEC;
@@ -460,40 +512,8 @@ __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red
       // tiles are left free so that consecutive sweeps can overlap.
       __builtin_amdgcn_sched_barrier(0);
     }
-    double s[VEC];
     float gb[VEC];
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) s[e] = (double)GT::val(raw[0], e);
-#pragma unroll
-    for (int j = 1; j < J; ++j)
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) s[e] += (double)GT::val(raw[j], e);
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) gb[e] = (float)(s[e] * p.inv_J);
-
-    if constexpr (MODE != MODE_ADAMW) {
-      float a[VEC], c[VEC], b[VEC];
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) a[e] = c[e] = 0.f;
-#pragma unroll
-      for (int j = 0; j < J; ++j)
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-          const float x = GT::val(raw[j], e);
-          const float r = x - gb[e];
-          c[e] = __builtin_fmaf(r, r, c[e]);
-          a[e] = __builtin_fmaf(x, x, a[e]);
-        }
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) {
-        const float sf = (float)s[e];
-        b[e] = sf * sf;
-        coord_test(p.coord_thr, c[e], gb[e], acc);
-      }
-      acc.A += (double)lane_tree<VEC>(a);
-      acc.B += (double)lane_tree<VEC>(b);
-      acc.C += (double)lane_tree<VEC>(c);
-    }
+    sweep_rows<GT, J, MODE>(p, raw, gb, acc);
     if constexpr (MODE != MODE_STATS) adamw_store<VEC>(p, i0, gb, sw, sm, sv);
     if (GBAR && p.gbar) gbar_store<VEC>(p, i0, gb);
   }
@@ -501,6 +521,59 @@ __device__ inline void fast_tile(const StepParams& p, int64_t tile, double (*red
   // AdamW-only tiles end with a block barrier like the other modes: the waves of a block then finish together
   // and the next block's waves start together (measured +2 %)
   if constexpr (MODE == MODE_ADAMW) __syncthreads();
+}
+
+// The end of a tile whose state update was deferred: the means of all its sweeps wait in LDS (gbs) until every
+// row has been read, then w, m, v of all sweeps are read and written in one go.  The memory system charges writes
+// sprinkled among reads several times their volume; gathered at the end of a block's life, and with all blocks
+// of a launch living at the same time (one generation per launch), they reach it as a dense burst.
+template <int MODE, int BLOCK, int ITERS, bool GBAR>
+__device__ inline void deferred_update(const StepParams& p, int64_t tile, double (*red)[BLOCK / 64][NT_NV], int buf,
+                                       const LaneAcc& acc, const f32x4* gbs) {
+  constexpr int VEC = 4;
+  constexpr int TILE = BLOCK * VEC * ITERS;
+  // the barrier inside keeps the waves of the block together on their way into the write phase
+  if constexpr (MODE != MODE_ADAMW)
+    tile_reduce<BLOCK>(acc, red, buf, p.partials, tile);
+  else
+    __syncthreads();
+  if (MODE != MODE_STATS || p.gbar) {
+#pragma unroll 2
+    for (int it = 0; it < ITERS; ++it) {
+      const int64_t i0 = tile * TILE + ((int64_t)it * BLOCK + threadIdx.x) * VEC;
+      const f32x4 g4 = gbs[it * BLOCK + threadIdx.x];   // this lane's own values: no barrier needed for them
+      const float gb[VEC] = {g4[0], g4[1], g4[2], g4[3]};
+      if constexpr (MODE != MODE_STATS) {
+        u32x4 sw[1], sm[1], sv[1];
+        sw[0] = ld16(p.w + i0);
+        sm[0] = ld16(p.m + i0);
+        sv[0] = ld16(p.v + i0);
+        adamw_store<VEC>(p, i0, gb, sw, sm, sv);
+      }
+      if (GBAR && p.gbar) gbar_store<VEC>(p, i0, gb);
+    }
+  }
+}
+
+// Deferred state update, rows in registers: the sweeps read rows only.
+template <class GT, int J, int MODE, int BLOCK, int ITERS, bool TABLE, bool GBAR>
+__device__ inline void fast_tile_defer(const StepParams& p, int64_t tile, double (*red)[BLOCK / 64][NT_NV], int buf,
+                                       f32x4* gbs) {
+  constexpr int VEC = GT::VEC;
+  static_assert(VEC == 4, "one 16-byte LDS slot per lane and sweep");
+  constexpr int TILE = BLOCK * VEC * ITERS;
+  LaneAcc acc;
+#pragma unroll NT_DEFER_UNROLL
+  for (int it = 0; it < ITERS; ++it) {
+    const int64_t i0 = tile * TILE + ((int64_t)it * BLOCK + threadIdx.x) * VEC;
+    typename GT::raw_t raw[J];
+#pragma unroll
+    for (int j = 0; j < J; ++j) raw[j] = GT::ldraw(row_base<GT, TABLE>(p, j) + i0 * GT::ESIZE);
+    float gb[VEC];
+    sweep_rows<GT, J, MODE>(p, raw, gb, acc);
+    gbs[it * BLOCK + threadIdx.x] = f32x4{gb[0], gb[1], gb[2], gb[3]};
+  }
+  deferred_update<MODE, BLOCK, ITERS, GBAR>(p, tile, red, buf, acc, gbs);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -529,11 +602,8 @@ __device__ inline void chunk_accumulate(const typename GT::raw_t* raw, int nb, c
     }
 }
 
-// The state update (and the gbar store) of a tile is deferred: the means of all its sweeps wait in LDS until every
-// row has been read, then w, m, v of all sweeps are read and written in one go.  With many rows the writes are a few
-// per cent of the traffic, and the memory system charges writes sprinkled among reads several times their volume;
-// gathered at the end of a block's life, and with all blocks of a launch living at the same time (one generation
-// per launch), they reach it as a dense burst.
+// The state update (and the gbar store) of a tile is deferred (see deferred_update): with many rows the writes are
+// a few per cent of the traffic.
 template <class GT, int MODE, int BLOCK, int ITERS, bool TABLE, bool GBAR>
 __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double (*red)[BLOCK / 64][NT_NV], int buf,
                                        f32x4* gbs) {
@@ -596,32 +666,10 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
     }
     if constexpr (WRITES) gbs[it * BLOCK + threadIdx.x] = f32x4{gb[0], gb[1], gb[2], gb[3]};
   }
-  // the barrier inside keeps the waves of the block together on their way into the write phase
-  if constexpr (MODE != MODE_ADAMW)
-    tile_reduce<BLOCK>(acc, red, buf, p.partials, tile);
+  if constexpr (WRITES)
+    deferred_update<MODE, BLOCK, ITERS, GBAR>(p, tile, red, buf, acc, gbs);
   else
-    __syncthreads();
-  if constexpr (WRITES) {
-    if (MODE != MODE_STATS || p.gbar) {
-#pragma unroll 2
-      for (int it = 0; it < ITERS; ++it) {
-        const int64_t i0 = tile * TILE + ((int64_t)it * BLOCK + threadIdx.x) * VEC;
-        const f32x4 g4 = gbs[it * BLOCK + threadIdx.x];   // this lane's own values: no barrier needed for them
-        const float gb[VEC] = {g4[0], g4[1], g4[2], g4[3]};
-        if constexpr (MODE != MODE_STATS) {
-          u32x4 sw[VEC / 4], sm[VEC / 4], sv[VEC / 4];
-#pragma unroll
-          for (int q4 = 0; q4 < VEC / 4; ++q4) {
-            sw[q4] = ld16(p.w + i0 + 4 * q4);
-            sm[q4] = ld16(p.m + i0 + 4 * q4);
-            sv[q4] = ld16(p.v + i0 + 4 * q4);
-          }
-          adamw_store<VEC>(p, i0, gb, sw, sm, sv);
-        }
-        if (GBAR && p.gbar) gbar_store<VEC>(p, i0, gb);
-      }
-    }
-  }
+    tile_reduce<BLOCK>(acc, red, buf, p.partials, tile);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -632,14 +680,16 @@ __device__ inline void fast_tile_multi(const StepParams& p, int64_t tile, double
 // J_T = 0 selects the J > 16 row-walking variant.
 // ---------------------------------------------------------------------------------------------
 // GBAR = false compiles the gbar store out (statistics-only launch class, so that sweeps can overlap).
-template <class GT, int J_T, int MODE, int BLOCK, int ITERS, bool TABLE, bool GBAR>
+// DEFER_T: up to 16 rows with the state update deferred to the end of the tile (always so beyond 16 rows).
+template <class GT, int J_T, int MODE, int BLOCK, int ITERS, bool TABLE, bool GBAR, bool DEFER_T = false>
 __global__ __launch_bounds__(BLOCK) void k_step(StepParams p, int64_t nfull, int64_t ntiles, int64_t slot0, int64_t slot1,
                                                  WsControl* ctl) {
   constexpr int TILE = BLOCK * GT::VEC * ITERS;
   static_assert(NT_TILE_MAX % TILE == 0, "tile sizes must divide NT_TILE_MAX");
   __shared__ double red[2][BLOCK / 64][NT_NV];
-  // J > 16: the means of a tile's sweeps wait here for the deferred state update (see fast_tile_multi)
-  constexpr bool DEFER = (J_T == 0) && ((MODE != MODE_STATS) || GBAR);
+  // the means of a tile's sweeps wait here for the deferred state update (see deferred_update)
+  constexpr bool DEFER = (J_T == 0 || DEFER_T) && ((MODE != MODE_STATS) || GBAR);
+  static_assert(!DEFER_T || DEFER, "a deferred update needs something to write");
   __shared__ f32x4 gbs[DEFER ? ITERS * BLOCK + NT_LDS_PAD_LARGE / 16 : 1];
   int buf = 0;
   if constexpr (TABLE) {
@@ -651,7 +701,9 @@ __global__ __launch_bounds__(BLOCK) void k_step(StepParams p, int64_t nfull, int
     // rotate: the first nrest slots are the guarded tiles nfull.., then the fast tiles 0..nfull-1
     const int64_t tile = (t < nrest) ? nfull + t : t - nrest;
     if (tile < nfull) {
-      if constexpr (J_T > 0)
+      if constexpr (J_T > 0 && DEFER_T)
+        fast_tile_defer<GT, J_T, MODE, BLOCK, ITERS, TABLE, GBAR>(p, tile, red, buf, gbs);
+      else if constexpr (J_T > 0)
         fast_tile<GT, J_T, MODE, BLOCK, ITERS, TABLE, GBAR>(p, tile, red, buf);
       else
         fast_tile_multi<GT, MODE, BLOCK, ITERS, TABLE, GBAR>(p, tile, red, buf, gbs);
@@ -1152,37 +1204,53 @@ struct TileCfg {
   int block, iters;
   int64_t coords() const { return (int64_t)block * NT_VEC * iters; }
 };
-inline TileCfg tile_cfg(int64_t J, int mode, bool gbar) {
+constexpr int defer_row_bytes(int mode) { return mode == MODE_ADAMW ? NT_DEFER_ROW_BYTES_ADAMW : NT_DEFER_ROW_BYTES; }
+// Up to 16 rows: does this call take the class with the deferred update?  esize: bytes per gradient element;
+// d_whole: length of the vector the call is a part of (its own d unless the caller said otherwise), so that the
+// parts of a vector and the vector itself are cut into the same tiles.
+inline bool defer_rows(int64_t J, int esize, int mode, bool gbar, int64_t d_whole) {
+  if (J > NT_JCHUNK || (mode == MODE_STATS && !gbar)) return false;
+  return J * esize >= defer_row_bytes(mode) && d_whole >= NT_DEFER_COORDS;
+}
+inline TileCfg tile_cfg(int64_t J, int esize, int mode, bool gbar, int64_t d_whole) {
   if (J > NT_JCHUNK)
     return (mode == MODE_STATS && !gbar) ? TileCfg{NT_BLOCK_LARGE_STATS, NT_ITERS_LARGE_STATS}
                                          : TileCfg{NT_BLOCK_LARGE, NT_ITERS_LARGE};
+  if (defer_rows(J, esize, mode, gbar, d_whole)) return {NT_BLOCK_DEFER, NT_ITERS_DEFER};
   if (mode == MODE_STATS && gbar) return {NT_BLOCK_STATS_GBAR, NT_ITERS_STATS_GBAR};
   if (mode == MODE_STATS) return {NT_BLOCK_STATS, NT_ITERS_STATS};
   if (mode == MODE_ADAMW) return {NT_BLOCK_ADAMW, NT_ITERS_ADAMW};
   return {NT_BLOCK, NT_ITERS};
 }
 static_assert(NT_BLOCK_FEW * NT_ITERS_FEW == NT_BLOCK_LARGE * NT_ITERS_LARGE, "both many-row shapes own the same tile");
+static_assert(NT_BLOCK_DEFER * NT_ITERS_DEFER >= NT_BLOCK * NT_ITERS &&
+                  NT_BLOCK_DEFER * NT_ITERS_DEFER >= NT_BLOCK_ADAMW * NT_ITERS_ADAMW &&
+                  NT_BLOCK_DEFER * NT_ITERS_DEFER >= NT_BLOCK_STATS_GBAR * NT_ITERS_STATS_GBAR,
+              "the deferred class never has more tiles than the class it replaces: the workspace is sized by the latter");
 // tile slots per launch of the step kernel for the same classes (at least one, at most all)
-inline int64_t launch_tiles(int64_t J, int mode, bool gbar, int64_t ntiles) {
+inline int64_t launch_tiles(int64_t J, int esize, int mode, bool gbar, bool defer16, int64_t ntiles) {
   int64_t coords;
-  if (J > NT_JCHUNK)
+  if (J > NT_JCHUNK || defer16)
     return ntiles;   // one launch, or generations of blocks: launch_step_shape knows the kernel's occupancy
   else if (mode == MODE_STATS)
     coords = gbar ? NT_CHUNK_STATS_GBAR : NT_CHUNK_STATS;
   else
     coords = (mode == MODE_ADAMW) ? NT_CHUNK_ADAMW : NT_CHUNK_FULL;
-  const int64_t n = coords / tile_cfg(J, mode, gbar).coords();
+  const int64_t n = coords / tile_cfg(J, esize, mode, gbar, 0).coords();
   return (n < 1 || n > ntiles) ? ntiles : n;
 }
-// smallest tile any mode uses for this J: sizes the workspace
+// smallest tile any mode and gradient type uses for this J: sizes the workspace
 inline int64_t min_tile_coords(int64_t J) {
-  int64_t best = tile_cfg(J, MODE_FULL, false).coords();
+  int64_t best = tile_cfg(J, 2, MODE_FULL, false, 0).coords();
   const int modes[3] = {MODE_FULL, MODE_STATS, MODE_ADAMW};
   for (int m : modes)
-    for (int g = 0; g < 2; ++g) {
-      const int64_t c = tile_cfg(J, m, g != 0).coords();
-      if (c < best) best = c;
-    }
+    for (int g = 0; g < 2; ++g)
+      for (int esize = 2; esize <= 4; esize += 2) {
+        for (int64_t d_whole = 0; d_whole <= NT_DEFER_COORDS; d_whole += NT_DEFER_COORDS) {
+          const int64_t c = tile_cfg(J, esize, m, g != 0, d_whole).coords();
+          if (c < best) best = c;
+        }
+      }
   return best;
 }
 
@@ -1206,17 +1274,16 @@ bool hyper_ok(const nt_hyper* h, int64_t J) {
   return true;
 }
 
-// How many blocks of the many-row kernel a CU holds at a time (the runtime's occupancy query, asked once per
-// device and kernel; 4 if it cannot be had).
-template <class GT, int MODE, bool TABLE, int BS, int IS>
-int large_blocks_per_cu() {
+// How many blocks of a kernel with a deferred update a CU holds at a time (the runtime's occupancy query, asked
+// once per device and kernel; 4 if it cannot be had).
+template <auto KERNEL, int BS>
+int blocks_per_cu() {
   static int cached[64] = {0};
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 4;
   int n = __atomic_load_n(&cached[dev], __ATOMIC_RELAXED);
   if (n <= 0) {
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_step<GT, 0, MODE, BS, IS, TABLE, true>, BS, 0) != hipSuccess ||
-        n < 1) {
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, KERNEL, BS, 0) != hipSuccess || n < 1) {
       (void)hipGetLastError();
       n = 4;
     }
@@ -1226,14 +1293,32 @@ int large_blocks_per_cu() {
 }
 
 template <class GT, int MODE, bool TABLE, int BS, int IS, bool GBAR>
-hipError_t launch_step_shape(const StepParams& p, int64_t nfull, int64_t ntiles, WsControl* ctl, int max_grid,
-                             hipStream_t st) {
-  int64_t per_launch = launch_tiles(p.J, MODE, MODE == MODE_STATS && p.gbar != nullptr, ntiles);
-  if (p.J > NT_JCHUNK && (MODE != MODE_STATS || p.gbar != nullptr)) {
+hipError_t launch_step_shape(const StepParams& p, bool defer16, int64_t nfull, int64_t ntiles, WsControl* ctl,
+                             int max_grid, hipStream_t st) {
+  constexpr bool WRITES = (MODE != MODE_STATS) || GBAR;
+  const bool gbar = MODE == MODE_STATS && p.gbar != nullptr;
+  int64_t per_launch = launch_tiles(p.J, GT::ESIZE, MODE, gbar, defer16, ntiles);
+  if (WRITES && (p.J > NT_JCHUNK || defer16)) {
     // blocks that write per coordinate do so at the end of their lives: a launch holds whole generations of blocks
     // (as many as the chip runs at a time), so that all of them read together and write together
-    const int per_cu = (p.J <= NT_FEW_ROWS) ? large_blocks_per_cu<GT, MODE, TABLE, NT_BLOCK_FEW, NT_ITERS_FEW>()
-                                            : large_blocks_per_cu<GT, MODE, TABLE, NT_BLOCK_LARGE, NT_ITERS_LARGE>();
+    int per_cu = 4;
+    if constexpr (WRITES) {
+#define NT_OCC(JJ)                                                                                          \
+  case JJ:                                                                                                  \
+    if constexpr (JJ * GT::ESIZE >= defer_row_bytes(MODE))                                                  \
+      per_cu = blocks_per_cu<k_step<GT, JJ, MODE, NT_BLOCK_DEFER, NT_ITERS_DEFER, TABLE, true, true>,       \
+                             NT_BLOCK_DEFER>();                                                             \
+    break;
+      switch (p.J) {
+        NT_OCC(2) NT_OCC(3) NT_OCC(4) NT_OCC(5) NT_OCC(6) NT_OCC(7) NT_OCC(8) NT_OCC(9)
+        NT_OCC(10) NT_OCC(11) NT_OCC(12) NT_OCC(13) NT_OCC(14) NT_OCC(15) NT_OCC(16)
+        default:
+          per_cu = (p.J <= NT_FEW_ROWS)
+                       ? blocks_per_cu<k_step<GT, 0, MODE, NT_BLOCK_FEW, NT_ITERS_FEW, TABLE, true>, NT_BLOCK_FEW>()
+                       : blocks_per_cu<k_step<GT, 0, MODE, NT_BLOCK_LARGE, NT_ITERS_LARGE, TABLE, true>, NT_BLOCK_LARGE>();
+      }
+#undef NT_OCC
+    }
     per_launch = (int64_t)cu_count() * per_cu * NT_GENS_LARGE;
     if (per_launch > ntiles) per_launch = ntiles;
   }
@@ -1242,6 +1327,13 @@ hipError_t launch_step_shape(const StepParams& p, int64_t nfull, int64_t ntiles,
     const unsigned grid = (unsigned)((slot1 - slot0 < max_grid) ? slot1 - slot0 : max_grid);
 #define NT_CASE(JJ)                                                                                             \
   case JJ:                                                                                                      \
+    if constexpr (WRITES && JJ * GT::ESIZE >= defer_row_bytes(MODE)) {                                          \
+      if (defer16) {                                                                                            \
+        hipLaunchKernelGGL((k_step<GT, JJ, MODE, NT_BLOCK_DEFER, NT_ITERS_DEFER, TABLE, true, true>), dim3(grid), \
+                           dim3(NT_BLOCK_DEFER), 0, st, p, nfull, ntiles, slot0, slot1, ctl);                   \
+        break;                                                                                                  \
+      }                                                                                                         \
+    }                                                                                                           \
     hipLaunchKernelGGL((k_step<GT, JJ, MODE, BS, IS, TABLE, GBAR>), dim3(grid), dim3(BS), 0, st, p, nfull,      \
                        ntiles, slot0, slot1, ctl);                                                              \
     break;
@@ -1268,26 +1360,29 @@ hipError_t launch_step_shape(const StepParams& p, int64_t nfull, int64_t ntiles,
 
 // picks the launch class (block size, sweeps per tile) that tile_cfg() describes
 template <class GT, int MODE, bool TABLE>
-hipError_t launch_step(const StepParams& p, int64_t nfull, int64_t ntiles, WsControl* ctl, int grid, hipStream_t st) {
+hipError_t launch_step(const StepParams& p, bool defer16, int64_t nfull, int64_t ntiles, WsControl* ctl, int grid,
+                       hipStream_t st) {
   if constexpr (MODE == MODE_STATS) {
     if (p.gbar)
-      return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS_GBAR, NT_ITERS_STATS_GBAR, true>(p, nfull, ntiles, ctl,
-                                                                                                 grid, st);
-    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS, NT_ITERS_STATS, false>(p, nfull, ntiles, ctl, grid, st);
+      return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS_GBAR, NT_ITERS_STATS_GBAR, true>(p, defer16, nfull, ntiles,
+                                                                                                 ctl, grid, st);
+    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS, NT_ITERS_STATS, false>(p, false, nfull, ntiles, ctl, grid,
+                                                                                      st);
   } else if constexpr (MODE == MODE_ADAMW) {
-    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_ADAMW, NT_ITERS_ADAMW, true>(p, nfull, ntiles, ctl, grid, st);
+    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_ADAMW, NT_ITERS_ADAMW, true>(p, defer16, nfull, ntiles, ctl, grid,
+                                                                                     st);
   } else {
-    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK, NT_ITERS, true>(p, nfull, ntiles, ctl, grid, st);
+    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK, NT_ITERS, true>(p, defer16, nfull, ntiles, ctl, grid, st);
   }
 }
 
 template <class GT, bool TABLE>
-hipError_t launch_step_mode(int mode, const StepParams& p, int64_t nfull, int64_t ntiles, WsControl* ctl, int grid,
-                            hipStream_t st) {
+hipError_t launch_step_mode(int mode, const StepParams& p, bool defer16, int64_t nfull, int64_t ntiles, WsControl* ctl,
+                            int grid, hipStream_t st) {
   switch (mode) {
-    case MODE_FULL: return launch_step<GT, MODE_FULL, TABLE>(p, nfull, ntiles, ctl, grid, st);
-    case MODE_STATS: return launch_step<GT, MODE_STATS, TABLE>(p, nfull, ntiles, ctl, grid, st);
-    default: return launch_step<GT, MODE_ADAMW, TABLE>(p, nfull, ntiles, ctl, grid, st);
+    case MODE_FULL: return launch_step<GT, MODE_FULL, TABLE>(p, defer16, nfull, ntiles, ctl, grid, st);
+    case MODE_STATS: return launch_step<GT, MODE_STATS, TABLE>(p, defer16, nfull, ntiles, ctl, grid, st);
+    default: return launch_step<GT, MODE_ADAMW, TABLE>(p, defer16, nfull, ntiles, ctl, grid, st);
   }
 }
 
@@ -1371,12 +1466,14 @@ static int check_step_args(const void* grads, nt_dtype gdtype, int64_t J, int64_
 
 // Enqueue the streaming kernel and the reduction/decision kernels.  Arguments are already validated.
 // `table`: grads is a device array of J row pointers instead of the first row of a strided matrix.
-static int enqueue_step(const void* grads, bool table, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld, float* w,
-                        float* m, float* v, float* gbar_out, uint32_t flags, const nt_hyper* hyper, double max_norm,
-                        void* workspace, nt_result* result_dev, hipStream_t st) {
+// `d_whole`: length of the vector these d coordinates are a part of (d itself for a call that stands alone).
+static int enqueue_step(const void* grads, bool table, nt_dtype gdtype, int64_t J, int64_t d, int64_t d_whole,
+                        int64_t ld, float* w, float* m, float* v, float* gbar_out, uint32_t flags, const nt_hyper* hyper,
+                        double max_norm, void* workspace, nt_result* result_dev, hipStream_t st) {
   const int esize = gdtype == NT_F32 ? 4 : 2;
   const int mode = (flags & NT_DO_STATS) ? ((flags & NT_DO_ADAMW) ? MODE_FULL : MODE_STATS) : MODE_ADAMW;
-  const int64_t tc = tile_cfg(J, mode, (flags & NT_WRITE_GBAR) != 0).coords();
+  const bool defer16 = defer_rows(J, esize, mode, (flags & NT_WRITE_GBAR) != 0, d_whole);
+  const int64_t tc = tile_cfg(J, esize, mode, (flags & NT_WRITE_GBAR) != 0, d_whole).coords();
   const int64_t ntiles = (d + tc - 1) / tc;
 
   StepParams p;
@@ -1412,11 +1509,11 @@ static int enqueue_step(const void* grads, bool table, nt_dtype gdtype, int64_t 
     const int grid = (int)(ntiles < max_grid ? ntiles : max_grid);
     hipError_t e;
     if (table)
-      e = (gdtype == NT_F32) ? launch_step_mode<F32, true>(mode, p, nfull, ntiles, ctl, grid, st)
-                             : launch_step_mode<BF16, true>(mode, p, nfull, ntiles, ctl, grid, st);
+      e = (gdtype == NT_F32) ? launch_step_mode<F32, true>(mode, p, defer16, nfull, ntiles, ctl, grid, st)
+                             : launch_step_mode<BF16, true>(mode, p, defer16, nfull, ntiles, ctl, grid, st);
     else
-      e = (gdtype == NT_F32) ? launch_step_mode<F32, false>(mode, p, nfull, ntiles, ctl, grid, st)
-                             : launch_step_mode<BF16, false>(mode, p, nfull, ntiles, ctl, grid, st);
+      e = (gdtype == NT_F32) ? launch_step_mode<F32, false>(mode, p, defer16, nfull, ntiles, ctl, grid, st)
+                             : launch_step_mode<BF16, false>(mode, p, defer16, nfull, ntiles, ctl, grid, st);
     if (e != hipSuccess) return hip_code(e);
   }
 
@@ -1483,13 +1580,18 @@ static int enqueue_adamw_gbar(const float* gbar, int64_t d, float* w, float* m, 
   return NT_OK;
 }
 
+// Length of the vector a call's d coordinates belong to: what the caller's shard record says, else d.
+inline int64_t whole_length(int64_t d, const nt_shard_info* shard) {
+  return (shard && shard->d_global > d) ? shard->d_global : d;
+}
+
 // The step as the caller's flags describe it, always one pass (NT_ONE_PASS, which once kept many-row steps from
 // being split into two passes, is accepted and changes nothing).
-static int enqueue_step_routed(const void* grads, bool table, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld,
-                               float* w, float* m, float* v, float* gbar_out, const nt_hyper* hyper, void* workspace,
-                               nt_result* result_dev, hipStream_t st) {
-  return enqueue_step(grads, table, gdtype, J, d, ld, w, m, v, gbar_out, hyper->flags, hyper, 0.0, workspace,
-                      result_dev, st);
+static int enqueue_step_routed(const void* grads, bool table, nt_dtype gdtype, int64_t J, int64_t d,
+                               const nt_shard_info* shard, int64_t ld, float* w, float* m, float* v, float* gbar_out,
+                               const nt_hyper* hyper, void* workspace, nt_result* result_dev, hipStream_t st) {
+  return enqueue_step(grads, table, gdtype, J, d, whole_length(d, shard), ld, w, m, v, gbar_out, hyper->flags, hyper, 0.0,
+                      workspace, result_dev, st);
 }
 
 int normtest_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int64_t ld, float* w, float* m,
@@ -1499,7 +1601,7 @@ int normtest_step(const void* grads, nt_dtype gdtype, int64_t J, int64_t d, int6
   const int rc = check_step_args(grads, gdtype, J, d, ld, w, m, v, gbar_out, hyper->flags, hyper, shard, workspace,
                                  workspace_bytes, result_dev);
   if (rc != NT_OK) return rc;
-  return enqueue_step_routed(grads, false, gdtype, J, d, ld, w, m, v, gbar_out, hyper, workspace, result_dev,
+  return enqueue_step_routed(grads, false, gdtype, J, d, shard, ld, w, m, v, gbar_out, hyper, workspace, result_dev,
                              (hipStream_t)hip_stream);
 }
 
@@ -1511,7 +1613,7 @@ int normtest_step_rows(const void* const* grad_rows_dev, nt_dtype gdtype, int64_
   const int rc = check_step_args(grad_rows_dev, gdtype, J, d, d, w, m, v, gbar_out, hyper->flags, hyper, shard,
                                  workspace, workspace_bytes, result_dev);
   if (rc != NT_OK) return rc;
-  return enqueue_step_routed(grad_rows_dev, true, gdtype, J, d, d, w, m, v, gbar_out, hyper, workspace, result_dev,
+  return enqueue_step_routed(grad_rows_dev, true, gdtype, J, d, shard, d, w, m, v, gbar_out, hyper, workspace, result_dev,
                              (hipStream_t)hip_stream);
 }
 
@@ -1558,7 +1660,7 @@ int normtest_step_static(const void* grads, nt_dtype gdtype, int64_t J, int64_t 
   void* ws = nullptr;
   const int rs = scratch_address(&ws);
   if (rs != NT_OK) return rs;
-  return enqueue_step_routed(grads, false, gdtype, J, d, ld, w, m, v, gbar_out, &hy, ws, result_dev,
+  return enqueue_step_routed(grads, false, gdtype, J, d, shard, ld, w, m, v, gbar_out, &hy, ws, result_dev,
                              (hipStream_t)hip_stream);
 }
 
@@ -1574,7 +1676,7 @@ int normtest_step_clipped(const void* grads, nt_dtype gdtype, int64_t J, int64_t
                                  shard, workspace, workspace_bytes, result_dev);
   if (rc != NT_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
-  const int rc1 = enqueue_step(grads, false, gdtype, J, d, ld, nullptr, nullptr, nullptr, gbar_buf,
+  const int rc1 = enqueue_step(grads, false, gdtype, J, d, whole_length(d, shard), ld, nullptr, nullptr, nullptr, gbar_buf,
                                NT_DO_STATS | NT_WRITE_GBAR | (hyper->flags & NT_COORD_TEST), hyper, max_norm, workspace,
                                result_dev, st);
   if (rc1 != NT_OK) return rc1;

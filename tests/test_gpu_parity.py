@@ -629,10 +629,21 @@ def test_structural_sweep_over_entry_points_flags_and_alignment():
     """250 seeded draws of row count (2 .. 3000, every path and both routes), length, dtype, misalignment of rows
     and of state, row padding, entry point (strided, pointer table, clipped), mode, and the optional flags; all
     outputs against the oracle, and guard words around every buffer the library may write."""
-    rng = np.random.default_rng(21)
+    structural_sweep(21, 250, [2, 3, 5, 8, 13, 16, 17, 31, 47, 48, 64, 95, 96, 97, 300, 1000, 3000], 20000)
+
+
+def test_structural_sweep_as_parts_of_a_long_vector():
+    """The same sweep for 5 .. 16 rows with a shard record that names a vector of 2^26 coordinates: from 28 bytes of
+    gradient per coordinate on (all the fp32 draws, bf16 from 14 rows), the calls that write per coordinate then run
+    in the launch class with the deferred state update (AdamW only: from 20 bytes)."""
+    structural_sweep(23, 200, [5, 6, 7, 8, 9, 10, 12, 14, 15, 16], 30000, whole=1 << 26)
+
+
+def structural_sweep(seed, cases, J_choices, seed0, whole=None):
+    rng = np.random.default_rng(seed)
     guard = 16
-    for case in range(250):
-        J = int(rng.choice([2, 3, 5, 8, 13, 16, 17, 31, 47, 48, 64, 95, 96, 97, 300, 1000, 3000]))
+    for case in range(cases):
+        J = int(rng.choice(J_choices))
         d = int(rng.choice([1, 3, 4, 100, 2047, 2048, 2049, 4095, 4097, 8192, 16383, 16385, 30000]))
         if J * d > 20_000_000:
             d = 2049
@@ -651,7 +662,7 @@ def test_structural_sweep_over_entry_points_flags_and_alignment():
                         b_max=int(rng.choice([0, 512])), round_to=int(rng.choice([1, 16])), ddof=int(rng.integers(0, 2)))
         sigma = float(rng.choice([1e-3, 1e-2, 1e-1]))
         max_norm = float(rng.choice([0.0, 0.01, 100.0]))
-        src = synth.make("r", J, d, gdtype=gdtype, sigma=sigma, seed=20000 + case, device=DEV, hyper=h)
+        src = synth.make("r", J, d, gdtype=gdtype, sigma=sigma, seed=seed0 + case, device=DEV, hyper=h)
         if d == 1:
             continue                      # a one-element vector has no rms to measure AdamW errors against
         big = torch.full((J, off + d + pad), 3.0, dtype=gdtype, device=DEV)
@@ -672,17 +683,18 @@ def test_structural_sweep_over_entry_points_flags_and_alignment():
         ws = wsraw[64:64 + need]
         ctx = "case %d J=%d d=%d %s off=%d pad=%d soff=%d entry=%s mode=%s coord=%s gbar=%s partial=%s one_pass=%s" % (
             case, J, d, gdtype, off, pad, soff, entry, mode, coord, want_gbar, partial, one_pass)
+        shard = B.nt_shard_info(0, 1, 0, whole) if whole else None
         try:
             a = [view(t) if mode != "stats" else None for t in st]
             if entry == "step":
-                res = B.normtest_step(grads, a[0], a[1], a[2], hyper_of(h, fl), d=d,
+                res = B.normtest_step(grads, a[0], a[1], a[2], hyper_of(h, fl), d=d, shard=shard,
                                       gbar_out=view(gb) if want_gbar else None, workspace=ws)
             elif entry == "rows":
                 res = B.normtest_step_rows([big[j, off:off + d] for j in range(J)], a[0], a[1], a[2], hyper_of(h, fl),
-                                           d=d, gbar_out=view(gb) if want_gbar else None, workspace=ws)
+                                           d=d, shard=shard, gbar_out=view(gb) if want_gbar else None, workspace=ws)
             else:
                 res = B.normtest_step_clipped(grads, a[0], a[1], a[2], view(gb), max_norm, hyper_of(h, fl), d=d,
-                                              workspace=ws)
+                                              shard=shard, workspace=ws)
             torch.cuda.synchronize()
             r = B.read_result(res).as_dict()
             ref = H.oracle_full(grads, d, J, h)
