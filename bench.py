@@ -50,6 +50,7 @@ def traffic_from_profile(workload: str, mode: str, traffic_file: str = TRAFFIC_F
 
 
 def make_workload(name: str, device: str, scale: float):
+    import torch
     from paper_2412_21124_amd import synth
     if name == "flat_1p5b":
         return synth.flat_1p5b(d=int(1_500_000_000 * scale), device=device)
@@ -65,10 +66,18 @@ def make_workload(name: str, device: str, scale: float):
     if name == "tiny":
         return synth.tiny(1e-2, device=device)
     if name.startswith("rows:"):
-        # rows:J:d -- J bf16 rows of a flat d-coordinate vector with the headline's distribution (row-count sweeps)
-        _, J, d = name.split(":")
-        wl = synth.flat_1p5b(d=int(int(d) * scale), J=int(J), device=device)
-        wl.name = "rows_J%s" % J
+        # rows:J:d[:f32] -- J bf16 (fp32) rows of a flat d-coordinate vector with the headline's distribution
+        # (row-count sweeps)
+        parts = name.split(":")
+        if len(parts) not in (3, 4) or (len(parts) == 4 and parts[3] not in ("f32", "bf16")):
+            raise SystemExit("workload rows:J:d[:f32|:bf16], got %r" % name)
+        J, d = int(parts[1]), int(parts[2])
+        wl = synth.flat_1p5b(d=int(d * scale), J=J, device=device)
+        wl.name = "rows_J%d" % J
+        if len(parts) == 4 and parts[3] == "f32":
+            ref = wl.hyper
+            wl = synth.make("rows_J%d_f32" % J, J, int(d * scale), gdtype=torch.float32, sigma=1e-2, mu="normal",
+                            mu_scale=1e-2, hyper=ref, seed=0, device=device)
         return wl
     if name in ("paper_300m", "paper_1.1b", "paper_3.4b"):
         which = name.split("_")[1]

@@ -61,6 +61,7 @@
 #define NT_BLOCK_DEFER 128
 #define NT_ITERS_DEFER 16
 #define NT_DEFER_UNROLL 1        // row sweeps in flight per lane in that class
+#define NT_GENS_DEFER 1          // generations of blocks per launch in that class (two: -7 .. -10 %)
 #define NT_BLOCK_LARGE_STATS 256 // J > 16, statistics only (nothing written per coordinate): short tiles, so that a
 #define NT_ITERS_LARGE_STATS 2   // vector of a few million coordinates still gives every CU several blocks
 #define NT_BLOCKS_PER_CU 4096    // grid = min(tiles, CUs * this); blocks stride over tiles beyond that
@@ -1319,7 +1320,7 @@ hipError_t launch_step_shape(const StepParams& p, bool defer16, int64_t nfull, i
       }
 #undef NT_OCC
     }
-    per_launch = (int64_t)cu_count() * per_cu * NT_GENS_LARGE;
+    per_launch = (int64_t)cu_count() * per_cu * (defer16 ? NT_GENS_DEFER : NT_GENS_LARGE);
     if (per_launch > ntiles) per_launch = ntiles;
   }
   for (int64_t slot0 = 0; slot0 < ntiles; slot0 += per_launch) {
