@@ -87,10 +87,10 @@ typedef struct {
 
 /* Where this call's coordinates sit in the full parameter vector (Sec. 3.3).  The sums are additive over
  * coordinates, so a shard needs nothing from the others; the record is checked for consistency, and d_global
- * has one effect: the library cuts long vectors (2^26 coordinates and more) of 7 to 16 fp32 or 14 to 16 bf16
- * rows into larger tiles than short ones (a step with AdamW only, which forms no sums: from 5 and 10 rows), and
- * a call with a shard record is cut the way a vector of d_global coordinates is (a call without one: the way a
- * vector of d is). */
+ * has one effect: steps that write per coordinate cut long vectors into larger tiles than short ones (7 to 16
+ * fp32 or 14 to 16 bf16 rows: from 2^26 coordinates; 17 to 32 rows: from 2^24; more rows: from 3 * 2^21; a
+ * step with AdamW only, which forms no sums, also from 5 fp32 and 10 bf16 rows), and a call with a shard record
+ * is cut the way a vector of d_global coordinates is (a call without one: the way a vector of d is). */
 typedef struct {
   int32_t shard_id, num_shards;
   int64_t shard_offset, d_global;
@@ -131,9 +131,9 @@ typedef struct {
 /* Alignment, in coordinates, of the partial-sum tiles for J rows (every tile size divides it).  Results are
  * bit-identical for any split of a vector into calls whose boundaries are multiples of this, for the
  * same J, dtype and flags, when each call names the vector's full length in shard->d_global (without shard
- * records: when the parts and the whole are all shorter than 2^26 coordinates, or all at least that long, or
- * the row count is outside the ranges named at nt_shard_info).  The updated w, m, v and a stored gbar never
- * depend on how a vector is cut. */
+ * records: when the parts and the whole are all on one side of the length named at nt_shard_info for that
+ * row count, or the row count has none).  The updated w, m, v and a stored gbar never depend on how a vector
+ * is cut. */
 int64_t normtest_tile_coords(int64_t J);
 
 /* Bytes of device workspace normtest_step needs for J rows of d coordinates (0 if J or d is invalid): a 256-byte

@@ -62,6 +62,13 @@
 #define NT_ITERS_DEFER 16
 #define NT_DEFER_UNROLL 1        // row sweeps in flight per lane in that class
 #define NT_GENS_DEFER 1          // generations of blocks per launch in that class (two: -7 .. -10 %)
+// J > 16, modes that write per coordinate: the shapes above from about one generation of blocks on (up to 32 rows,
+// where a generation is short-lived and a half-empty one costs more, from two); shorter vectors in one launch of
+// short tiles, else a few large blocks would have the chip to themselves (512 rows, d = 2^18: 607 -> 92 us).
+#define NT_MANY_LONG_COORDS (3ll << 21)
+#define NT_MANY_LONG_COORDS_32 (1ll << 24)
+#define NT_BLOCK_MANY_SHORT 256
+#define NT_ITERS_MANY_SHORT 2
 #define NT_BLOCK_LARGE_STATS 256 // J > 16, statistics only (nothing written per coordinate): short tiles, so that a
 #define NT_ITERS_LARGE_STATS 2   // vector of a few million coordinates still gives every CU several blocks
 #define NT_BLOCKS_PER_CU 4096    // grid = min(tiles, CUs * this); blocks stride over tiles beyond that
@@ -1206,18 +1213,22 @@ struct TileCfg {
   int64_t coords() const { return (int64_t)block * NT_VEC * iters; }
 };
 constexpr int defer_row_bytes(int mode) { return mode == MODE_ADAMW ? NT_DEFER_ROW_BYTES_ADAMW : NT_DEFER_ROW_BYTES; }
-// Up to 16 rows: does this call take the class with the deferred update?  esize: bytes per gradient element;
-// d_whole: length of the vector the call is a part of (its own d unless the caller said otherwise), so that the
-// parts of a vector and the vector itself are cut into the same tiles.
-inline bool defer_rows(int64_t J, int esize, int mode, bool gbar, int64_t d_whole) {
-  if (J > NT_JCHUNK || (mode == MODE_STATS && !gbar)) return false;
+// Does this call take one of the classes for long vectors (large tiles, state update deferred, one generation of
+// blocks per launch)?  esize: bytes per gradient element; d_whole: length of the vector the call is a part of (its
+// own d unless the caller said otherwise), so that the parts of a vector and the vector itself are cut into the
+// same tiles.
+inline bool is_long_class(int64_t J, int esize, int mode, bool gbar, int64_t d_whole) {
+  if (mode == MODE_STATS && !gbar) return false;
+  if (J > NT_JCHUNK) return d_whole >= (J <= 32 ? NT_MANY_LONG_COORDS_32 : NT_MANY_LONG_COORDS);
   return J * esize >= defer_row_bytes(mode) && d_whole >= NT_DEFER_COORDS;
 }
 inline TileCfg tile_cfg(int64_t J, int esize, int mode, bool gbar, int64_t d_whole) {
-  if (J > NT_JCHUNK)
-    return (mode == MODE_STATS && !gbar) ? TileCfg{NT_BLOCK_LARGE_STATS, NT_ITERS_LARGE_STATS}
-                                         : TileCfg{NT_BLOCK_LARGE, NT_ITERS_LARGE};
-  if (defer_rows(J, esize, mode, gbar, d_whole)) return {NT_BLOCK_DEFER, NT_ITERS_DEFER};
+  const bool lng = is_long_class(J, esize, mode, gbar, d_whole);
+  if (J > NT_JCHUNK) {
+    if (mode == MODE_STATS && !gbar) return {NT_BLOCK_LARGE_STATS, NT_ITERS_LARGE_STATS};
+    return lng ? TileCfg{NT_BLOCK_LARGE, NT_ITERS_LARGE} : TileCfg{NT_BLOCK_MANY_SHORT, NT_ITERS_MANY_SHORT};
+  }
+  if (lng) return {NT_BLOCK_DEFER, NT_ITERS_DEFER};
   if (mode == MODE_STATS && gbar) return {NT_BLOCK_STATS_GBAR, NT_ITERS_STATS_GBAR};
   if (mode == MODE_STATS) return {NT_BLOCK_STATS, NT_ITERS_STATS};
   if (mode == MODE_ADAMW) return {NT_BLOCK_ADAMW, NT_ITERS_ADAMW};
@@ -1229,9 +1240,9 @@ static_assert(NT_BLOCK_DEFER * NT_ITERS_DEFER >= NT_BLOCK * NT_ITERS &&
                   NT_BLOCK_DEFER * NT_ITERS_DEFER >= NT_BLOCK_STATS_GBAR * NT_ITERS_STATS_GBAR,
               "the deferred class never has more tiles than the class it replaces: the workspace is sized by the latter");
 // tile slots per launch of the step kernel for the same classes (at least one, at most all)
-inline int64_t launch_tiles(int64_t J, int esize, int mode, bool gbar, bool defer16, int64_t ntiles) {
+inline int64_t launch_tiles(int64_t J, int esize, int mode, bool gbar, bool long_class, int64_t ntiles) {
   int64_t coords;
-  if (J > NT_JCHUNK || defer16)
+  if (J > NT_JCHUNK || long_class)
     return ntiles;   // one launch, or generations of blocks: launch_step_shape knows the kernel's occupancy
   else if (mode == MODE_STATS)
     coords = gbar ? NT_CHUNK_STATS_GBAR : NT_CHUNK_STATS;
@@ -1294,12 +1305,12 @@ int blocks_per_cu() {
 }
 
 template <class GT, int MODE, bool TABLE, int BS, int IS, bool GBAR>
-hipError_t launch_step_shape(const StepParams& p, bool defer16, int64_t nfull, int64_t ntiles, WsControl* ctl,
+hipError_t launch_step_shape(const StepParams& p, bool long_class, int64_t nfull, int64_t ntiles, WsControl* ctl,
                              int max_grid, hipStream_t st) {
   constexpr bool WRITES = (MODE != MODE_STATS) || GBAR;
   const bool gbar = MODE == MODE_STATS && p.gbar != nullptr;
-  int64_t per_launch = launch_tiles(p.J, GT::ESIZE, MODE, gbar, defer16, ntiles);
-  if (WRITES && (p.J > NT_JCHUNK || defer16)) {
+  int64_t per_launch = launch_tiles(p.J, GT::ESIZE, MODE, gbar, long_class, ntiles);
+  if (WRITES && long_class) {
     // blocks that write per coordinate do so at the end of their lives: a launch holds whole generations of blocks
     // (as many as the chip runs at a time), so that all of them read together and write together
     int per_cu = 4;
@@ -1320,7 +1331,7 @@ hipError_t launch_step_shape(const StepParams& p, bool defer16, int64_t nfull, i
       }
 #undef NT_OCC
     }
-    per_launch = (int64_t)cu_count() * per_cu * (defer16 ? NT_GENS_DEFER : NT_GENS_LARGE);
+    per_launch = (int64_t)cu_count() * per_cu * (p.J <= NT_JCHUNK ? NT_GENS_DEFER : NT_GENS_LARGE);
     if (per_launch > ntiles) per_launch = ntiles;
   }
   for (int64_t slot0 = 0; slot0 < ntiles; slot0 += per_launch) {
@@ -1329,7 +1340,7 @@ hipError_t launch_step_shape(const StepParams& p, bool defer16, int64_t nfull, i
 #define NT_CASE(JJ)                                                                                             \
   case JJ:                                                                                                      \
     if constexpr (WRITES && JJ * GT::ESIZE >= defer_row_bytes(MODE)) {                                          \
-      if (defer16) {                                                                                            \
+      if (long_class) {                                                                                         \
         hipLaunchKernelGGL((k_step<GT, JJ, MODE, NT_BLOCK_DEFER, NT_ITERS_DEFER, TABLE, true, true>), dim3(grid), \
                            dim3(NT_BLOCK_DEFER), 0, st, p, nfull, ntiles, slot0, slot1, ctl);                   \
         break;                                                                                                  \
@@ -1345,6 +1356,9 @@ hipError_t launch_step_shape(const StepParams& p, bool defer16, int64_t nfull, i
         if (MODE == MODE_STATS && p.gbar == nullptr)
           hipLaunchKernelGGL((k_step<GT, 0, MODE, NT_BLOCK_LARGE_STATS, NT_ITERS_LARGE_STATS, TABLE, false>), dim3(grid),
                              dim3(NT_BLOCK_LARGE_STATS), 0, st, p, nfull, ntiles, slot0, slot1, ctl);
+        else if (!long_class)
+          hipLaunchKernelGGL((k_step<GT, 0, MODE, NT_BLOCK_MANY_SHORT, NT_ITERS_MANY_SHORT, TABLE, true>), dim3(grid),
+                             dim3(NT_BLOCK_MANY_SHORT), 0, st, p, nfull, ntiles, slot0, slot1, ctl);
         else if (p.J <= NT_FEW_ROWS)
           hipLaunchKernelGGL((k_step<GT, 0, MODE, NT_BLOCK_FEW, NT_ITERS_FEW, TABLE, true>), dim3(grid),
                              dim3(NT_BLOCK_FEW), 0, st, p, nfull, ntiles, slot0, slot1, ctl);
@@ -1361,29 +1375,29 @@ hipError_t launch_step_shape(const StepParams& p, bool defer16, int64_t nfull, i
 
 // picks the launch class (block size, sweeps per tile) that tile_cfg() describes
 template <class GT, int MODE, bool TABLE>
-hipError_t launch_step(const StepParams& p, bool defer16, int64_t nfull, int64_t ntiles, WsControl* ctl, int grid,
+hipError_t launch_step(const StepParams& p, bool long_class, int64_t nfull, int64_t ntiles, WsControl* ctl, int grid,
                        hipStream_t st) {
   if constexpr (MODE == MODE_STATS) {
     if (p.gbar)
-      return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS_GBAR, NT_ITERS_STATS_GBAR, true>(p, defer16, nfull, ntiles,
-                                                                                                 ctl, grid, st);
+      return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS_GBAR, NT_ITERS_STATS_GBAR, true>(p, long_class, nfull,
+                                                                                                 ntiles, ctl, grid, st);
     return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS, NT_ITERS_STATS, false>(p, false, nfull, ntiles, ctl, grid,
                                                                                       st);
   } else if constexpr (MODE == MODE_ADAMW) {
-    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_ADAMW, NT_ITERS_ADAMW, true>(p, defer16, nfull, ntiles, ctl, grid,
-                                                                                     st);
+    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_ADAMW, NT_ITERS_ADAMW, true>(p, long_class, nfull, ntiles, ctl,
+                                                                                     grid, st);
   } else {
-    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK, NT_ITERS, true>(p, defer16, nfull, ntiles, ctl, grid, st);
+    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK, NT_ITERS, true>(p, long_class, nfull, ntiles, ctl, grid, st);
   }
 }
 
 template <class GT, bool TABLE>
-hipError_t launch_step_mode(int mode, const StepParams& p, bool defer16, int64_t nfull, int64_t ntiles, WsControl* ctl,
-                            int grid, hipStream_t st) {
+hipError_t launch_step_mode(int mode, const StepParams& p, bool long_class, int64_t nfull, int64_t ntiles,
+                            WsControl* ctl, int grid, hipStream_t st) {
   switch (mode) {
-    case MODE_FULL: return launch_step<GT, MODE_FULL, TABLE>(p, defer16, nfull, ntiles, ctl, grid, st);
-    case MODE_STATS: return launch_step<GT, MODE_STATS, TABLE>(p, defer16, nfull, ntiles, ctl, grid, st);
-    default: return launch_step<GT, MODE_ADAMW, TABLE>(p, defer16, nfull, ntiles, ctl, grid, st);
+    case MODE_FULL: return launch_step<GT, MODE_FULL, TABLE>(p, long_class, nfull, ntiles, ctl, grid, st);
+    case MODE_STATS: return launch_step<GT, MODE_STATS, TABLE>(p, long_class, nfull, ntiles, ctl, grid, st);
+    default: return launch_step<GT, MODE_ADAMW, TABLE>(p, long_class, nfull, ntiles, ctl, grid, st);
   }
 }
 
@@ -1473,7 +1487,7 @@ static int enqueue_step(const void* grads, bool table, nt_dtype gdtype, int64_t 
                         double max_norm, void* workspace, nt_result* result_dev, hipStream_t st) {
   const int esize = gdtype == NT_F32 ? 4 : 2;
   const int mode = (flags & NT_DO_STATS) ? ((flags & NT_DO_ADAMW) ? MODE_FULL : MODE_STATS) : MODE_ADAMW;
-  const bool defer16 = defer_rows(J, esize, mode, (flags & NT_WRITE_GBAR) != 0, d_whole);
+  const bool long_class = is_long_class(J, esize, mode, (flags & NT_WRITE_GBAR) != 0, d_whole);
   const int64_t tc = tile_cfg(J, esize, mode, (flags & NT_WRITE_GBAR) != 0, d_whole).coords();
   const int64_t ntiles = (d + tc - 1) / tc;
 
@@ -1510,11 +1524,11 @@ static int enqueue_step(const void* grads, bool table, nt_dtype gdtype, int64_t 
     const int grid = (int)(ntiles < max_grid ? ntiles : max_grid);
     hipError_t e;
     if (table)
-      e = (gdtype == NT_F32) ? launch_step_mode<F32, true>(mode, p, defer16, nfull, ntiles, ctl, grid, st)
-                             : launch_step_mode<BF16, true>(mode, p, defer16, nfull, ntiles, ctl, grid, st);
+      e = (gdtype == NT_F32) ? launch_step_mode<F32, true>(mode, p, long_class, nfull, ntiles, ctl, grid, st)
+                             : launch_step_mode<BF16, true>(mode, p, long_class, nfull, ntiles, ctl, grid, st);
     else
-      e = (gdtype == NT_F32) ? launch_step_mode<F32, false>(mode, p, defer16, nfull, ntiles, ctl, grid, st)
-                             : launch_step_mode<BF16, false>(mode, p, defer16, nfull, ntiles, ctl, grid, st);
+      e = (gdtype == NT_F32) ? launch_step_mode<F32, false>(mode, p, long_class, nfull, ntiles, ctl, grid, st)
+                             : launch_step_mode<BF16, false>(mode, p, long_class, nfull, ntiles, ctl, grid, st);
     if (e != hipSuccess) return hip_code(e);
   }
 

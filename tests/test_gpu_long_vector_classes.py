@@ -1,8 +1,10 @@
 """Up to 16 rows with at least 28 bytes of gradient per coordinate (14 bf16 or 7 fp32 rows; AdamW only: 20 bytes),
-in a vector of at least 2^26 coordinates: steps that write per coordinate run in a second launch class (rows in registers, the state update
-deferred to the end of an 8192-coordinate tile, one generation of blocks per launch).  The class is chosen by the
-length of the whole vector, which a call that covers a part of it states in its shard record; the small cases here
-use that to reach the class with vectors the oracle finishes in a moment, the last ones run it at its real size."""
+in a vector of at least 2^26 coordinates: steps that write per coordinate run in a second launch class (rows in
+registers, the state update deferred to the end of an 8192-coordinate tile, one generation of blocks per launch).
+More than 16 rows run that way from 2^24 coordinates on (more than 32 rows: 3 * 2^21) and in one launch of
+2048-coordinate tiles below.  The class is chosen by the length of the whole vector, which a call that covers a
+part of it states in its shard record; the small cases here use that to reach the classes for long vectors with
+vectors the oracle finishes in a moment, the last ones run them at their real size."""
 import math
 
 import pytest
@@ -53,7 +55,9 @@ def shifted_copy(wl: synth.Workload):
 
 
 CASES = [(14, torch.bfloat16), (15, torch.bfloat16), (16, torch.bfloat16),
-         (7, torch.float32), (8, torch.float32), (11, torch.float32), (16, torch.float32)]
+         (7, torch.float32), (8, torch.float32), (11, torch.float32), (16, torch.float32),
+         # more than 16 rows: short vectors run in one launch of 2048-coordinate tiles, long ones like the above
+         (17, torch.bfloat16), (20, torch.float32), (21, torch.bfloat16), (33, torch.bfloat16), (100, torch.bfloat16)]
 
 
 @pytest.mark.parametrize("J,gdtype", CASES)
@@ -170,20 +174,20 @@ def test_row_table_and_clipped_step_in_the_deferred_class():
     assert H.oracle_adamw_check(wl.grads, d, *state0, wl.w, wl.m, wl.v, wl.hyper, gbar=gbar, grad_scale=coef) == d
 
 
-def test_parts_of_a_long_vector_add_up_bit_exactly():
+@pytest.mark.parametrize("J,whole", [(16, WHOLE), (24, 1 << 24)])
+def test_parts_of_a_long_vector_add_up_bit_exactly(J, whole):
     """A vector long enough for the class, cut at multiples of normtest_tile_coords into parts that are far too short
     for it on their own: with the whole length in their shard records they are cut into the same tiles, so the
     combined sums and the state equal the one call's bit for bit."""
-    J = 16
     tc = B.normtest_tile_coords(J)
-    d = WHOLE + 3 * tc + 517
+    d = whole + 3 * tc + 517
     wl = synth.make("t", J, d, gdtype=torch.bfloat16, sigma=1e-2, seed=49, device=DEV, hyper=synth.Hyper(b_k=64, round_to=J, step=2))
     state0 = (wl.w.clone(), wl.m.clone(), wl.v.clone())
-    whole = run(wl, FULL)
+    full = run(wl, FULL)
     whole_state = (wl.w.clone(), wl.m.clone(), wl.v.clone())
     for t, s in zip((wl.w, wl.m, wl.v), state0):
         t.copy_(s)
-    cuts = [0, 2 * tc, 1000 * tc, WHOLE + tc, d]
+    cuts = [0, 2 * tc, 100 * tc, whole // 2 + tc, d]
     parts = []
     for sid, (lo, hi) in enumerate(zip(cuts[:-1], cuts[1:])):
         res = B.normtest_step(wl.grads[:, lo:hi], wl.w[lo:hi], wl.m[lo:hi], wl.v[lo:hi],
@@ -192,7 +196,7 @@ def test_parts_of_a_long_vector_add_up_bit_exactly():
         parts.append(B.read_result(res))
     comb = B.normtest_combine(parts, J, hyper_of(wl.hyper)).as_dict()
     for k in ("A", "B", "C", "gbar_sq", "var_l1", "T", "next_b", "pass", "status"):
-        assert comb[k] == whole[k], k
+        assert comb[k] == full[k], k
     for a, b in zip((wl.w, wl.m, wl.v), whole_state):
         assert torch.equal(a, b)
 

@@ -633,10 +633,11 @@ def test_structural_sweep_over_entry_points_flags_and_alignment():
 
 
 def test_structural_sweep_as_parts_of_a_long_vector():
-    """The same sweep for 5 .. 16 rows with a shard record that names a vector of 2^26 coordinates: from 28 bytes of
-    gradient per coordinate on (all the fp32 draws, bf16 from 14 rows), the calls that write per coordinate then run
-    in the launch class with the deferred state update (AdamW only: from 20 bytes)."""
-    structural_sweep(23, 200, [5, 6, 7, 8, 9, 10, 12, 14, 15, 16], 30000, whole=1 << 26)
+    """The same sweep with a shard record that names a vector of 2^26 coordinates, which selects the launch classes
+    for long vectors: up to 16 rows from 28 bytes of gradient per coordinate on (all the fp32 draws from 7 rows, bf16
+    from 14 rows; AdamW only: from 20 bytes), and beyond 16 rows always (without the record these short vectors
+    run in one launch of short tiles)."""
+    structural_sweep(23, 260, [5, 6, 7, 8, 9, 10, 12, 14, 15, 16, 17, 20, 24, 47, 64, 300], 30000, whole=1 << 26)
 
 
 def structural_sweep(seed, cases, J_choices, seed0, whole=None):
