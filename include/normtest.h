@@ -87,10 +87,11 @@ typedef struct {
 
 /* Where this call's coordinates sit in the full parameter vector (Sec. 3.3).  The sums are additive over
  * coordinates, so a shard needs nothing from the others; the record is checked for consistency, and d_global
- * has one effect: steps that write per coordinate cut long vectors into larger tiles than short ones (7 to 16
- * fp32 or 14 to 16 bf16 rows: from 2^26 coordinates; 17 to 32 rows: from 2^24; more rows: from 3 * 2^21; a
- * step with AdamW only, which forms no sums, also from 5 fp32 and 10 bf16 rows), and a call with a shard record
- * is cut the way a vector of d_global coordinates is (a call without one: the way a vector of d is). */
+ * has one effect: long vectors are cut into larger tiles than short ones (steps that write per coordinate,
+ * with 7 to 16 fp32 or 14 to 16 bf16 rows: from 2^26 coordinates; 17 to 32 rows: from 2^24; more rows: from
+ * 3 * 2^21; a step with AdamW only, which forms no sums, also from 5 fp32 and 10 bf16 rows; read-only
+ * statistics of up to 16 rows: from 2^21), and a call with a shard record is cut the way a vector of d_global
+ * coordinates is (a call without one: the way a vector of d is). */
 typedef struct {
   int32_t shard_id, num_shards;
   int64_t shard_offset, d_global;

@@ -39,6 +39,8 @@
 #define NT_ITERS 1
 #define NT_BLOCK_STATS 512       // J <= 16, statistics only: read-only and few bytes per lane, so smaller blocks
 #define NT_ITERS_STATS 8         // that each walk a longer tile
+#define NT_STATS_SHORT_COORDS (1ll << 21)  // ... in vectors shorter than this, the next shape (64 blocks of 512 threads
+                                           // for 2^20 coordinates leave most of the chip idle: 18 -> 14 us at 8 rows)
 #define NT_BLOCK_STATS_GBAR 512  // statistics that also store gbar (phase 1 of the clipped variant): one write
 #define NT_ITERS_STATS_GBAR 2    // stream moves the optimum to shorter tiles
 #define NT_BLOCK_ADAMW 1024      // J <= 16, AdamW only (test skipped)
@@ -1213,23 +1215,25 @@ struct TileCfg {
   int64_t coords() const { return (int64_t)block * NT_VEC * iters; }
 };
 constexpr int defer_row_bytes(int mode) { return mode == MODE_ADAMW ? NT_DEFER_ROW_BYTES_ADAMW : NT_DEFER_ROW_BYTES; }
-// Does this call take one of the classes for long vectors (large tiles, state update deferred, one generation of
-// blocks per launch)?  esize: bytes per gradient element; d_whole: length of the vector the call is a part of (its
-// own d unless the caller said otherwise), so that the parts of a vector and the vector itself are cut into the
-// same tiles.
-inline bool is_long_class(int64_t J, int esize, int mode, bool gbar, int64_t d_whole) {
-  if (mode == MODE_STATS && !gbar) return false;
-  if (J > NT_JCHUNK) return d_whole >= (J <= 32 ? NT_MANY_LONG_COORDS_32 : NT_MANY_LONG_COORDS);
-  return J * esize >= defer_row_bytes(mode) && d_whole >= NT_DEFER_COORDS;
+// Which launch class a call takes beside its row count, dtype and mode: CLS_LONG, the classes for long vectors
+// (large tiles, state update deferred, one generation of blocks per launch); CLS_SHORT_STATS, read-only statistics
+// of up to 16 rows over a short vector; else CLS_BASE.  esize: bytes per gradient element; d_whole: length of the
+// vector the call is a part of (its own d unless the caller said otherwise), so that the parts of a vector and the
+// vector itself are cut into the same tiles.
+enum { CLS_BASE = 0, CLS_LONG = 1, CLS_SHORT_STATS = 2 };
+inline int launch_class(int64_t J, int esize, int mode, bool gbar, int64_t d_whole) {
+  if (mode == MODE_STATS && !gbar) return (J <= NT_JCHUNK && d_whole < NT_STATS_SHORT_COORDS) ? CLS_SHORT_STATS : CLS_BASE;
+  if (J > NT_JCHUNK) return d_whole >= (J <= 32 ? NT_MANY_LONG_COORDS_32 : NT_MANY_LONG_COORDS) ? CLS_LONG : CLS_BASE;
+  return (J * esize >= defer_row_bytes(mode) && d_whole >= NT_DEFER_COORDS) ? CLS_LONG : CLS_BASE;
 }
 inline TileCfg tile_cfg(int64_t J, int esize, int mode, bool gbar, int64_t d_whole) {
-  const bool lng = is_long_class(J, esize, mode, gbar, d_whole);
+  const int cls = launch_class(J, esize, mode, gbar, d_whole);
   if (J > NT_JCHUNK) {
     if (mode == MODE_STATS && !gbar) return {NT_BLOCK_LARGE_STATS, NT_ITERS_LARGE_STATS};
-    return lng ? TileCfg{NT_BLOCK_LARGE, NT_ITERS_LARGE} : TileCfg{NT_BLOCK_MANY_SHORT, NT_ITERS_MANY_SHORT};
+    return cls == CLS_LONG ? TileCfg{NT_BLOCK_LARGE, NT_ITERS_LARGE} : TileCfg{NT_BLOCK_MANY_SHORT, NT_ITERS_MANY_SHORT};
   }
-  if (lng) return {NT_BLOCK_DEFER, NT_ITERS_DEFER};
-  if (mode == MODE_STATS && gbar) return {NT_BLOCK_STATS_GBAR, NT_ITERS_STATS_GBAR};
+  if (cls == CLS_LONG) return {NT_BLOCK_DEFER, NT_ITERS_DEFER};
+  if (mode == MODE_STATS && (gbar || cls == CLS_SHORT_STATS)) return {NT_BLOCK_STATS_GBAR, NT_ITERS_STATS_GBAR};
   if (mode == MODE_STATS) return {NT_BLOCK_STATS, NT_ITERS_STATS};
   if (mode == MODE_ADAMW) return {NT_BLOCK_ADAMW, NT_ITERS_ADAMW};
   return {NT_BLOCK, NT_ITERS};
@@ -1240,9 +1244,9 @@ static_assert(NT_BLOCK_DEFER * NT_ITERS_DEFER >= NT_BLOCK * NT_ITERS &&
                   NT_BLOCK_DEFER * NT_ITERS_DEFER >= NT_BLOCK_STATS_GBAR * NT_ITERS_STATS_GBAR,
               "the deferred class never has more tiles than the class it replaces: the workspace is sized by the latter");
 // tile slots per launch of the step kernel for the same classes (at least one, at most all)
-inline int64_t launch_tiles(int64_t J, int esize, int mode, bool gbar, bool long_class, int64_t ntiles) {
+inline int64_t launch_tiles(int64_t J, int esize, int mode, bool gbar, int cls, int64_t ntiles) {
   int64_t coords;
-  if (J > NT_JCHUNK || long_class)
+  if (J > NT_JCHUNK || cls != CLS_BASE)
     return ntiles;   // one launch, or generations of blocks: launch_step_shape knows the kernel's occupancy
   else if (mode == MODE_STATS)
     coords = gbar ? NT_CHUNK_STATS_GBAR : NT_CHUNK_STATS;
@@ -1258,7 +1262,7 @@ inline int64_t min_tile_coords(int64_t J) {
   for (int m : modes)
     for (int g = 0; g < 2; ++g)
       for (int esize = 2; esize <= 4; esize += 2) {
-        for (int64_t d_whole = 0; d_whole <= NT_DEFER_COORDS; d_whole += NT_DEFER_COORDS) {
+        for (int64_t d_whole = 0; d_whole <= NT_DEFER_COORDS; d_whole += NT_DEFER_COORDS) {   // shortest and longest
           const int64_t c = tile_cfg(J, esize, m, g != 0, d_whole).coords();
           if (c < best) best = c;
         }
@@ -1305,11 +1309,12 @@ int blocks_per_cu() {
 }
 
 template <class GT, int MODE, bool TABLE, int BS, int IS, bool GBAR>
-hipError_t launch_step_shape(const StepParams& p, bool long_class, int64_t nfull, int64_t ntiles, WsControl* ctl,
+hipError_t launch_step_shape(const StepParams& p, int cls, int64_t nfull, int64_t ntiles, WsControl* ctl,
                              int max_grid, hipStream_t st) {
+  const bool long_class = cls == CLS_LONG;
   constexpr bool WRITES = (MODE != MODE_STATS) || GBAR;
   const bool gbar = MODE == MODE_STATS && p.gbar != nullptr;
-  int64_t per_launch = launch_tiles(p.J, GT::ESIZE, MODE, gbar, long_class, ntiles);
+  int64_t per_launch = launch_tiles(p.J, GT::ESIZE, MODE, gbar, cls, ntiles);
   if (WRITES && long_class) {
     // blocks that write per coordinate do so at the end of their lives: a launch holds whole generations of blocks
     // (as many as the chip runs at a time), so that all of them read together and write together
@@ -1375,29 +1380,30 @@ hipError_t launch_step_shape(const StepParams& p, bool long_class, int64_t nfull
 
 // picks the launch class (block size, sweeps per tile) that tile_cfg() describes
 template <class GT, int MODE, bool TABLE>
-hipError_t launch_step(const StepParams& p, bool long_class, int64_t nfull, int64_t ntiles, WsControl* ctl, int grid,
+hipError_t launch_step(const StepParams& p, int cls, int64_t nfull, int64_t ntiles, WsControl* ctl, int grid,
                        hipStream_t st) {
   if constexpr (MODE == MODE_STATS) {
-    if (p.gbar)
-      return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS_GBAR, NT_ITERS_STATS_GBAR, true>(p, long_class, nfull,
-                                                                                                 ntiles, ctl, grid, st);
-    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS, NT_ITERS_STATS, false>(p, false, nfull, ntiles, ctl, grid,
+    // read-only statistics over a short vector borrow the kernels that can also store gbar (there is none to store)
+    if (p.gbar || (cls == CLS_SHORT_STATS && p.J <= NT_JCHUNK))
+      return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS_GBAR, NT_ITERS_STATS_GBAR, true>(p, cls, nfull, ntiles,
+                                                                                                 ctl, grid, st);
+    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_STATS, NT_ITERS_STATS, false>(p, cls, nfull, ntiles, ctl, grid,
                                                                                       st);
   } else if constexpr (MODE == MODE_ADAMW) {
-    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_ADAMW, NT_ITERS_ADAMW, true>(p, long_class, nfull, ntiles, ctl,
-                                                                                     grid, st);
+    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK_ADAMW, NT_ITERS_ADAMW, true>(p, cls, nfull, ntiles, ctl, grid,
+                                                                                     st);
   } else {
-    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK, NT_ITERS, true>(p, long_class, nfull, ntiles, ctl, grid, st);
+    return launch_step_shape<GT, MODE, TABLE, NT_BLOCK, NT_ITERS, true>(p, cls, nfull, ntiles, ctl, grid, st);
   }
 }
 
 template <class GT, bool TABLE>
-hipError_t launch_step_mode(int mode, const StepParams& p, bool long_class, int64_t nfull, int64_t ntiles,
-                            WsControl* ctl, int grid, hipStream_t st) {
+hipError_t launch_step_mode(int mode, const StepParams& p, int cls, int64_t nfull, int64_t ntiles, WsControl* ctl,
+                            int grid, hipStream_t st) {
   switch (mode) {
-    case MODE_FULL: return launch_step<GT, MODE_FULL, TABLE>(p, long_class, nfull, ntiles, ctl, grid, st);
-    case MODE_STATS: return launch_step<GT, MODE_STATS, TABLE>(p, long_class, nfull, ntiles, ctl, grid, st);
-    default: return launch_step<GT, MODE_ADAMW, TABLE>(p, long_class, nfull, ntiles, ctl, grid, st);
+    case MODE_FULL: return launch_step<GT, MODE_FULL, TABLE>(p, cls, nfull, ntiles, ctl, grid, st);
+    case MODE_STATS: return launch_step<GT, MODE_STATS, TABLE>(p, cls, nfull, ntiles, ctl, grid, st);
+    default: return launch_step<GT, MODE_ADAMW, TABLE>(p, cls, nfull, ntiles, ctl, grid, st);
   }
 }
 
@@ -1487,7 +1493,7 @@ static int enqueue_step(const void* grads, bool table, nt_dtype gdtype, int64_t 
                         double max_norm, void* workspace, nt_result* result_dev, hipStream_t st) {
   const int esize = gdtype == NT_F32 ? 4 : 2;
   const int mode = (flags & NT_DO_STATS) ? ((flags & NT_DO_ADAMW) ? MODE_FULL : MODE_STATS) : MODE_ADAMW;
-  const bool long_class = is_long_class(J, esize, mode, (flags & NT_WRITE_GBAR) != 0, d_whole);
+  const int cls = launch_class(J, esize, mode, (flags & NT_WRITE_GBAR) != 0, d_whole);
   const int64_t tc = tile_cfg(J, esize, mode, (flags & NT_WRITE_GBAR) != 0, d_whole).coords();
   const int64_t ntiles = (d + tc - 1) / tc;
 
@@ -1524,11 +1530,11 @@ static int enqueue_step(const void* grads, bool table, nt_dtype gdtype, int64_t 
     const int grid = (int)(ntiles < max_grid ? ntiles : max_grid);
     hipError_t e;
     if (table)
-      e = (gdtype == NT_F32) ? launch_step_mode<F32, true>(mode, p, long_class, nfull, ntiles, ctl, grid, st)
-                             : launch_step_mode<BF16, true>(mode, p, long_class, nfull, ntiles, ctl, grid, st);
+      e = (gdtype == NT_F32) ? launch_step_mode<F32, true>(mode, p, cls, nfull, ntiles, ctl, grid, st)
+                             : launch_step_mode<BF16, true>(mode, p, cls, nfull, ntiles, ctl, grid, st);
     else
-      e = (gdtype == NT_F32) ? launch_step_mode<F32, false>(mode, p, long_class, nfull, ntiles, ctl, grid, st)
-                             : launch_step_mode<BF16, false>(mode, p, long_class, nfull, ntiles, ctl, grid, st);
+      e = (gdtype == NT_F32) ? launch_step_mode<F32, false>(mode, p, cls, nfull, ntiles, ctl, grid, st)
+                             : launch_step_mode<BF16, false>(mode, p, cls, nfull, ntiles, ctl, grid, st);
     if (e != hipSuccess) return hip_code(e);
   }
 

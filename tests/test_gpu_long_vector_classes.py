@@ -144,6 +144,36 @@ def test_adamw_only_takes_the_deferred_class_from_fewer_rows(J, gdtype):
     assert H.oracle_adamw_check(wl.grads, d, *state0, wl.w, wl.m, wl.v, wl.hyper) == d
 
 
+@pytest.mark.parametrize("J,gdtype", [(2, torch.bfloat16), (8, torch.bfloat16), (16, torch.bfloat16), (4, torch.float32)])
+def test_read_only_statistics_in_both_tile_sizes(J, gdtype):
+    """Statistics only, up to 16 rows: vectors shorter than 2^21 coordinates are cut into 4096-coordinate tiles,
+    longer ones into 16384.  Both against the oracle (the second reached through the shard record), aligned and
+    misaligned with the same bits, and nothing but the result written."""
+    d = 3 * 16384 + 4096 + 3 * 512 + 7
+    wl = synth.make("t", J, d, gdtype=gdtype, sigma=1e-2, seed=70 + J, device=DEV, hyper=synth.Hyper(b_k=64, round_to=J, step=3))
+    state0 = (wl.w.clone(), wl.m.clone(), wl.v.clone())
+    g2, _ = shifted_copy(wl)
+    flags = B.NT_DO_STATS | B.NT_COORD_TEST
+    ref = H.oracle_full(wl.grads, d, J, wl.hyper)
+    counts = H.oracle_coord_counts(wl.grads, d, wl.hyper)
+    got = []
+    for shard in (None, part_of_long_vector(d)):
+        res = run(wl, flags, shard=shard)
+        H.assert_stats_close(res, ref)
+        H.assert_decision_matches(res, ref, wl.hyper)
+        H.assert_coord_matches(res, counts)
+        res2 = B.normtest_step(g2, None, None, None, hyper_of(wl.hyper, flags), d=d, shard=shard)
+        torch.cuda.synchronize()
+        assert B.read_result(res2).as_dict() == res
+        got.append(res)
+    for k in ("A", "B", "C", "T"):
+        assert got[0][k] == pytest.approx(got[1][k], rel=1e-13), k
+    for k in ("next_b", "pass", "status", "coord_fail", "coord_max_ratio"):
+        assert got[0][k] == got[1][k], k
+    for t, s0 in zip((wl.w, wl.m, wl.v), state0):
+        assert torch.equal(t, s0)
+
+
 def test_row_table_and_clipped_step_in_the_deferred_class():
     """Row pointers instead of a matrix, and the two-phase clipped step, both as parts of a long vector."""
     J, d = 8, 4 * TILE + 333
