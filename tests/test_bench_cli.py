@@ -101,3 +101,20 @@ def test_tracked_traffic_profile_is_well_formed():
         got = bench.traffic_from_profile(wl, mode)
         assert got == (float(entry["hbm_bytes_per_step"]) if current else None), key
         assert entry["hbm_bytes_per_step"] == entry["fetch_bytes"] + entry["write_bytes"]
+
+
+def test_row_sweep_workloads_are_parsed_on_the_host():
+    """rows:J:d is J bf16 rows with the headline's recipe, rows:J:d:f32 the same with fp32 rows; anything else in the
+    fourth field is refused."""
+    import pytest
+    import torch
+    sys.path.insert(0, ROOT)
+    import bench
+    wl = bench.make_workload("rows:12:5000", "cpu", 1.0)
+    assert (wl.name, wl.J, wl.d, wl.grads.dtype) == ("rows_J12", 12, 5000, torch.bfloat16)
+    wf = bench.make_workload("rows:12:5000:f32", "cpu", 1.0)
+    assert (wf.name, wf.J, wf.d, wf.grads.dtype) == ("rows_J12_f32", 12, 5000, torch.float32)
+    assert wf.hyper == wl.hyper
+    for bad in ("rows:12:5000:f16", "rows:12", "rows:12:5000:f32:x"):
+        with pytest.raises(SystemExit):
+            bench.make_workload(bad, "cpu", 1.0)
