@@ -187,12 +187,18 @@ def time_steps(wl, mode: str, steps: int, warmup: int, *, layers=0, graph=False,
         layer_off = torch.tensor(offs, dtype=torch.int64, device=dev)
         layer_out = torch.empty(len(sizes) * B.LAYER_BYTES, dtype=torch.uint8, device=dev)
 
+    # a shard of a longer vector says so (the library cuts it into tiles the way it would cut the whole vector)
+    shard = None
+    if "d_global" in wl.meta:
+        shard = B.nt_shard_info(wl.meta["shard_id"], wl.meta["num_shards"], wl.meta["shard_offset"], wl.meta["d_global"])
+
     def step():
         if mode == "clipped":
-            B.normtest_step_clipped(wl.grads, wl.w, wl.m, wl.v, gbar_buf, 1.0, hy, workspace=workspace,
+            B.normtest_step_clipped(wl.grads, wl.w, wl.m, wl.v, gbar_buf, 1.0, hy, shard=shard, workspace=workspace,
                                     result=result, stream=stream)
         else:
-            B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hy, workspace=workspace, result=result, stream=stream)
+            B.normtest_step(wl.grads, wl.w, wl.m, wl.v, hy, shard=shard, workspace=workspace, result=result,
+                            stream=stream)
         if layer_off is not None:
             B.normtest_layer_stats(wl.grads, layer_off, workspace, layers=layer_out, stream=stream)
 
