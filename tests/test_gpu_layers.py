@@ -35,9 +35,10 @@ def offsets_for(d, tile, rng, n_cuts=12):
     return off
 
 
-def run_layers(wl, flags, offsets, *, rows=False, clipped=False, coord=False):
+def run_layers(wl, flags, offsets, *, rows=False, clipped=False, coord=False, whole=None):
     h = wl.hyper
     d, J = wl.d, wl.J
+    shard = B.nt_shard_info(0, 1, 0, whole) if whole else None     # the step as a part of a vector of `whole`
     if coord:
         flags |= B.NT_COORD_TEST
     ws = torch.empty(B.normtest_workspace_bytes(J, d), dtype=torch.uint8, device=DEV)
@@ -45,15 +46,15 @@ def run_layers(wl, flags, offsets, *, rows=False, clipped=False, coord=False):
     hy = hyper_of(h, flags)
     if rows:
         rws = [wl.grads[j, :d].clone() for j in range(J)]
-        res = B.normtest_step_rows(rws, wl.w, wl.m, wl.v, hy, d=d, workspace=ws)
+        res = B.normtest_step_rows(rws, wl.w, wl.m, wl.v, hy, d=d, shard=shard, workspace=ws)
         lay = B.normtest_layer_stats(rws, off, ws, d=d)
     elif clipped:
         gbar = torch.empty(d, dtype=torch.float32, device=DEV)
-        res = B.normtest_step_clipped(wl.grads, wl.w, wl.m, wl.v, gbar, 1.0, hy, d=d, workspace=ws)
+        res = B.normtest_step_clipped(wl.grads, wl.w, wl.m, wl.v, gbar, 1.0, hy, d=d, shard=shard, workspace=ws)
         lay = B.normtest_layer_stats(wl.grads, off, ws, d=d)
     else:
         res = B.normtest_step(wl.grads, wl.w if flags & B.NT_DO_ADAMW else None, wl.m if flags & B.NT_DO_ADAMW else None,
-                              wl.v if flags & B.NT_DO_ADAMW else None, hy, d=d, workspace=ws)
+                              wl.v if flags & B.NT_DO_ADAMW else None, hy, d=d, shard=shard, workspace=ws)
         lay = B.normtest_layer_stats(wl.grads, off, ws, d=d)
     torch.cuda.synchronize()
     return B.read_result(res).as_dict(), [x.as_dict() for x in B.read_layers(lay)]
@@ -120,6 +121,30 @@ def test_layers_match_oracle(J, gdtype, d, mode):
     tile = {"full": 4096, "stats": 16384, "clipped": 4096, "rows": 4096}[mode] if J <= 16 else 2048
     offsets = [0] + offsets_for(d, tile, rng) + [d]
     res, layers = run_layers(wl, flags, offsets, rows=mode == "rows", clipped=mode == "clipped", coord=True)
+    check_layers(wl, res, layers, offsets, coord=True)
+
+
+LONG_CASES = [
+    # J, dtype, d, mode: with a shard record that names a vector of 2^26 coordinates these steps leave 8192-coordinate
+    # tiles (statistics only, up to 16 rows: 16384 instead of the 4096 of a short vector)
+    (16, torch.bfloat16, 5 * 8192 + 1237, "full"),
+    (14, torch.bfloat16, 5 * 8192 + 1237, "clipped"),
+    (8, torch.float32, 5 * 8192 + 1237, "rows"),
+    (8, torch.bfloat16, 5 * 16384 + 1237, "stats"),
+    (33, torch.bfloat16, 6 * 8192 + 77, "full"),
+    (20, torch.float32, 6 * 8192 + 77, "clipped"),
+]
+
+
+@pytest.mark.parametrize("J,gdtype,d,mode", LONG_CASES)
+def test_layers_after_a_step_in_the_long_vector_classes(J, gdtype, d, mode):
+    rng = np.random.default_rng(J * 1000 + d % 991)
+    wl = synth.make("layers", J, d, gdtype=gdtype, sigma=2e-2, seed=J + d % 11, device=DEV,
+                    hyper=synth.Hyper(b_k=64, round_to=J, step=4))
+    flags = B.NT_DO_STATS if mode == "stats" else FULL
+    tile = 16384 if mode == "stats" else 8192
+    offsets = [0] + offsets_for(d, tile, rng) + [d]
+    res, layers = run_layers(wl, flags, offsets, rows=mode == "rows", clipped=mode == "clipped", coord=True, whole=1 << 26)
     check_layers(wl, res, layers, offsets, coord=True)
 
 
