@@ -18,21 +18,23 @@ def hyper_of(h, flags):
                         step=h.step, b_k=h.b_k, b_max=h.b_max, round_to=h.round_to, ddof=h.ddof, flags=flags)
 
 
-def run_both(J, d, gdtype, seed, flags):
+def run_both(J, d, gdtype, seed, flags, whole=None):
     dev = "cuda:0"
+    shard = B.nt_shard_info(0, 1, 0, whole) if whole else None    # the call as a part of a vector of `whole` coordinates
     wl = synth.make("noalloc", J, d, gdtype=gdtype, sigma=1e-2, seed=seed, device=dev,
                     hyper=synth.Hyper(b_k=256, round_to=128, b_max=8192, step=10))
     hy = hyper_of(wl.hyper, flags)
     state = [t.clone() for t in (wl.w, wl.m, wl.v)]
     ref_state = [t.clone() for t in (wl.w, wl.m, wl.v)]
-    ref = B.read_result(B.normtest_step(wl.grads, *ref_state, hy))
+    ref = B.read_result(B.normtest_step(wl.grads, *ref_state, hy, shard=shard))
     # raw call through the C ABI: no workspace argument, caller-owned result
     result = torch.zeros(B.RESULT_BYTES, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
     J_, ld = wl.grads.shape[0], wl.grads.stride(0)
     rc = B.lib().normtest_step_static(ctypes.c_void_p(wl.grads.data_ptr()), B._gdtype(wl.grads), J_, d, ld,
                                       ctypes.c_void_p(state[0].data_ptr()), ctypes.c_void_p(state[1].data_ptr()),
-                                      ctypes.c_void_p(state[2].data_ptr()), None, ctypes.byref(hy), None,
+                                      ctypes.c_void_p(state[2].data_ptr()), None, ctypes.byref(hy),
+                                      ctypes.byref(shard) if shard is not None else None,
                                       ctypes.c_void_p(result.data_ptr()), ctypes.c_void_p(stream.cuda_stream))
     assert rc == B.NT_OK, B.normtest_strerror(rc)
     got = B.read_result(result)
@@ -57,6 +59,10 @@ def test_static_scratch_matches_workspace_entry_point_on_calls_in_a_row():
     run_both(40, 3 * tc + 12, torch.bfloat16, 4, B.NT_DO_STATS)
     print("call 5: J=128 bf16 (many rows: the state update deferred to the end of each block's walk)", flush=True)
     run_both(128, 2 * tc + 8, torch.bfloat16, 5, full)
+    print("calls 6-8: parts of a vector of 2^26 coordinates (the launch classes for long vectors): 16 bf16, 8 fp32, 24 bf16 rows", flush=True)
+    run_both(16, 3 * tc + 99, torch.bfloat16, 6, full, whole=1 << 26)
+    run_both(8, 2 * tc + 5, torch.float32, 7, full | B.NT_COORD_TEST, whole=1 << 26)
+    run_both(24, 2 * tc + 77, torch.bfloat16, 8, full, whole=1 << 26)
 
 
 def test_static_entry_point_rejects_what_does_not_fit():
